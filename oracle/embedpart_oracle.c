@@ -1,0 +1,318 @@
+/*
+ * EmbedPart phase-2 oracle: a plain, slow, fp64 CPU statement of what the
+ * clustering hot path computes.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may load it.  It shares no code, header,
+ * table or helper with the HIP library and neither side includes the other.
+ *
+ * What it follows (EmbedPart paper):
+ *   - Alg. 3, first step  P <- KMeans(E, k): cluster one dense embedding per
+ *     vertex into exactly k groups; the clusters are the partitions
+ *     (Sec. "Phase 2: Clustering and Balancing").
+ *   - Sec. "Partitioning quality metrics": an edge (u,v) is cut iff
+ *     pid(u) != pid(v); ECR = |C|/|E|; vertex balance = max|P_i| / mean|P_i|.
+ *   - Sec. "Extension to Graph Reordering": gap xi_pi(u,v) = |pi(u)-pi(v)|,
+ *     vertex bandwidth = max gap over a vertex's neighbours, average graph
+ *     bandwidth = its mean over vertices; the reordering gives vertices of
+ *     one partition consecutive ids.
+ *
+ * The paper names K-Means but none of its details.  The readings taken here
+ * (squared Euclidean distance in its direct form, lowest index wins ties, an
+ * empty cluster keeps its previous centroid, Lloyd iterations over all points
+ * from k distinct seeded rows) are listed in the design notes of this
+ * repository; each function below says which reading it implements.
+ *
+ * Pins (tests marked "not gpu"): brute force on integer coordinates, a
+ * hand-worked 1-D Lloyd run, k = 1 and k = N special cases, separated blobs,
+ * translation / permutation equivariance, monotone objective, mean property,
+ * closed-form cuts on paths / cycles / complete graphs / matchings,
+ * adjacency-matrix brute force, balance extremes, permutation bijectivity.
+ * Numerical parity with figures printed in the paper is unpinned: every such
+ * figure depends on datasets and trained weights that are not available.
+ *
+ * Arithmetic: fp64 throughout; inputs arrive as the exact fp32 values the
+ * device sees (bf16 inputs are widened to fp32 by the caller, which is exact).
+ * Sums run in index order.  The only parallel loop is the per-point search of
+ * the assignment step, whose iterations are independent.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define OR_FLAG_FINAL_REASSIGN 1
+#define OR_FLAG_BF16_CENTROIDS 2
+
+int or_version(void) { return 1; }
+
+/* ---- seeded choice of k distinct rows -------------------------------- */
+
+/* splitmix64 (Steele, Lea, Flood 2014; Vigna's public-domain constants). */
+static uint64_t splitmix64_next(uint64_t *state)
+{
+    uint64_t z = (*state += 0x9E3779B97F4A7C15ULL);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/*
+ * Initial centroids are k distinct rows.  Reading: distinct row indices,
+ * drawn as (splitmix64 output mod n) from a stream started at `seed`,
+ * repeats rejected, draw order kept as centroid order.
+ * Returns 0, or -1 when k > n or an argument is out of range.
+ */
+int or_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx)
+{
+    if (n < 1 || k < 1 || (int64_t)k > n || !idx) return -1;
+    uint64_t state = seed;
+    int32_t have = 0;
+    while (have < k) {
+        int64_t r = (int64_t)(splitmix64_next(&state) % (uint64_t)n);
+        int seen = 0;
+        for (int32_t j = 0; j < have; ++j)
+            if (idx[j] == r) { seen = 1; break; }
+        if (!seen) idx[have++] = r;
+    }
+    return 0;
+}
+
+/* ---- bf16 rounding of a centroid coordinate --------------------------- */
+
+/*
+ * Round to bfloat16 (8 exponent bits, 7 stored mantissa bits), nearest-even,
+ * in the precision path the device uses: the fp64 master value is first
+ * rounded to fp32 (the device's master copy), then the fp32 value to bf16.
+ * NaN/Inf do not occur for finite centroids of finite data.
+ */
+double or_round_bf16(double v)
+{
+    float f = (float)v;                 /* fp64 -> fp32, nearest-even */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t lsb = (u >> 16) & 1u;      /* last kept bit */
+    u += 0x7FFFu + lsb;                 /* nearest, ties to even */
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* ---- assignment step --------------------------------------------------- */
+
+/*
+ * For every point i: squared Euclidean distance to every centroid in the
+ * direct form sum_m (x_im - c_jm)^2, m ascending; the label is the first j
+ * that attains the minimum (strict < while j ascends).  best[i] is that
+ * minimum, second[i] the second-smallest distance (HUGE_VAL when k == 1);
+ * both may be NULL.  With round_bf16 != 0 the centroids used for distances
+ * are the bf16-rounded copies, C itself is not modified.
+ * Returns the objective sum_i best[i], added in index order.
+ */
+double or_assign(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
+                 const double *C, int round_bf16,
+                 int32_t *labels, double *best, double *second)
+{
+    double *Cq = (double *)malloc((size_t)k * d * sizeof(double));
+    double *b = best ? best : (double *)malloc((size_t)n * sizeof(double));
+    for (int64_t t = 0; t < (int64_t)k * d; ++t)
+        Cq[t] = round_bf16 ? or_round_bf16(C[t]) : C[t];
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float *x = X + i * ld;
+        double dmin = HUGE_VAL, dsec = HUGE_VAL;
+        int32_t jmin = 0;
+        for (int32_t j = 0; j < k; ++j) {
+            const double *c = Cq + (int64_t)j * d;
+            double d2 = 0.0;
+            for (int32_t m = 0; m < d; ++m) {
+                double diff = (double)x[m] - c[m];
+                d2 += diff * diff;
+            }
+            if (d2 < dmin) { dsec = dmin; dmin = d2; jmin = j; }
+            else if (d2 < dsec) { dsec = d2; }
+        }
+        labels[i] = jmin;
+        b[i] = dmin;
+        if (second) second[i] = dsec;
+    }
+
+    double obj = 0.0;
+    for (int64_t i = 0; i < n; ++i) obj += b[i];
+    if (!best) free(b);
+    free(Cq);
+    return obj;
+}
+
+/* ---- update step --------------------------------------------------------- */
+
+/*
+ * c_j <- mean of the points labelled j (sums in index order); a cluster with
+ * no points keeps its previous centroid and gets count 0.  C is updated in
+ * place.  Returns the number of empty clusters.
+ */
+int32_t or_update(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
+                  const int32_t *labels, double *C, int64_t *counts)
+{
+    double *sum = (double *)calloc((size_t)k * d, sizeof(double));
+    for (int32_t j = 0; j < k; ++j) counts[j] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float *x = X + i * ld;
+        double *s = sum + (int64_t)labels[i] * d;
+        for (int32_t m = 0; m < d; ++m) s[m] += (double)x[m];
+        counts[labels[i]] += 1;
+    }
+    int32_t empty = 0;
+    for (int32_t j = 0; j < k; ++j) {
+        if (counts[j] == 0) { ++empty; continue; }
+        for (int32_t m = 0; m < d; ++m)
+            C[(int64_t)j * d + m] = sum[(int64_t)j * d + m] / (double)counts[j];
+    }
+    free(sum);
+    return empty;
+}
+
+/* ---- Lloyd iterations ---------------------------------------------------- */
+
+/*
+ * KMeans(E, k) of Alg. 3 read as `iters` Lloyd rounds (assign, then update)
+ * from the rows idx[0..k) as initial centroids.
+ *   labels  : labels of the last assignment step run
+ *   C       : k x d centroids, means of the labels of the iters-th assignment
+ *   counts  : sizes of those clusters
+ *   obj_hist: objective of each of the `iters` assignment steps (may be NULL)
+ * OR_FLAG_FINAL_REASSIGN: one more assignment against the final C; labels
+ *   then hold that assignment, and *obj_final its objective.  counts and C
+ *   still describe the iters-th round.
+ * OR_FLAG_BF16_CENTROIDS: distances use bf16-rounded centroids.
+ */
+int or_lloyd(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
+             int32_t iters, const int64_t *idx, int flags,
+             double *C, int32_t *labels, int64_t *counts,
+             double *obj_hist, double *obj_final)
+{
+    if (n < 1 || d < 1 || k < 1 || (int64_t)k > n || ld < d || iters < 0) return -1;
+    for (int32_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || idx[j] >= n) return -1;
+        for (int32_t m = 0; m < d; ++m)
+            C[(int64_t)j * d + m] = (double)X[idx[j] * ld + m];
+    }
+    int q = (flags & OR_FLAG_BF16_CENTROIDS) ? 1 : 0;
+    for (int32_t t = 0; t < iters; ++t) {
+        double obj = or_assign(n, d, k, X, ld, C, q, labels, NULL, NULL);
+        if (obj_hist) obj_hist[t] = obj;
+        or_update(n, d, k, X, ld, labels, C, counts);
+    }
+    if (flags & OR_FLAG_FINAL_REASSIGN) {
+        double obj = or_assign(n, d, k, X, ld, C, q, labels, NULL, NULL);
+        if (obj_final) *obj_final = obj;
+    }
+    return 0;
+}
+
+/* ---- partition quality over a CSR graph ---------------------------------- */
+
+/*
+ * cut   = number of stored CSR entries (u,v) with pid(u) != pid(v)
+ *         (an undirected edge stored in both directions counts twice, so
+ *         cut / nnz is the edge-cut ratio either way);
+ * sizes = |P_p| for p in [0,k).
+ * Returns 0, or -1 if a label or a column index is out of range.
+ */
+int or_partition_quality(int64_t n, int32_t k, const int64_t *rowptr,
+                         const int32_t *colidx, const int32_t *labels,
+                         int64_t *cut, int64_t *sizes)
+{
+    for (int32_t p = 0; p < k; ++p) sizes[p] = 0;
+    int64_t c = 0;
+    for (int64_t u = 0; u < n; ++u) {
+        if (labels[u] < 0 || labels[u] >= k) return -1;
+        sizes[labels[u]] += 1;
+        for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+            int32_t v = colidx[e];
+            if (v < 0 || v >= n) return -1;
+            if (labels[u] != labels[v]) ++c;
+        }
+    }
+    *cut = c;
+    return 0;
+}
+
+/* ECR = |C| / |E| and vertex balance = max / mean of the partition sizes. */
+double or_edge_cut_ratio(int64_t cut, int64_t nnz)
+{
+    return nnz > 0 ? (double)cut / (double)nnz : 0.0;
+}
+
+double or_vertex_balance(int32_t k, const int64_t *sizes)
+{
+    int64_t mx = 0, total = 0;
+    for (int32_t p = 0; p < k; ++p) {
+        total += sizes[p];
+        if (sizes[p] > mx) mx = sizes[p];
+    }
+    return (double)mx / ((double)total / (double)k);
+}
+
+/* ---- reordering ------------------------------------------------------------ */
+
+/*
+ * Vertices of one partition get consecutive new ids.  Reading that makes the
+ * result unique: partitions in increasing id, vertices inside a partition in
+ * increasing original id.  new_id[v] = pi(v); order[pi(v)] = v.
+ */
+int or_permutation(int64_t n, int32_t k, const int32_t *labels,
+                   int32_t *new_id, int32_t *order)
+{
+    int64_t *next = (int64_t *)calloc((size_t)k + 1, sizeof(int64_t));
+    for (int64_t v = 0; v < n; ++v) {
+        if (labels[v] < 0 || labels[v] >= k) { free(next); return -1; }
+        next[labels[v] + 1] += 1;
+    }
+    for (int32_t p = 0; p < k; ++p) next[p + 1] += next[p];  /* next[p] = first id of p */
+    for (int64_t v = 0; v < n; ++v) {
+        int64_t id = next[labels[v]]++;
+        new_id[v] = (int32_t)id;
+        order[id] = (int32_t)v;
+    }
+    free(next);
+    return 0;
+}
+
+/* Sum over stored CSR entries of |pi(u) - pi(v)|; pi = identity when NULL. */
+uint64_t or_edge_gap_sum(int64_t n, const int64_t *rowptr, const int32_t *colidx,
+                         const int32_t *new_id)
+{
+    uint64_t total = 0;
+    for (int64_t u = 0; u < n; ++u) {
+        int64_t pu = new_id ? new_id[u] : u;
+        for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+            int64_t pv = new_id ? new_id[colidx[e]] : colidx[e];
+            total += (uint64_t)(pu > pv ? pu - pv : pv - pu);
+        }
+    }
+    return total;
+}
+
+/*
+ * Sum over vertices of the vertex bandwidth max_{u in N(v)} |pi(v) - pi(u)|
+ * (0 for an isolated vertex); divided by |V| it is the average graph
+ * bandwidth.
+ */
+uint64_t or_vertex_bandwidth_sum(int64_t n, const int64_t *rowptr, const int32_t *colidx,
+                                 const int32_t *new_id)
+{
+    uint64_t total = 0;
+    for (int64_t u = 0; u < n; ++u) {
+        int64_t pu = new_id ? new_id[u] : u;
+        int64_t widest = 0;
+        for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+            int64_t pv = new_id ? new_id[colidx[e]] : colidx[e];
+            int64_t gap = pu > pv ? pu - pv : pv - pu;
+            if (gap > widest) widest = gap;
+        }
+        total += (uint64_t)widest;
+    }
+    return total;
+}
