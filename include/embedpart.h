@@ -1,0 +1,191 @@
+/*
+ * embedpart.h -- C ABI of the MI355X (gfx950) clustering hot path of EmbedPart.
+ *
+ * The library implements the dense, data-parallel part of the paper's Phase 2
+ * (Alg. 3, first step: P <- KMeans(E, k); Sec. "Phase 2: Clustering and
+ * Balancing": one embedding per vertex is clustered into exactly k groups and
+ * the clusters are the graph partitions), the integer evaluation of the
+ * resulting partition (Sec. "Partitioning quality metrics": cut edges and
+ * partition sizes, from which ECR = |C|/|E| and the vertex balance follow) and
+ * the relabelling used for graph reordering (Sec. "Adapting EmbedPart for
+ * Reordering": vertices of one partition get consecutive ids; Eq. gap:
+ * xi_pi(u,v) = |pi(u) - pi(v)|).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in `_host`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; no call synchronises, so outputs are valid
+ *     once the caller has synchronised the stream.
+ *   - The caller owns every buffer, including the workspace `ws`, which must be
+ *     256-byte aligned and at least as large as the matching *_workspace_bytes
+ *     call reports.  The library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns.  Its only global state is the code of the
+ *     last failing HIP call (ep_last_hip_error).
+ *   - Partition / cluster ids are 0-based, in [0, k).  (The paper numbers
+ *     partitions 1..k.)
+ *   - Return value: EP_OK (0) or a negative EP_E* code.  Arguments are checked
+ *     on the host before any HIP call is made; no exception crosses the ABI.
+ *   - Results are bit-reproducible from run to run: no floating-point atomics
+ *     are used and every reduction has a fixed order.
+ */
+#ifndef EMBEDPART_H
+#define EMBEDPART_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EP_OK            0
+#define EP_EINVAL       (-1)  /* null pointer, size out of range, k > n, ld < d, misaligned buffer */
+#define EP_EUNSUPPORTED (-2)  /* shape or dtype no kernel of this build covers */
+#define EP_EWORKSPACE   (-3)  /* workspace missing, misaligned or too small */
+#define EP_EHIP         (-4)  /* a HIP runtime call failed: see ep_last_hip_error() */
+
+#define EP_F32  0             /* embeddings stored as IEEE binary32 */
+#define EP_BF16 1             /* embeddings stored as bfloat16; all accumulation is fp32 or wider */
+
+/* kmeans_run flags */
+#define EP_RUN_FINAL_REASSIGN 1  /* one more assignment against the final centroids */
+
+/* Limits of this build. */
+#define EP_MAX_D          1024
+#define EP_MAX_K          65536
+#define EP_MAX_N          ((int64_t)1 << 31)   /* vertex ids and labels are int32; n < 2^31 */
+
+/* The clustering problem: n embeddings of dimension d, row-major with row
+ * stride ld (elements, ld >= d), to be grouped into k clusters.
+ * For EP_BF16, X must be 4-byte aligned and ld even; for EP_F32, X must be
+ * 16-byte aligned and ld a multiple of 4. */
+typedef struct ep_problem {
+    int64_t n;
+    int64_t ld;
+    int32_t d;
+    int32_t k;
+    int32_t dtype;     /* EP_F32 or EP_BF16 */
+    int32_t reserved;  /* must be 0 */
+} ep_problem;
+
+/* Library version (major * 100 + minor). */
+int ep_version(void);
+
+/* Static, human-readable text for a return code. */
+const char *ep_strerror(int code);
+
+/* hipError_t value of the most recent failing HIP call of this process (0 if none). */
+int ep_last_hip_error(void);
+
+/*
+ * Seeded choice of the k initial rows.  The paper leaves K-Means'
+ * initialisation open; here the initial centroids are k distinct rows:
+ * a splitmix64 stream started at `seed` is reduced mod n, repeats are
+ * rejected and the draw order is the centroid order.
+ * idx_host: k entries, host memory, written.   Host-only, no HIP call.
+ */
+int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host);
+
+/* Bytes of workspace that kmeans_init / assign / update / run need for `p`. */
+int kmeans_workspace_bytes(const ep_problem *p, size_t *bytes_host);
+
+/*
+ * Initial centroids: C[j, :] = X[idx_host[j], :] widened to fp32.
+ * idx_host: k row indices in [0, n) on the host (copied during the call).
+ * C: k x d fp32, dense (row stride d), written.
+ */
+int kmeans_init(const ep_problem *p, const void *X, const int64_t *idx_host,
+                float *C, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Assignment step of K-Means: labels[i] = argmin_j ||x_i - c_j||^2 (squared
+ * Euclidean; the lowest j wins an exact tie), evaluated as
+ * ||c_j||^2 - 2 x_i.c_j in fp32.  With EP_BF16 the centroids are rounded to
+ * bf16 (nearest-even) for the x.c products, which accumulate in fp32.
+ *   C         k x d fp32, read
+ *   labels    n int32, written
+ *   min_d2    n fp32 or NULL: ||x_i - c_label||^2 (clamped at 0), written
+ *   objective 1 double or NULL: sum_i ||x_i - c_label||^2, written (not added to)
+ */
+int kmeans_assign(const ep_problem *p, const void *X, const float *C,
+                  int32_t *labels, float *min_d2, double *objective,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Update step of K-Means: C_out[j] = mean of the rows labelled j; a cluster
+ * without rows keeps C_prev[j] and gets count 0.  Sums are fp32 over bounded
+ * runs of rows, combined in fp64 in a fixed order.
+ *   labels  n int32 in [0, k), read (a label outside the range is undefined behaviour
+ *           in the sense of a wrong result, never of an out-of-bounds access: such
+ *           rows are skipped)
+ *   C_prev  k x d fp32, read;  C_out k x d fp32, written (may alias C_prev)
+ *   counts  k int64, written
+ */
+int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels,
+                  const float *C_prev, float *C_out, int64_t *counts,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * `iters` Lloyd rounds (assign, then update) starting from the centroids in C.
+ *   C               k x d fp32: initial centroids in, final centroids out
+ *   labels          n int32, written: the labels of the last assignment performed
+ *   counts          k int64, written: cluster sizes of round `iters`, of which C holds the means
+ *   objective_hist  iters + 1 doubles or NULL: [t] = objective of round t's assignment;
+ *                   [iters] is written only with EP_RUN_FINAL_REASSIGN
+ * Without the flag, C is exactly the mean of the rows carrying each returned label.
+ * With it, labels come from one further assignment against the final C
+ * (train-then-assign use); counts and C still describe round `iters`.
+ * iters may be 0 (then only the optional final assignment runs).
+ */
+int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
+               int32_t *labels, int64_t *counts, double *objective_hist, int flags,
+               void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of workspace that the graph calls below need. */
+int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host);
+
+/*
+ * Quality of a partition over a CSR graph, in integers.
+ *   rowptr   n + 1 offsets, int32 or int64 (rowptr_is_i64), rowptr[n] == nnz
+ *   colidx   nnz int32 column indices in [0, n)
+ *   labels   n int32 partition ids in [0, k)
+ *   cut      1 int64, written: stored entries (u,v) with labels[u] != labels[v]
+ *            (an undirected edge stored in both directions counts twice; divide
+ *            by nnz for the edge-cut ratio)
+ *   sizes    k int64, written: vertices per partition (max * k / n is the vertex balance)
+ * Entries whose column index or whose labels fall outside their range are skipped.
+ */
+int partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, int rowptr_is_i64,
+                      const int32_t *colidx, const int32_t *labels,
+                      int64_t *cut, int64_t *sizes, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Reordering: vertices of one partition get consecutive ids; partitions in
+ * increasing id, vertices inside a partition in increasing original id.
+ *   new_id  n int32, written: pi(v)
+ *   order   n int32, written: order[pi(v)] = v
+ */
+int partition_permutation(int64_t n, int32_t k, const int32_t *labels,
+                          int32_t *new_id, int32_t *order, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Sum over stored CSR entries (u,v) of the gap |pi(u) - pi(v)|; new_id == NULL
+ * means the identity.  gap_sum: 1 uint64, written.  Divide by nnz for the mean gap.
+ */
+int edge_gap_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
+                 const int32_t *colidx, const int32_t *new_id,
+                 uint64_t *gap_sum, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Sum over vertices of the vertex bandwidth max_{u in N(v)} |pi(v) - pi(u)|
+ * (0 for a vertex without neighbours); divided by n it is the average graph
+ * bandwidth of the paper's reordering evaluation.  bw_sum: 1 uint64, written.
+ */
+int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
+                         const int32_t *colidx, const int32_t *new_id,
+                         uint64_t *bw_sum, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMBEDPART_H */

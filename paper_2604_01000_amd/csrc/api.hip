@@ -1,0 +1,212 @@
+// C-ABI entry points of libembedpart: argument checks on the host, then kernel launches.
+// See include/embedpart.h for the contract of every call.
+#include <atomic>
+
+#include "kernels.h"
+
+namespace ep {
+
+static std::atomic<int> g_last_hip_error{0};
+void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_problem(const ep_problem *p) {
+    if (!p) return EP_EINVAL;
+    if (p->n < 1 || p->n >= EP_MAX_N || p->d < 1 || p->k < 1 || (int64_t)p->k > p->n || p->ld < p->d) return EP_EINVAL;
+    if (p->reserved != 0) return EP_EINVAL;
+    if (p->dtype != EP_F32 && p->dtype != EP_BF16) return EP_EUNSUPPORTED;
+    if (p->d > EP_MAX_D || p->k > EP_MAX_K) return EP_EUNSUPPORTED;
+    if (p->ld % (p->dtype == EP_F32 ? 4 : 8) != 0) return EP_EINVAL;
+    return EP_OK;
+}
+
+int check_x(const ep_problem *p, const void *X) {
+    if (!X || !aligned(X, 16)) return EP_EINVAL;
+    (void)p;
+    return EP_OK;
+}
+
+int check_ws(const void *ws, size_t have, size_t need) {
+    if (!ws || !aligned(ws, 256) || have < need) return EP_EWORKSPACE;
+    return EP_OK;
+}
+
+uint64_t splitmix64(uint64_t &state) {
+    uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+bool small_k(const ep_problem &p) { return (int64_t)p.k * p.d <= kSmallKElems; }
+
+int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+              float *min_d2, double *objective, hipStream_t s) {
+    int rc = launch_prep_centroids(p, C, w, s);
+    if (rc != EP_OK) return rc;
+    return launch_assign_generic(p, X, C, w, labels, min_d2, objective, s);
+}
+
+int do_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
+              int64_t *counts, const KmeansWs &w, hipStream_t s) {
+    return small_k(p) ? launch_update_small(p, X, labels, C_prev, C_out, counts, w, s)
+                      : launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, s);
+}
+
+int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colidx) {
+    if (n < 1 || n >= EP_MAX_N || nnz < 0 || !rowptr || (nnz > 0 && !colidx)) return EP_EINVAL;
+    if (!aligned(rowptr, 8) || !aligned(colidx, 4)) return EP_EINVAL;
+    return EP_OK;
+}
+
+}  // namespace
+}  // namespace ep
+
+using namespace ep;
+
+extern "C" {
+
+int ep_version(void) { return 100; }
+
+const char *ep_strerror(int code) {
+    switch (code) {
+        case EP_OK: return "ok";
+        case EP_EINVAL: return "invalid argument (null pointer, size out of range, k > n, ld < d or misaligned buffer)";
+        case EP_EUNSUPPORTED: return "shape or dtype not supported by this build";
+        case EP_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case EP_EHIP: return "a HIP runtime call failed (see ep_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+int ep_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host) {
+    if (!idx_host || n < 1 || k < 1 || (int64_t)k > n) return EP_EINVAL;
+    uint64_t state = seed;
+    int32_t have = 0;
+    while (have < k) {
+        const int64_t r = (int64_t)(splitmix64(state) % (uint64_t)n);
+        bool seen = false;
+        for (int32_t j = 0; j < have && !seen; ++j) seen = idx_host[j] == r;
+        if (!seen) idx_host[have++] = r;
+    }
+    return EP_OK;
+}
+
+int kmeans_workspace_bytes(const ep_problem *p, size_t *bytes_host) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!bytes_host) return EP_EINVAL;
+    *bytes_host = carve_kmeans_ws(*p, nullptr).bytes;
+    return EP_OK;
+}
+
+int kmeans_init(const ep_problem *p, const void *X, const int64_t *idx_host, float *C, void *ws, size_t ws_bytes,
+                void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!idx_host || !C) return EP_EINVAL;
+    for (int32_t j = 0; j < p->k; ++j)
+        if (idx_host[j] < 0 || idx_host[j] >= p->n) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
+    const KmeansWs w = carve_kmeans_ws(*p, ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    EP_HIP_TRY(hipMemcpyAsync(w.idx, idx_host, sizeof(int64_t) * p->k, hipMemcpyHostToDevice, s));
+    return launch_gather_rows(*p, X, w.idx, C, s);
+}
+
+int kmeans_assign(const ep_problem *p, const void *X, const float *C, int32_t *labels, float *min_d2,
+                  double *objective, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!C || !labels) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
+    return do_assign(*p, X, C, carve_kmeans_ws(*p, ws), labels, min_d2, objective, static_cast<hipStream_t>(stream));
+}
+
+int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
+                  int64_t *counts, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!labels || !C_prev || !C_out || !counts) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
+    return do_update(*p, X, labels, C_prev, C_out, counts, carve_kmeans_ws(*p, ws), static_cast<hipStream_t>(stream));
+}
+
+int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
+               double *objective_hist, int flags, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!C || !labels || !counts || iters < 0 || (flags & ~EP_RUN_FINAL_REASSIGN)) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
+    const KmeansWs w = carve_kmeans_ws(*p, ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int32_t t = 0; t < iters; ++t) {
+        if ((rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + t : nullptr, s)) != EP_OK)
+            return rc;
+        if ((rc = do_update(*p, X, labels, C, C, counts, w, s)) != EP_OK) return rc;
+    }
+    if (flags & EP_RUN_FINAL_REASSIGN)
+        rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+    return rc;
+}
+
+int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host) {
+    if (n < 1 || n >= EP_MAX_N || nnz < 0 || k < 1 || !bytes_host) return EP_EINVAL;
+    if (k > EP_MAX_K) return EP_EUNSUPPORTED;
+    *bytes_host = carve_graph_ws(n, nnz, k, nullptr).bytes;
+    return EP_OK;
+}
+
+int partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
+                      const int32_t *labels, int64_t *cut, int64_t *sizes, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_graph(n, nnz, rowptr, colidx);
+    if (rc != EP_OK) return rc;
+    if (k < 1 || !labels || !cut || !sizes) return EP_EINVAL;
+    if (k > EP_MAX_K) return EP_EUNSUPPORTED;
+    if ((rc = check_ws(ws, ws_bytes, carve_graph_ws(n, nnz, k, nullptr).bytes)) != EP_OK) return rc;
+    return launch_partition_quality(n, nnz, k, rowptr, rowptr_is_i64 != 0, colidx, labels, cut, sizes,
+                                    carve_graph_ws(n, nnz, k, ws), static_cast<hipStream_t>(stream));
+}
+
+int partition_permutation(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order, void *ws,
+                          size_t ws_bytes, void *stream) {
+    if (n < 1 || n >= EP_MAX_N || k < 1 || !labels || !new_id || !order) return EP_EINVAL;
+    if (k > EP_MAX_K) return EP_EUNSUPPORTED;
+    int rc = check_ws(ws, ws_bytes, carve_graph_ws(n, 0, k, nullptr).bytes);
+    if (rc != EP_OK) return rc;
+    const GraphWs w = carve_graph_ws(n, 0, k, ws);
+    return launch_sort_by_label(n, k, labels, new_id, order, w.order_tmp, w.sort_hist,
+                                static_cast<hipStream_t>(stream));
+}
+
+static int gap_call(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
+                    const int32_t *new_id, uint64_t *out, EdgeReduce what, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_graph(n, nnz, rowptr, colidx);
+    if (rc != EP_OK) return rc;
+    if (!out) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_graph_ws(n, nnz, 1, nullptr).bytes)) != EP_OK) return rc;
+    return launch_edge_gap(n, nnz, rowptr, rowptr_is_i64 != 0, colidx, new_id, out, what,
+                           carve_graph_ws(n, nnz, 1, ws), static_cast<hipStream_t>(stream));
+}
+
+int edge_gap_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
+                 const int32_t *new_id, uint64_t *gap_sum, void *ws, size_t ws_bytes, void *stream) {
+    return gap_call(n, nnz, rowptr, rowptr_is_i64, colidx, new_id, gap_sum, EdgeReduce::GapSum, ws, ws_bytes, stream);
+}
+
+int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
+                         const int32_t *new_id, uint64_t *bw_sum, void *ws, size_t ws_bytes, void *stream) {
+    return gap_call(n, nnz, rowptr, rowptr_is_i64, colidx, new_id, bw_sum, EdgeReduce::BandwidthSum, ws, ws_bytes,
+                    stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal helpers shared by the HIP translation units of libembedpart (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/embedpart.h"
+
+namespace ep {
+
+// Records the failing hipError_t for ep_last_hip_error().
+void note_hip_error(hipError_t e);
+
+#define EP_HIP_TRY(expr)                                  \
+    do {                                                  \
+        hipError_t _e = (expr);                           \
+        if (_e != hipSuccess) {                           \
+            ::ep::note_hip_error(_e);                     \
+            return EP_EHIP;                               \
+        }                                                 \
+    } while (0)
+
+#define EP_LAUNCH_CHECK() EP_HIP_TRY(hipGetLastError())
+
+constexpr int kWave = 64;
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- workspace carving ------------------------------------------------------
+struct Carver {
+    char *base;
+    size_t used;
+    explicit Carver(void *p) : base(static_cast<char *>(p)), used(0) {}
+    template <typename T> T *take(size_t count) {
+        used = align_up(used, 256);
+        T *r = base ? reinterpret_cast<T *>(base + used) : nullptr;
+        used += count * sizeof(T);
+        return r;
+    }
+};
+
+// ---- device helpers -----------------------------------------------------------
+typedef uint16_t bf16_t;  // storage type of bfloat16
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(static_cast<uint32_t>(v) << 16); }
+
+// fp32 -> bf16, round to nearest, ties to even (finite inputs).
+__device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<bf16_t>(u >> 16);
+}
+
+__device__ __forceinline__ float load_elem(const float *p) { return *p; }
+__device__ __forceinline__ float load_elem(const bf16_t *p) { return bf16_to_f32(*p); }
+
+// Four consecutive elements starting at a 4-element-aligned column.
+__device__ __forceinline__ float4 load4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 load4(const bf16_t *p) {
+    uint2 r = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+}
+
+}  // namespace ep

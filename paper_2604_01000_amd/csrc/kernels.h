@@ -1,0 +1,60 @@
+// Host-side launchers of the HIP kernels; each enqueues on `s` and returns an EP_* code.
+#pragma once
+
+#include "common.h"
+
+namespace ep {
+
+// ---- K-Means, shape-generic kernels (kmeans_generic.hip) ----------------------
+constexpr int kObjBlocksMax = 2048;   // partial objectives per assignment launch
+constexpr int kUpdBlocksMax = 1024;   // partial sums per small-k update launch
+constexpr int kSmallKElems = 8192;    // k*d at or below this: per-workgroup LDS partial sums
+
+struct KmeansWs {
+    double *obj_part;     // [kObjBlocksMax]
+    float *cnorm;         // [k]   ||c_j||^2 of the centroids the distances use
+    float *cq;            // [k*d] bf16-rounded centroids as fp32 (EP_BF16 only, else unused)
+    bf16_t *cq16;         // [k*d] the same as bf16 (EP_BF16 only)
+    float *psum;          // [kUpdBlocksMax * k * d]   (small k)
+    int32_t *pcnt;        // [kUpdBlocksMax * k]       (small k)
+    int64_t *idx;         // [k] init row indices
+    int32_t *order;       // [n]  rows sorted by label           (large k)
+    int32_t *order_tmp;   // [n]
+    int64_t *seg;         // [k+1] segment offsets               (large k)
+    int32_t *sort_hist;   // radix-sort block histograms
+    size_t bytes;
+};
+KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws);
+
+int launch_gather_rows(const ep_problem &p, const void *X, const int64_t *idx_dev, float *C, hipStream_t s);
+int launch_prep_centroids(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s);
+int launch_assign_generic(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                          float *min_d2, double *objective, hipStream_t s);
+int launch_update_small(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
+                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
+                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+
+// ---- graph kernels (graph.hip) ---------------------------------------------------
+constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass
+struct GraphWs {
+    int64_t *partial;     // [kGraphBlocksMax] per-workgroup partial counts / sums
+    int32_t *sort_hist;   // [kSortBlocksMax * 256]
+    int32_t *order_tmp;   // [n]
+    int32_t *order_tmp2;  // [n]
+    size_t bytes;
+};
+constexpr int kGraphBlocksMax = 8192;
+GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws);
+size_t sort_hist_elems();
+
+int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, bool i64, const int32_t *colidx,
+                             const int32_t *labels, int64_t *cut, int64_t *sizes, const GraphWs &w, hipStream_t s);
+// Stable sort of vertex ids by label: order (sorted position -> vertex) and, if non-null, new_id (its inverse).
+int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
+                         int32_t *tmp, int32_t *hist, hipStream_t s);
+enum class EdgeReduce { GapSum, BandwidthSum };
+int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const int32_t *colidx,
+                    const int32_t *new_id, uint64_t *out, EdgeReduce what, const GraphWs &w, hipStream_t s);
+
+}  // namespace ep

@@ -1,0 +1,371 @@
+// Shape-generic K-Means kernels: any d, any k, fp32 or bf16 embeddings.  They are the
+// reference-shaped fallbacks of the library; the shapes the benchmark runs have tuned
+// kernels elsewhere and share these kernels' reductions and second passes.
+//
+// What they compute (EmbedPart paper, Alg. 3, step P <- KMeans(E, k)): one Lloyd round =
+// assign every embedding to its nearest centroid (squared Euclidean, evaluated as
+// ||c||^2 - 2 x.c, lowest index on ties), then move every centroid to the mean of its
+// embeddings (an empty cluster keeps its centroid).
+#include <algorithm>
+#include <type_traits>
+
+#include "kernels.h"
+
+namespace ep {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// ---- init: C[j,:] = X[idx[j],:] ------------------------------------------------------------
+template <typename XT>
+__global__ void gather_rows_kernel(int32_t d, int32_t k, int64_t ld, const XT *__restrict__ X,
+                                   const int64_t *__restrict__ idx, float *__restrict__ C) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)k * d) return;
+    const int32_t j = (int32_t)(t / d), m = (int32_t)(t % d);
+    C[t] = load_elem(X + idx[j] * ld + m);
+}
+
+// ---- centroid preparation: squared norms (and bf16-rounded copies) -------------------------
+// One wave per centroid; the norm is accumulated in fp64 and rounded once.
+__global__ __launch_bounds__(kBlock) void prep_centroids_kernel(int32_t d, int32_t k, int round_bf16,
+                                                                 const float *__restrict__ C,
+                                                                 float *__restrict__ cnorm, float *__restrict__ cq,
+                                                                 bf16_t *__restrict__ cq16) {
+    const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (j >= k) return;
+    const int lane = threadIdx.x & 63;
+    double acc = 0.0;
+    for (int m = lane; m < d; m += 64) {
+        float c = C[(int64_t)j * d + m];
+        if (round_bf16) {
+            const bf16_t q = f32_to_bf16_rne(c);
+            c = bf16_to_f32(q);
+            cq[(int64_t)j * d + m] = c;
+            cq16[(int64_t)j * d + m] = q;
+        }
+        acc += (double)c * (double)c;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) cnorm[j] = (float)acc;
+}
+
+// ---- assignment ------------------------------------------------------------------------------
+// One point per lane.  Centroids pass through LDS in chunks of kChunk; each lane keeps kChunk
+// running dot products and folds them into its best (score, index) pair with a strict <, so
+// the lowest index wins ties.
+constexpr int kChunk = 16;
+constexpr int kChunkLdsFloats = 8192;  // 32 KB
+
+template <typename XT>
+__global__ __launch_bounds__(kBlock) void assign_generic_kernel(int64_t n, int32_t d, int32_t k, int64_t ld,
+                                                                 const XT *__restrict__ X,
+                                                                 const float *__restrict__ C,
+                                                                 const float *__restrict__ cnorm,
+                                                                 int32_t *__restrict__ labels,
+                                                                 float *__restrict__ min_d2,
+                                                                 double *__restrict__ obj_part) {
+    __shared__ float cs[kChunkLdsFloats];
+    __shared__ double red[kBlock / 64];
+    const int dseg = min(d, kChunkLdsFloats / kChunk);  // columns of a chunk held in LDS at once
+    double obj = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const int64_t rounds = (n + stride - 1) / stride;
+    for (int64_t it = 0; it < rounds; ++it) {
+        const int64_t i = it * stride + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+        const bool valid = i < n;
+        const XT *x = X + (valid ? i : 0) * ld;
+        float best = 3.0e38f;
+        int32_t best_j = 0;
+        float xnorm = 0.f;
+        for (int32_t j0 = 0; j0 < k; j0 += kChunk) {
+            const int kc = min(kChunk, k - j0);
+            float acc[kChunk];
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) acc[j] = 0.f;
+            for (int32_t m0 = 0; m0 < d; m0 += dseg) {
+                const int dm = min(dseg, d - m0);
+                __syncthreads();
+                for (int t = threadIdx.x; t < kc * dm; t += kBlock) {
+                    const int j = t / dm, m = t % dm;
+                    cs[j * dseg + m] = C[(int64_t)(j0 + j) * d + m0 + m];
+                }
+                for (int t = threadIdx.x + kc * dseg; t < kChunk * dseg; t += kBlock) cs[t] = 0.f;  // unused slots
+                __syncthreads();
+                if (valid) {
+                    const int dm4 = dm & ~3;
+                    for (int m = 0; m < dm4; m += 4) {
+                        const float4 xv = load4(x + m0 + m);
+                        if (j0 == 0) xnorm += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
+#pragma unroll
+                        for (int j = 0; j < kChunk; ++j) {
+                            const float *c = cs + j * dseg + m;
+                            acc[j] += xv.x * c[0] + xv.y * c[1] + xv.z * c[2] + xv.w * c[3];
+                        }
+                    }
+                    for (int m = dm4; m < dm; ++m) {
+                        const float xv = load_elem(x + m0 + m);
+                        if (j0 == 0) xnorm += xv * xv;
+#pragma unroll
+                        for (int j = 0; j < kChunk; ++j) acc[j] += xv * cs[j * dseg + m];
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) {
+                if (j < kc) {
+                    const float score = cnorm[j0 + j] - 2.f * acc[j];
+                    if (score < best) { best = score; best_j = j0 + j; }
+                }
+            }
+        }
+        if (valid) {
+            labels[i] = best_j;
+            const float d2 = fmaxf(xnorm + best, 0.f);
+            if (min_d2) min_d2[i] = d2;
+            obj += (double)d2;
+        }
+    }
+    if (obj_part) {
+        for (int off = 32; off > 0; off >>= 1) obj += __shfl_down(obj, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = obj;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+            obj_part[blockIdx.x] = t;
+        }
+    }
+}
+
+__global__ void sum_partials_kernel(const double *__restrict__ part, int count, double *__restrict__ out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double t = 0.0;
+        for (int b = 0; b < count; ++b) t += part[b];
+        *out = t;
+    }
+}
+
+// ---- update, small k: per-workgroup LDS partial sums + fixed-order second pass -----------------
+// Workgroup b owns rows [b*R, (b+1)*R).  Thread t owns column t % dpad of the rows with
+// (row - b*R) % rpp == t / dpad, and adds them into its own LDS copy, so no two threads ever
+// touch the same LDS word and the order of additions is fixed.
+template <typename XT>
+__global__ __launch_bounds__(kBlock) void update_partial_kernel(int64_t n, int32_t d, int32_t k, int64_t ld,
+                                                                 int64_t rows_per_block, int dpad, int rpp,
+                                                                 const XT *__restrict__ X,
+                                                                 const int32_t *__restrict__ labels,
+                                                                 float *__restrict__ psum,
+                                                                 int32_t *__restrict__ pcnt) {
+    extern __shared__ float lds[];  // rpp * k * d floats, then rpp * k ints
+    float *sums = lds;
+    int32_t *cnts = reinterpret_cast<int32_t *>(lds + (size_t)rpp * k * d);
+    const int kd = k * d;
+    for (int t = threadIdx.x; t < rpp * kd; t += kBlock) sums[t] = 0.f;
+    for (int t = threadIdx.x; t < rpp * k; t += kBlock) cnts[t] = 0;
+    __syncthreads();
+    const int sub = threadIdx.x / dpad, col0 = threadIdx.x % dpad;
+    const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
+    if (sub < rpp) {
+        float *mine = sums + (size_t)sub * kd;
+        for (int64_t i = b + sub; i < e; i += rpp) {
+            const int32_t l = labels[i];
+            if (l < 0 || l >= k) continue;
+            for (int m = col0; m < d; m += dpad) mine[l * d + m] += load_elem(X + i * ld + m);
+            if (col0 == 0) cnts[sub * k + l] += 1;
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < kd; t += kBlock) {
+        float s = sums[t];
+        for (int r = 1; r < rpp; ++r) s += sums[(size_t)r * kd + t];
+        psum[(int64_t)blockIdx.x * kd + t] = s;
+    }
+    for (int t = threadIdx.x; t < k; t += kBlock) {
+        int32_t c = cnts[t];
+        for (int r = 1; r < rpp; ++r) c += cnts[r * k + t];
+        pcnt[(int64_t)blockIdx.x * k + t] = c;
+    }
+}
+
+}  // namespace
+
+// Second pass shared with the fused kernels: fp64 sum of the per-workgroup partials in
+// workgroup order, divide, round to fp32; empty clusters keep C_prev.
+__global__ __launch_bounds__(kBlock) void update_finalize_kernel(int32_t d, int32_t k, int blocks,
+                                                                  const float *__restrict__ psum,
+                                                                  const int32_t *__restrict__ pcnt,
+                                                                  const float *__restrict__ C_prev,
+                                                                  float *__restrict__ C_out,
+                                                                  int64_t *__restrict__ counts) {
+    const int t = blockIdx.x * kBlock + threadIdx.x;
+    const int kd = k * d;
+    if (t >= kd) return;
+    const int j = t / d;
+    double s = 0.0;
+    int64_t c = 0;
+    for (int b = 0; b < blocks; ++b) {
+        s += (double)psum[(int64_t)b * kd + t];
+        c += pcnt[(int64_t)b * k + j];
+    }
+    C_out[t] = c > 0 ? (float)(s / (double)c) : C_prev[t];
+    if (t % d == 0) counts[j] = c;
+}
+
+namespace {
+
+// ---- update, large k: rows sorted by label, one wave per cluster --------------------------------
+// seg[j] = first sorted position whose label is >= j  (seg[k] = n).
+// Labels are read through the mask the sort used for its keys, so the sequence is monotone
+// (and every seg entry is written) whatever the labels hold.
+__global__ void segment_offsets_kernel(int64_t n, int32_t k, uint32_t key_mask, const int32_t *__restrict__ labels,
+                                       const int32_t *__restrict__ order, int64_t *__restrict__ seg) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n) return;
+    const int32_t prev = i == 0 ? -1 : min((int32_t)((uint32_t)labels[order[i - 1]] & key_mask), k - 1);
+    const int32_t cur = i == n ? k : min((int32_t)((uint32_t)labels[order[i]] & key_mask), k - 1);
+    for (int32_t j = prev + 1; j <= cur; ++j) seg[j] = i;
+}
+
+template <typename XT>
+__global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t k, int64_t ld,
+                                                               const XT *__restrict__ X,
+                                                               const int32_t *__restrict__ order,
+                                                               const int64_t *__restrict__ seg,
+                                                               const float *__restrict__ C_prev,
+                                                               float *__restrict__ C_out,
+                                                               int64_t *__restrict__ counts) {
+    const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (j >= k) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t b = seg[j], e = seg[j + 1];
+    const int64_t cnt = e - b;
+    if (lane == 0) counts[j] = cnt;
+    for (int m0 = 0; m0 < d; m0 += 128) {  // two columns per lane per sweep
+        const int m = m0 + 2 * lane;
+        double s0 = 0.0, s1 = 0.0;
+        if (m < d) {
+            for (int64_t t = b; t < e; ++t) {
+                const XT *x = X + (int64_t)order[t] * ld + m;
+                s0 += (double)load_elem(x);
+                if (m + 1 < d) s1 += (double)load_elem(x + 1);
+            }
+            float *co = C_out + (int64_t)j * d + m;
+            const float *cp = C_prev + (int64_t)j * d + m;
+            co[0] = cnt > 0 ? (float)(s0 / (double)cnt) : cp[0];
+            if (m + 1 < d) co[1] = cnt > 0 ? (float)(s1 / (double)cnt) : cp[1];
+        }
+    }
+}
+
+template <typename F>
+int by_dtype(const ep_problem &p, F &&f) {
+    if (p.dtype == EP_F32) return f(static_cast<const float *>(nullptr));
+    return f(static_cast<const bf16_t *>(nullptr));
+}
+
+}  // namespace
+
+KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
+    Carver c(ws);
+    KmeansWs w{};
+    const size_t kd = (size_t)p.k * p.d;
+    w.obj_part = c.take<double>(kObjBlocksMax);
+    w.cnorm = c.take<float>(p.k);
+    w.idx = c.take<int64_t>(p.k);
+    if (p.dtype == EP_BF16) {
+        w.cq = c.take<float>(kd);
+        w.cq16 = c.take<bf16_t>(kd);
+    }
+    if (kd <= (size_t)kSmallKElems) {
+        w.psum = c.take<float>((size_t)kUpdBlocksMax * kd);
+        w.pcnt = c.take<int32_t>((size_t)kUpdBlocksMax * p.k);
+    } else {
+        w.order = c.take<int32_t>((size_t)p.n);
+        w.order_tmp = c.take<int32_t>((size_t)p.n);
+        w.seg = c.take<int64_t>((size_t)p.k + 1);
+        w.sort_hist = c.take<int32_t>(sort_hist_elems());
+    }
+    w.bytes = align_up(c.used, 256);
+    return w;
+}
+
+int launch_gather_rows(const ep_problem &p, const void *X, const int64_t *idx_dev, float *C, hipStream_t s) {
+    const int64_t total = (int64_t)p.k * p.d;
+    return by_dtype(p, [&](auto *tag) {
+        using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        gather_rows_kernel<XT><<<(unsigned)ceil_div(total, kBlock), kBlock, 0, s>>>(
+            p.d, p.k, p.ld, static_cast<const XT *>(X), idx_dev, C);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    });
+}
+
+int launch_prep_centroids(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s) {
+    prep_centroids_kernel<<<(unsigned)ceil_div(p.k, kBlock / 64), kBlock, 0, s>>>(
+        p.d, p.k, p.dtype == EP_BF16, C, w.cnorm, w.cq, w.cq16);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
+
+int launch_assign_generic(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                          float *min_d2, double *objective, hipStream_t s) {
+    const int blocks = (int)std::min<int64_t>(kObjBlocksMax, ceil_div(p.n, kBlock));
+    const float *Cuse = p.dtype == EP_BF16 ? w.cq : C;
+    int rc = by_dtype(p, [&](auto *tag) {
+        using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        assign_generic_kernel<XT><<<blocks, kBlock, 0, s>>>(p.n, p.d, p.k, p.ld, static_cast<const XT *>(X), Cuse,
+                                                            w.cnorm, labels, min_d2,
+                                                            objective ? w.obj_part : nullptr);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    });
+    if (rc != EP_OK) return rc;
+    if (objective) {
+        sum_partials_kernel<<<1, 64, 0, s>>>(w.obj_part, blocks, objective);
+        EP_LAUNCH_CHECK();
+    }
+    return EP_OK;
+}
+
+int launch_update_small(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
+                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
+    const int kd = p.k * p.d;
+    int dpad = 1;
+    while (dpad < p.d && dpad < kBlock) dpad <<= 1;
+    int rpp = kBlock / dpad;
+    while (rpp > 1 && (size_t)rpp * (kd + p.k) * 4 > 64 * 1024) rpp >>= 1;
+    const size_t lds = (size_t)rpp * (kd + p.k) * 4;
+    int64_t rows_per_block = std::max<int64_t>(ceil_div(p.n, kUpdBlocksMax), 64);
+    const int blocks = (int)ceil_div(p.n, rows_per_block);
+    int rc = by_dtype(p, [&](auto *tag) {
+        using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        update_partial_kernel<XT><<<blocks, kBlock, lds, s>>>(p.n, p.d, p.k, p.ld, rows_per_block, dpad, rpp,
+                                                              static_cast<const XT *>(X), labels, w.psum, w.pcnt);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    });
+    if (rc != EP_OK) return rc;
+    update_finalize_kernel<<<(unsigned)ceil_div(kd, kBlock), kBlock, 0, s>>>(p.d, p.k, blocks, w.psum, w.pcnt, C_prev,
+                                                                             C_out, counts);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
+
+int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
+                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
+    int rc = launch_sort_by_label(p.n, p.k, labels, nullptr, w.order, w.order_tmp, w.sort_hist, s);
+    if (rc != EP_OK) return rc;
+    segment_offsets_kernel<<<(unsigned)ceil_div(p.n + 1, kBlock), kBlock, 0, s>>>(p.n, p.k, p.k <= 256 ? 0xFFu : 0xFFFFu, labels, w.order, w.seg);
+    EP_LAUNCH_CHECK();
+    return by_dtype(p, [&](auto *tag) {
+        using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        segment_mean_kernel<XT><<<(unsigned)ceil_div(p.k, kBlock / 64), kBlock, 0, s>>>(
+            p.d, p.k, p.ld, static_cast<const XT *>(X), w.order, w.seg, C_prev, C_out, counts);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    });
+}
+
+}  // namespace ep

@@ -1,0 +1,116 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, rejects bad arguments before any HIP call, and derives the seeded initial rows
+exactly as the oracle does."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_01000_amd import embedpart as ep
+
+HEADER = Path(__file__).resolve().parent.parent / "include" / "embedpart.h"
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    text = re.sub(r"typedef struct.*?\}\s*\w+;", "", text, flags=re.S)
+    return set(re.findall(r"\b(?:int|const char \*)\s*(\w+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_functions()
+    assert declared == set(ep.SYMBOLS)
+    L = ep.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert ep.ep_version() >= 100
+    assert ep.strerror(0) == "ok" and "workspace" in ep.strerror(ep.EP_EWORKSPACE)
+    assert ep.strerror(-99) == "unknown error code"
+
+
+def _prob(**kw):
+    base = dict(n=1000, ld=128, d=128, k=8, dtype=ep.EP_F32, reserved=0)
+    base.update(kw)
+    return ep.ep_problem(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n=0), ep.EP_EINVAL), (dict(k=0), ep.EP_EINVAL), (dict(d=0), ep.EP_EINVAL),
+    (dict(k=1001), ep.EP_EINVAL), (dict(ld=64), ep.EP_EINVAL), (dict(ld=130), ep.EP_EINVAL),
+    (dict(reserved=1), ep.EP_EINVAL), (dict(dtype=7), ep.EP_EUNSUPPORTED),
+    (dict(d=4096, ld=4096), ep.EP_EUNSUPPORTED), (dict(n=2**31), ep.EP_EINVAL),
+    (dict(n=10**6, k=70000), ep.EP_EUNSUPPORTED),
+])
+def test_bad_problems_are_rejected_on_the_host(kw, code):
+    L = ep.lib()
+    p = _prob(**kw)
+    out = C.c_size_t(0)
+    assert L.kmeans_workspace_bytes(C.byref(p), C.byref(out)) == code
+    fake = C.c_void_p(0x1000)
+    assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, fake, 1 << 40, None) == code
+    assert L.kmeans_run(C.byref(p), fake, 3, fake, fake, fake, None, 0, fake, 1 << 40, None) == code
+
+
+def test_null_pointers_workspace_and_flags():
+    L = ep.lib()
+    p = _prob()
+    need = ep.kmeans_workspace_bytes(p)
+    assert need > 0 and need % 256 == 0
+    fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)
+    assert L.kmeans_workspace_bytes(None, None) == ep.EP_EINVAL
+    assert L.kmeans_workspace_bytes(C.byref(p), None) == ep.EP_EINVAL
+    assert L.kmeans_assign(C.byref(p), None, fake, fake, None, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_assign(C.byref(p), C.c_void_p(0x1004), fake, fake, None, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_assign(C.byref(p), fake, None, fake, None, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_assign(C.byref(p), fake, fake, None, None, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, None, need, None) == ep.EP_EWORKSPACE
+    assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, ws, need - 1, None) == ep.EP_EWORKSPACE
+    assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, C.c_void_p(0x100010), need, None) == ep.EP_EWORKSPACE
+    assert L.kmeans_update(C.byref(p), fake, None, fake, fake, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_update(C.byref(p), fake, fake, fake, fake, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_run(C.byref(p), fake, -1, fake, fake, fake, None, 0, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_run(C.byref(p), fake, 1, fake, fake, fake, None, 8, ws, need, None) == ep.EP_EINVAL
+    idx = (C.c_int64 * 8)(*range(8))
+    assert L.kmeans_init(C.byref(p), fake, None, fake, ws, need, None) == ep.EP_EINVAL
+    idx[3] = 1000                                            # row index out of range
+    assert L.kmeans_init(C.byref(p), fake, idx, fake, ws, need, None) == ep.EP_EINVAL
+
+
+def test_graph_calls_reject_bad_arguments():
+    L = ep.lib()
+    fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)
+    out = C.c_size_t(0)
+    assert L.graph_workspace_bytes(0, 10, 4, C.byref(out)) == ep.EP_EINVAL
+    assert L.graph_workspace_bytes(10, -1, 4, C.byref(out)) == ep.EP_EINVAL
+    assert L.graph_workspace_bytes(10, 10, 0, C.byref(out)) == ep.EP_EINVAL
+    assert L.graph_workspace_bytes(10, 10, 1 << 20, C.byref(out)) == ep.EP_EUNSUPPORTED
+    need = ep.graph_workspace_bytes(1000, 5000, 8)
+    assert need > 0
+    args = (1000, 5000, 8, fake, 0, fake, fake, fake, fake)
+    assert L.partition_quality(*args, None, need, None) == ep.EP_EWORKSPACE
+    assert L.partition_quality(*args, ws, need - 1, None) == ep.EP_EWORKSPACE
+    assert L.partition_quality(1000, 5000, 8, None, 0, fake, fake, fake, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.partition_quality(1000, 5000, 8, fake, 0, None, fake, fake, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.partition_quality(1000, 5000, 0, fake, 0, fake, fake, fake, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.partition_quality(1000, 5000, 8, fake, 0, fake, fake, None, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.partition_permutation(1000, 8, None, fake, fake, ws, need, None) == ep.EP_EINVAL
+    assert L.partition_permutation(1000, 8, fake, fake, fake, None, need, None) == ep.EP_EWORKSPACE
+    assert L.edge_gap_sum(1000, 5000, fake, 0, fake, None, None, ws, need, None) == ep.EP_EINVAL
+    assert L.vertex_bandwidth_sum(1000, 5000, fake, 1, fake, None, fake, None, need, None) == ep.EP_EWORKSPACE
+    assert ep.lib().ep_last_hip_error() == 0                 # nothing above reached the HIP runtime
+
+
+@pytest.mark.parametrize("seed,n,k", [(0, 10, 10), (1, 20_000, 4), (2, 170_000, 8), (3, 2_450_000, 16),
+                                       (5, 111_000_000, 64), (2**63 + 11, 5000, 4999), (3, 2_450_000, 16_384)])
+def test_seeded_rows_match_the_oracle(seed, n, k):
+    got = ep.kmeans_init_indices(seed, n, k).numpy()
+    np.testing.assert_array_equal(got, oracle.init_indices(seed, n, k))
+    assert len(set(got.tolist())) == k
+
+
+def test_seeded_rows_reject_k_above_n():
+    with pytest.raises(ep.EmbedPartError):
+        ep.kmeans_init_indices(0, 3, 4)

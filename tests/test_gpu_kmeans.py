@@ -1,0 +1,235 @@
+"""GPU parity of the K-Means calls against the fp64 oracle, through the C ABI.
+
+Bars: labels equal to the oracle's except where the two nearest distances differ by less
+than 1e-5 relative (checked in fp64 against the same centroids); centroids within 1e-4
+relative L2 per centroid; counts exact given equal labels; ||x - c||^2 within
+1e-5 * (||x||^2 + ||c||^2), the size of the terms the expanded form cancels; objective within
+1e-5 relative.  Lockstep tests feed each device step the oracle's state, free-running
+tests start both from the same initial rows and compare at the end.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_01000_amd import embedpart as ep
+from paper_2604_01000_amd import synth
+
+from parity import (CENTROID_RTOL, DEV, Kmeans, centroid_rel_err, centroids_used, label_mismatches, to_np32)
+
+pytestmark = pytest.mark.gpu
+
+
+def _mixture(n, d, k_true, seed, relu=False, dtype=torch.float32, ld=None):
+    g = torch.Generator().manual_seed(seed)
+    means = 2.0 * torch.randn(k_true, d, generator=g)
+    X = means[torch.randint(0, k_true, (n,), generator=g)] + torch.randn(n, d, generator=g)
+    if relu:
+        X.clamp_(min=0)
+    X = X.to(dtype)
+    if ld is not None:                                   # padded rows: the kernels must honour ld
+        wide = torch.full((n, ld), 1e4, dtype=dtype)
+        wide[:, :d] = X
+        return wide.to(DEV)[:, :d]
+    return X.to(DEV)
+
+
+def _check_assign(X, C64, k, bf16):
+    X32 = to_np32(X)
+    km = Kmeans(X, k).set_centroids(C64)
+    got, d2, obj = km.assign()
+    used = centroids_used(C64, bf16)
+    want, best, _, obj_or = oracle.assign(X32, used)
+    differing, unexcused = label_mismatches(X32, used, got, want, best)
+    assert unexcused == 0, f"{unexcused} of {differing} differing labels are not near-ties"
+    xn = (X32.astype(np.float64) ** 2).sum(axis=1)
+    cn = (used ** 2).sum(axis=1)[got]
+    assert np.all(np.abs(d2 - best) <= 1e-5 * (xn + cn) + 1e-30)
+    assert abs(obj - obj_or) <= 1e-5 * obj_or + 1e-12
+    return differing
+
+
+SHAPES = [  # n, d, k, relu, dtype, ld
+    (1037, 64, 4, False, torch.float32, None),
+    (5003, 128, 8, True, torch.float32, None),
+    (7777, 128, 16, True, torch.float32, 132),
+    (4099, 128, 64, True, torch.float32, None),
+    (3001, 20, 5, False, torch.float32, None),
+    (2500, 7, 3, False, torch.float32, 8),
+    (1500, 516, 9, True, torch.float32, None),
+    (4097, 128, 300, True, torch.bfloat16, None),
+    (2049, 64, 33, True, torch.bfloat16, 72),
+    (6000, 128, 1024, True, torch.bfloat16, None),
+    (64, 128, 64, False, torch.float32, None),      # k == n
+    (1, 64, 1, False, torch.float32, None),
+]
+
+
+@pytest.mark.parametrize("n,d,k,relu,dtype,ld", SHAPES)
+def test_assign_lockstep(n, d, k, relu, dtype, ld):
+    X = _mixture(n, d, max(2, min(k, 40)), seed=n + k, relu=relu, dtype=dtype, ld=ld)
+    X32 = to_np32(X)
+    idx = oracle.init_indices(n, n, k)
+    C0 = X32[idx].astype(np.float64)
+    _check_assign(X, C0, k, dtype == torch.bfloat16)
+    # centroids that are not data rows: one oracle update later
+    labels, _, _, _ = oracle.assign(X32, centroids_used(C0, dtype == torch.bfloat16))
+    C1, _, _ = oracle.update(X32, labels, C0)
+    _check_assign(X, C1, k, dtype == torch.bfloat16)
+
+
+def test_assign_ties_take_the_lowest_index():
+    X = _mixture(3000, 128, 6, seed=5)
+    X32 = to_np32(X)
+    C = X32[oracle.init_indices(9, 3000, 6)].astype(np.float64)
+    C = np.concatenate([C, C[[2, 0]]])                   # centroids 6, 7 duplicate 2, 0
+    got, _, _ = Kmeans(X, 8).set_centroids(C).assign()
+    want, _, _, _ = oracle.assign(X32, C)
+    assert not np.any(got >= 6)
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("n,d,k,relu,dtype,ld", SHAPES)
+def test_update_lockstep(n, d, k, relu, dtype, ld):
+    X = _mixture(n, d, max(2, min(k, 40)), seed=2 * n + k, relu=relu, dtype=dtype, ld=ld)
+    X32 = to_np32(X)
+    rng = np.random.default_rng(n)
+    labels = rng.integers(0, k, size=n).astype(np.int32)
+    if k >= 3:
+        labels[labels == 1] = 0                           # cluster 1 is empty: it must keep its centroid
+    C_prev = rng.normal(size=(k, d)).astype(np.float32)
+    C_or, counts_or, empty = oracle.update(X32, labels, C_prev.astype(np.float64))
+    C_got, counts = Kmeans(X, k).update(labels, C_prev)
+    np.testing.assert_array_equal(counts, counts_or)
+    assert centroid_rel_err(C_got, C_or) <= CENTROID_RTOL
+    assert np.abs(C_got - C_or).max() <= 1e-5 * max(1.0, np.abs(C_or).max())
+    if k >= 3:
+        assert empty >= 1
+        np.testing.assert_array_equal(C_got[1], C_prev[1])
+
+
+def test_update_skips_out_of_range_labels():
+    X = _mixture(4000, 64, 4, seed=1)
+    X32 = to_np32(X)
+    labels = np.random.default_rng(0).integers(0, 4, size=4000).astype(np.int32)
+    bad = labels.copy()
+    bad[::7] = 99
+    bad[3::11] = -1
+    keep = (bad >= 0) & (bad < 4)
+    C_or, counts_or, _ = oracle.update(X32[keep], bad[keep], np.zeros((4, 64)))
+    C_got, counts = Kmeans(X, 4).update(bad, np.zeros((4, 64), dtype=np.float32))
+    np.testing.assert_array_equal(counts, counts_or)
+    assert centroid_rel_err(C_got, C_or) <= CENTROID_RTOL
+
+
+def _oracle_rounds(X32, k, iters, idx, bf16):
+    """Oracle Lloyd, round by round, keeping what each round used and produced."""
+    C = X32[idx].astype(np.float64)
+    hist = []
+    for _ in range(iters):
+        used = oracle.round_bf16(C.astype(np.float32).astype(np.float64)) if bf16 else C
+        labels, best, second, obj = oracle.assign(X32, used)
+        C_next, counts, _ = oracle.update(X32, labels, C)
+        hist.append(dict(C_used=used, labels=labels, best=best, obj=obj, C=C_next, counts=counts))
+        C = C_next
+    return hist
+
+
+def _check_free_running(X, k, iters, idx, bf16=False):
+    X32 = to_np32(X)
+    rounds = _oracle_rounds(X32, k, iters, idx, bf16)
+    lib = oracle.lloyd(X32, k, iters, idx, flags=oracle.FLAG_BF16_CENTROIDS if bf16 else 0)
+    np.testing.assert_array_equal(lib["labels"], rounds[-1]["labels"])     # the two oracle drivers agree
+    got = Kmeans(X, k).init(idx).run(iters)
+    last = rounds[-1]
+    differing, unexcused = label_mismatches(X32, last["C_used"], got["labels"], last["labels"], last["best"])
+    assert unexcused == 0, f"{unexcused} of {differing} differing labels are not near-ties"
+    assert centroid_rel_err(got["C"], last["C"]) <= CENTROID_RTOL
+    assert got["counts"].sum() == X.shape[0]
+    np.testing.assert_array_equal(got["counts"], np.bincount(got["labels"], minlength=k))
+    if differing == 0:
+        np.testing.assert_array_equal(got["counts"], last["counts"])
+    obj_or = np.array([r["obj"] for r in rounds])
+    assert np.all(np.abs(got["obj_hist"][:iters] - obj_or) <= 1e-5 * obj_or)
+    assert np.isnan(got["obj_hist"][iters])                                 # written only with the re-assign flag
+    assert np.all(np.diff(got["obj_hist"][:iters]) <= 1e-6 * obj_or[:-1])  # non-increasing
+    return differing
+
+
+@pytest.mark.parametrize("name", ["tiny", "arxiv_like"])
+def test_run_matches_oracle_full_size(name):
+    w = synth.WORKLOADS[name]
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    _check_free_running(X, w.k, w.iters, idx)
+
+
+@pytest.mark.parametrize("n,d,k,dtype,iters", [(20_011, 128, 16, torch.float32, 8), (9_000, 128, 64, torch.float32, 6),
+                                               (12_345, 128, 700, torch.bfloat16, 4),
+                                               (5_000, 48, 6, torch.float32, 10)])
+def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
+    X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
+    idx = oracle.init_indices(n + 1, n, k)
+    _check_free_running(X, k, iters, idx, bf16=dtype == torch.bfloat16)
+
+
+def test_run_equals_its_steps_resumes_and_repeats():
+    w = synth.WORKLOADS["tiny"]
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    full = Kmeans(X, w.k).init(idx).run(6)
+    again = Kmeans(X, w.k).init(idx).run(6)
+    for key in ("C", "labels", "counts"):
+        np.testing.assert_array_equal(full[key], again[key])               # bit-reproducible
+    np.testing.assert_array_equal(full["obj_hist"][:6], again["obj_hist"][:6])
+    # resume: 2 rounds, then 4 more from the saved centroids
+    km = Kmeans(X, w.k).init(idx)
+    first = km.run(2)
+    second = km.run(4)
+    for key in ("C", "labels", "counts"):
+        np.testing.assert_array_equal(full[key], second[key])
+    np.testing.assert_array_equal(full["obj_hist"][:2], first["obj_hist"][:2])
+    np.testing.assert_array_equal(full["obj_hist"][2:6], second["obj_hist"][:4])
+    # the separate entry points give the same state as the driver
+    km = Kmeans(X, w.k).init(idx)
+    for t in range(6):
+        labels, _, obj = km.assign(want_d2=False)
+        assert obj == full["obj_hist"][t]
+        C_next, counts = km.update()
+        km.set_centroids(C_next)
+    np.testing.assert_array_equal(C_next, full["C"])
+    np.testing.assert_array_equal(labels, full["labels"])
+    np.testing.assert_array_equal(counts, full["counts"])
+
+
+def test_final_reassign_flag():
+    X = _mixture(6000, 128, 8, seed=3, relu=True)
+    idx = oracle.init_indices(4, 6000, 8)
+    plain = Kmeans(X, 8).init(idx).run(3)
+    km = Kmeans(X, 8).init(idx)
+    flagged = km.run(3, flags=ep.EP_RUN_FINAL_REASSIGN)
+    np.testing.assert_array_equal(flagged["C"], plain["C"])
+    np.testing.assert_array_equal(flagged["counts"], plain["counts"])
+    labels4, _, obj4 = Kmeans(X, 8).set_centroids(plain["C"]).assign()
+    np.testing.assert_array_equal(flagged["labels"], labels4)
+    assert flagged["obj_hist"][3] == obj4
+    only = Kmeans(X, 8).set_centroids(plain["C"]).run(0, flags=ep.EP_RUN_FINAL_REASSIGN)    # iters = 0
+    np.testing.assert_array_equal(only["labels"], labels4)
+
+
+def test_init_gathers_rows():
+    for dtype in (torch.float32, torch.bfloat16):
+        X = _mixture(999, 64, 3, seed=8, dtype=dtype, ld=72)
+        idx = oracle.init_indices(1, 999, 17)
+        km = Kmeans(X, 17).init(idx)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(km.C.cpu().numpy(), to_np32(X)[idx])
+
+
+def test_device_errors_are_reported_not_thrown():
+    X = _mixture(100, 64, 3, seed=8)
+    km = Kmeans(X, 4)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(ep.EmbedPartError) as e:
+        ep.kmeans_assign(km.p, km.X, km.C, km.labels, None, None, small)
+    assert e.value.code == ep.EP_EWORKSPACE
