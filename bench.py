@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the EmbedPart clustering hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: seeded initial centroids, `iters` Lloyd rounds (kmeans_run), the integer
+partition-quality sweep over the CSR graph (partition_quality) and, for the reordering
+workload, the partition-sorted relabelling and its edge-gap sum.  The headline value is
+point-iterations per second over whole steps (n * iters / step time).
+
+Prints ONE JSON line.  `roofline` describes the kernel that reads X in every Lloyd round, timed
+with HIP events recorded around each of its launches (ep_profile_arm) in a second pass of the
+same steps, so that the events do not perturb the headline timing.  `cpu_baseline` is the fp64
+oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/), scaled by the copy-kernel calibration; None where not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+class HipEvents:
+    """hipEvent_t handles owned by the benchmark (created through the HIP runtime directly)."""
+
+    def __init__(self, count: int):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.arr = (C.c_void_p * count)()
+        for i in range(count):
+            ev = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(ev)) == 0
+            self.arr[i] = ev
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        out = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(out), self.arr[i], self.arr[j])
+        assert rc == 0, f"hipEventElapsedTime -> {rc}"
+        return out.value
+
+    def destroy(self):
+        for ev in self.arr:
+            self.hip.hipEventDestroy(C.c_void_p(ev))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="arxiv_like",
+                    help="tiny | arxiv_like | products_like | products_reorder | papers_like")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2604_01000_amd import embedpart as ep
+    from paper_2604_01000_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    reorder = w.name == "products_reorder"
+
+    # ---- inputs, resident in HBM before anything is timed ----
+    blocks = synth.block_labels(w)
+    X = synth.embeddings(w, dev, blocks)
+    rowptr, colidx, _ = synth.sbm_graph(w, dev, blocks)
+    nnz = colidx.numel()
+    idx = ep.kmeans_init_indices(w.seed, w.n, w.k)
+
+    p = ep.problem(X, w.k)
+    ws = ep.workspace(ep.kmeans_workspace_bytes(p), dev)
+    gws = ep.workspace(ep.graph_workspace_bytes(w.n, nnz, w.k), dev)
+    Cc = torch.empty((w.k, w.d), dtype=torch.float32, device=dev)
+    labels = torch.empty(w.n, dtype=torch.int32, device=dev)
+    counts = torch.empty(w.k, dtype=torch.int64, device=dev)
+    hist = torch.zeros(w.iters + 1, dtype=torch.float64, device=dev)
+    cut = torch.zeros(1, dtype=torch.int64, device=dev)
+    sizes = torch.zeros(w.k, dtype=torch.int64, device=dev)
+    new_id = torch.empty(w.n, dtype=torch.int32, device=dev) if reorder else None
+    order = torch.empty(w.n, dtype=torch.int32, device=dev) if reorder else None
+    gap = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        ep.kmeans_init(p, X, idx, Cc, ws)
+        ep.kmeans_run(p, X, w.iters, Cc, labels, counts, hist, 0, ws)
+        ep.partition_quality(w.n, nnz, w.k, rowptr, colidx, labels, cut, sizes, gws)
+        if reorder:
+            ep.partition_permutation(w.n, w.k, labels, new_id, order, gws)
+            ep.edge_gap_sum(w.n, nnz, rowptr, colidx, new_id, gap, gws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = w.n * w.iters / (elapsed / args.steps) / 1e6
+
+    # ---- second pass of the same steps with events around the kernel that reads X each round ----
+    launches = args.steps * w.iters
+    evs = HipEvents(2 * launches)
+    assert ep.lib().ep_profile_arm(evs.arr, 2 * launches, ep.EP_PROF_LLOYD_MAIN) == 0
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    seen = ep.lib().ep_profile_count()
+    ep.lib().ep_profile_arm(None, 0, 0)
+    assert seen == launches, (seen, launches)
+    kernel_ms = float(np.mean([evs.elapsed_ms(2 * i, 2 * i + 1) for i in range(launches)]))
+    evs.destroy()
+
+    elem = 2 if w.dtype == "bf16" else 4
+    if reorder:   # dense contraction on the matrix cores: 2*n*k*d flop per launch
+        flop = 2.0 * w.n * w.k * w.d
+        roofline = dict(bound="mfma", achieved=flop / (kernel_ms * 1e-3) / 1e12, peak=2500.0, unit="TFLOP/s")
+    else:         # streaming: X read once + one int32 label per point
+        nbytes = w.n * (w.d * elem + 4)
+        roofline = dict(bound="hbm", achieved=nbytes / (kernel_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
+    roofline["kernel_ms"] = kernel_ms
+    roofline["kernel"] = "lloyd round kernel that reads X (EP_PROF_LLOYD_MAIN)"
+
+    torch.cuda.synchronize()
+    result_labels = labels.cpu().numpy()
+    quality = dict(edge_cut_ratio=int(cut.item()) / max(nnz, 1), vertex_balance=int(sizes.max().item()) * w.k / w.n,
+                   objective=float(hist[w.iters - 1].item()), nnz=nnz)
+    if reorder:
+        quality["mean_edge_gap"] = (int(gap.item()) & (2**64 - 1)) / max(nnz, 1)
+
+    # ---- the oracle on this machine's host cores ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample_n = min(w.n, 1 << 18 if w.k > 64 else 1 << 22)
+        sample_iters = w.iters if w.k <= 64 else 1
+        Xs = X[:sample_n].to("cpu", torch.float32).numpy()
+        kk = min(w.k, sample_n)
+        t0 = time.perf_counter()
+        oracle.lloyd(Xs, kk, sample_iters, oracle.init_indices(w.seed, sample_n, kk),
+                     flags=oracle.FLAG_BF16_CENTROIDS if w.dtype == "bf16" else 0)
+        dt = time.perf_counter() - t0
+        cpu = dict(value=sample_n * sample_iters / dt / 1e6, unit="Mpts*iter/s", cores=oracle.threads(), kind="oracle",
+                   sample=f"first {sample_n} rows of the workload, k={kk}, {sample_iters} Lloyd rounds, {dt:.1f} s")
+
+    out = dict(metric="kmeans_point_iterations_per_s", value=value, unit="Mpts*iter/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16" if w.dtype == "bf16" else "f32", data="synthetic",
+               config=dict(workload=w.name, n=w.n, d=w.d, k=w.k, iters=w.iters, nnz=nnz,
+                           step="kmeans_init + kmeans_run + partition_quality" +
+                                (" + partition_permutation + edge_gap_sum" if reorder else "")),
+               roofline=roofline, cpu_baseline=cpu, quality=quality,
+               labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

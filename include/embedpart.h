@@ -20,7 +20,8 @@
  *     256-byte aligned and at least as large as the matching *_workspace_bytes
  *     call reports.  The library allocates nothing, frees nothing and keeps no
  *     pointer after a call returns.  Its only global state is the code of the
- *     last failing HIP call (ep_last_hip_error).
+ *     last failing HIP call (ep_last_hip_error) and the benchmark aid
+ *     ep_profile_arm at the end of this file.
  *   - Partition / cluster ids are 0-based, in [0, k).  (The paper numbers
  *     partitions 1..k.)
  *   - Return value: EP_OK (0) or a negative EP_E* code.  Arguments are checked
@@ -57,8 +58,8 @@ extern "C" {
 
 /* The clustering problem: n embeddings of dimension d, row-major with row
  * stride ld (elements, ld >= d), to be grouped into k clusters.
- * For EP_BF16, X must be 4-byte aligned and ld even; for EP_F32, X must be
- * 16-byte aligned and ld a multiple of 4. */
+ * X must be 16-byte aligned; ld must be a multiple of 4 (EP_F32) or of 8
+ * (EP_BF16), so that every row starts 16-byte aligned. */
 typedef struct ep_problem {
     int64_t n;
     int64_t ld;
@@ -184,6 +185,22 @@ int edge_gap_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
 int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
                          const int32_t *colidx, const int32_t *new_id,
                          uint64_t *bw_sum, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Benchmark aid, not part of the method: per-kernel timing with HIP events the caller owns.
+ * While armed, each launch of a kernel of class `kernel_class` made by any call records
+ * events_host[2*i] just before and events_host[2*i+1] just after launch number i (counted from
+ * arming) on that call's stream, for i < capacity / 2; later launches are not recorded.
+ * events_host: host array of hipEvent_t handles created with timing enabled; it must stay
+ * valid until disarmed.  ep_profile_arm(NULL, 0, 0) disarms.  This and the HIP error code are
+ * the library's only process-global state; arming is not thread-safe.
+ * ep_profile_count(): launches of the armed class seen since arming (may exceed capacity / 2).
+ */
+#define EP_PROF_LLOYD_MAIN  1  /* the kernel that reads X in a Lloyd round (assignment, fused with the sums where fused) */
+#define EP_PROF_UPDATE_SUMS 2  /* the separate partial-sum / segment-mean kernel of kmeans_update */
+#define EP_PROF_EDGE_SWEEP  3  /* the CSR sweep of partition_quality / edge_gap_sum */
+int ep_profile_arm(void **events_host, int capacity, int kernel_class);
+int ep_profile_count(void);
 
 #ifdef __cplusplus
 }

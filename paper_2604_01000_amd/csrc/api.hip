@@ -9,6 +9,20 @@ namespace ep {
 static std::atomic<int> g_last_hip_error{0};
 void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 
+static void **g_prof_events = nullptr;
+static int g_prof_capacity = 0, g_prof_class = 0, g_prof_count = 0;
+
+ProfScope::ProfScope(int kernel_class, hipStream_t s) : stop_(nullptr), s_(s) {
+    if (!g_prof_events || kernel_class != g_prof_class) return;
+    const int i = g_prof_count++;
+    if (2 * i + 1 >= g_prof_capacity) return;
+    (void)hipEventRecord(static_cast<hipEvent_t>(g_prof_events[2 * i]), s);
+    stop_ = static_cast<hipEvent_t>(g_prof_events[2 * i + 1]);
+}
+ProfScope::~ProfScope() {
+    if (stop_) (void)hipEventRecord(stop_, s_);
+}
+
 namespace {
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -83,6 +97,18 @@ const char *ep_strerror(int code) {
 }
 
 int ep_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int ep_profile_arm(void **events_host, int capacity, int kernel_class) {
+    if (events_host && (capacity < 2 || kernel_class < EP_PROF_LLOYD_MAIN || kernel_class > EP_PROF_EDGE_SWEEP))
+        return EP_EINVAL;
+    g_prof_events = events_host;
+    g_prof_capacity = events_host ? capacity : 0;
+    g_prof_class = events_host ? kernel_class : 0;
+    g_prof_count = 0;
+    return EP_OK;
+}
+
+int ep_profile_count(void) { return g_prof_count; }
 
 int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host) {
     if (!idx_host || n < 1 || k < 1 || (int64_t)k > n) return EP_EINVAL;

@@ -22,6 +22,14 @@ void note_hip_error(hipError_t e);
 
 #define EP_LAUNCH_CHECK() EP_HIP_TRY(hipGetLastError())
 
+// Records the caller's events around one kernel launch while ep_profile_arm() is in force.
+struct ProfScope {
+    ProfScope(int kernel_class, hipStream_t s);
+    ~ProfScope();
+    hipEvent_t stop_;
+    hipStream_t s_;
+};
+
 constexpr int kWave = 64;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -258,6 +258,7 @@ int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowp
     if (nnz > 0) {
         const int64_t blocks = ceil_div(nnz, (int64_t)kBlock * kEdgesPerThread);
         auto out = reinterpret_cast<unsigned long long *>(cut);
+        ProfScope prof(EP_PROF_EDGE_SWEEP, s);
         if (i64)
             edge_sweep_kernel<int64_t, true><<<(unsigned)blocks, kBlock, 0, s>>>(
                 n, nnz, k, static_cast<const int64_t *>(rowptr), colidx, labels, out);
@@ -276,6 +277,7 @@ int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const 
     EP_LAUNCH_CHECK();
     if (nnz <= 0) return EP_OK;
     auto out = reinterpret_cast<unsigned long long *>(out64);
+    ProfScope prof(EP_PROF_EDGE_SWEEP, s);
     if (what == EdgeReduce::GapSum) {
         const int64_t blocks = ceil_div(nnz, (int64_t)kBlock * kEdgesPerThread);
         if (i64)

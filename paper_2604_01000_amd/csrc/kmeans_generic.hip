@@ -315,6 +315,7 @@ int launch_assign_generic(const ep_problem &p, const void *X, const float *C, co
     const float *Cuse = p.dtype == EP_BF16 ? w.cq : C;
     int rc = by_dtype(p, [&](auto *tag) {
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        ProfScope prof(EP_PROF_LLOYD_MAIN, s);
         assign_generic_kernel<XT><<<blocks, kBlock, 0, s>>>(p.n, p.d, p.k, p.ld, static_cast<const XT *>(X), Cuse,
                                                             w.cnorm, labels, min_d2,
                                                             objective ? w.obj_part : nullptr);
@@ -341,6 +342,7 @@ int launch_update_small(const ep_problem &p, const void *X, const int32_t *label
     const int blocks = (int)ceil_div(p.n, rows_per_block);
     int rc = by_dtype(p, [&](auto *tag) {
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        ProfScope prof(EP_PROF_UPDATE_SUMS, s);
         update_partial_kernel<XT><<<blocks, kBlock, lds, s>>>(p.n, p.d, p.k, p.ld, rows_per_block, dpad, rpp,
                                                               static_cast<const XT *>(X), labels, w.psum, w.pcnt);
         EP_LAUNCH_CHECK();
@@ -361,6 +363,7 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
     EP_LAUNCH_CHECK();
     return by_dtype(p, [&](auto *tag) {
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        ProfScope prof(EP_PROF_UPDATE_SUMS, s);
         segment_mean_kernel<XT><<<(unsigned)ceil_div(p.k, kBlock / 64), kBlock, 0, s>>>(
             p.d, p.k, p.ld, static_cast<const XT *>(X), w.order, w.seg, C_prev, C_out, counts);
         EP_LAUNCH_CHECK();

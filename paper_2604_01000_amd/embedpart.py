@@ -22,7 +22,9 @@ SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
     "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
+    "ep_profile_arm", "ep_profile_count",
 )
+EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
 
 
 class ep_problem(C.Structure):
@@ -62,6 +64,7 @@ def lib() -> C.CDLL:
         L.partition_permutation.argtypes = [i64, i32, vp, vp, vp, vp, sz, vp]
         L.edge_gap_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.vertex_bandwidth_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
+        L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
         for name in SYMBOLS:
             if name not in ("ep_strerror",):
                 getattr(L, name).restype = C.c_int
