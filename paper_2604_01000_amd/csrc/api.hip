@@ -59,6 +59,11 @@ bool small_k(const ep_problem &p) { return (int64_t)p.k * p.d <= kSmallKElems; }
 
 int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
               float *min_d2, double *objective, hipStream_t s) {
+    if (small_path_supported(p)) {
+        int rc = launch_small_half_norms(p, C, w, s);
+        if (rc != EP_OK) return rc;
+        return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
+    }
     int rc = launch_prep_centroids(p, C, w, s);
     if (rc != EP_OK) return rc;
     return launch_assign_generic(p, X, C, w, labels, min_d2, objective, s);
@@ -66,6 +71,7 @@ int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs
 
 int do_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
               int64_t *counts, const KmeansWs &w, hipStream_t s) {
+    if (small_path_supported(p)) return launch_small_update(p, X, labels, C_prev, C_out, counts, w, s);
     return small_k(p) ? launch_update_small(p, X, labels, C_prev, C_out, counts, w, s)
                       : launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, s);
 }
@@ -175,6 +181,16 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
     if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (small_path_supported(*p)) {  // fused rounds: X is read once per round
+        if (iters > 0 && (rc = launch_small_half_norms(*p, C, w, s)) != EP_OK) return rc;
+        for (int32_t t = 0; t < iters; ++t)
+            if ((rc = launch_small_round(*p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
+                                         s)) != EP_OK)
+                return rc;
+        if (flags & EP_RUN_FINAL_REASSIGN)
+            rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+        return rc;
+    }
     for (int32_t t = 0; t < iters; ++t) {
         if ((rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + t : nullptr, s)) != EP_OK)
             return rc;

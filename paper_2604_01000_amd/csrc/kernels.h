@@ -35,6 +35,20 @@ int launch_update_small(const ep_problem &p, const void *X, const int32_t *label
 int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
                          float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
 
+// ---- K-Means, k <= 64, d in {64,128}, fp32: fused matrix-core kernels (kmeans_small.hip) --------
+constexpr int kSmallMaxBlocks = 512;  // workgroups (= partial sums) per launch; <= kUpdBlocksMax
+bool small_path_supported(const ep_problem &p);
+// w.cnorm holds -||c||^2/2 on this path.
+int launch_small_half_norms(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s);
+int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                        float *min_d2, double *objective, hipStream_t s);
+int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
+                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+// One fused round: assign against C (whose half norms are in w.cnorm), sums, then C <- means
+// (in place), w.cnorm <- half norms of the new C, *objective <- this round's objective.
+int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
+                       int64_t *counts, double *objective, hipStream_t s);
+
 // ---- graph kernels (graph.hip) ---------------------------------------------------
 constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass
 struct GraphWs {

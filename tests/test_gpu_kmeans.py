@@ -122,38 +122,51 @@ def test_update_skips_out_of_range_labels():
     assert centroid_rel_err(C_got, C_or) <= CENTROID_RTOL
 
 
-def _oracle_rounds(X32, k, iters, idx, bf16):
-    """Oracle Lloyd, round by round, keeping what each round used and produced."""
-    C = X32[idx].astype(np.float64)
-    hist = []
-    for _ in range(iters):
-        used = oracle.round_bf16(C.astype(np.float32).astype(np.float64)) if bf16 else C
-        labels, best, second, obj = oracle.assign(X32, used)
-        C_next, counts, _ = oracle.update(X32, labels, C)
-        hist.append(dict(C_used=used, labels=labels, best=best, obj=obj, C=C_next, counts=counts))
-        C = C_next
-    return hist
-
-
 def _check_free_running(X, k, iters, idx, bf16=False):
+    """Free-running device Lloyd against the oracle.
+
+    Every round of the device's own trajectory is checked: its labels against the oracle's
+    assignment from the centroids the device held (differences only at near-ties), its new
+    centroids against the oracle's means of the device's labels, its objective against the
+    oracle's.  A near-tie resolved differently moves a centroid by about |x - c| / n_j, which
+    can be more than the centroid tolerance for small clusters and then moves other points, so
+    the device's and the oracle's own trajectories are compared at the end only when no label
+    differed on the way; otherwise their final objectives must still agree closely.
+    Returns the number of labels that differed over all rounds."""
     X32 = to_np32(X)
-    rounds = _oracle_rounds(X32, k, iters, idx, bf16)
-    lib = oracle.lloyd(X32, k, iters, idx, flags=oracle.FLAG_BF16_CENTROIDS if bf16 else 0)
-    np.testing.assert_array_equal(lib["labels"], rounds[-1]["labels"])     # the two oracle drivers agree
-    got = Kmeans(X, k).init(idx).run(iters)
-    last = rounds[-1]
-    differing, unexcused = label_mismatches(X32, last["C_used"], got["labels"], last["labels"], last["best"])
-    assert unexcused == 0, f"{unexcused} of {differing} differing labels are not near-ties"
-    assert centroid_rel_err(got["C"], last["C"]) <= CENTROID_RTOL
-    assert got["counts"].sum() == X.shape[0]
-    np.testing.assert_array_equal(got["counts"], np.bincount(got["labels"], minlength=k))
-    if differing == 0:
-        np.testing.assert_array_equal(got["counts"], last["counts"])
-    obj_or = np.array([r["obj"] for r in rounds])
-    assert np.all(np.abs(got["obj_hist"][:iters] - obj_or) <= 1e-5 * obj_or)
-    assert np.isnan(got["obj_hist"][iters])                                 # written only with the re-assign flag
-    assert np.all(np.diff(got["obj_hist"][:iters]) <= 1e-6 * obj_or[:-1])  # non-increasing
-    return differing
+    n = X32.shape[0]
+    free = Kmeans(X, k).init(idx).run(iters)
+    km = Kmeans(X, k).init(idx)
+    C_prev = km.C.cpu().numpy().astype(np.float64)
+    np.testing.assert_array_equal(C_prev, X32[idx].astype(np.float64))
+    flips = 0
+    for t in range(iters):
+        got = km.run(1)
+        used = centroids_used(C_prev, bf16)
+        want, best, _, obj_or = oracle.assign(X32, used)
+        differing, unexcused = label_mismatches(X32, used, got["labels"], want, best)
+        assert unexcused == 0, f"round {t}: {unexcused} of {differing} differing labels are not near-ties"
+        flips += differing
+        C_or, counts_or, _ = oracle.update(X32, got["labels"], C_prev)
+        np.testing.assert_array_equal(got["counts"], counts_or)
+        assert centroid_rel_err(got["C"], C_or) <= CENTROID_RTOL, f"round {t}"
+        assert abs(got["obj_hist"][0] - obj_or) <= 1e-5 * obj_or
+        assert abs(free["obj_hist"][t] - got["obj_hist"][0]) == 0.0       # stepping = running
+        C_prev = got["C"].astype(np.float64)
+    for key in ("C", "labels", "counts"):
+        np.testing.assert_array_equal(free[key], got[key])
+    assert np.isnan(free["obj_hist"][iters])                                # written only with the re-assign flag
+    assert free["counts"].sum() == n
+    assert np.all(np.diff(free["obj_hist"][:iters]) <= 1e-6 * free["obj_hist"][:iters - 1])   # non-increasing
+    ref = oracle.lloyd(X32, k, iters, idx, flags=oracle.FLAG_BF16_CENTROIDS if bf16 else 0)
+    if flips == 0:
+        np.testing.assert_array_equal(free["labels"], ref["labels"])
+        np.testing.assert_array_equal(free["counts"], ref["counts"])
+        assert centroid_rel_err(free["C"], ref["C"]) <= CENTROID_RTOL
+        assert np.all(np.abs(free["obj_hist"][:iters] - ref["obj_hist"]) <= 1e-5 * ref["obj_hist"])
+    else:
+        assert abs(free["obj_hist"][iters - 1] - ref["obj_hist"][-1]) <= 1e-3 * ref["obj_hist"][-1]
+    return flips
 
 
 @pytest.mark.parametrize("name", ["tiny", "arxiv_like"])
@@ -161,7 +174,8 @@ def test_run_matches_oracle_full_size(name):
     w = synth.WORKLOADS[name]
     X = synth.embeddings(w, DEV)
     idx = oracle.init_indices(w.seed, w.n, w.k)
-    _check_free_running(X, w.k, w.iters, idx)
+    flips = _check_free_running(X, w.k, w.iters, idx)
+    assert flips == 0, "the benchmark configurations are expected to follow the oracle's trajectory exactly"
 
 
 @pytest.mark.parametrize("n,d,k,dtype,iters", [(20_011, 128, 16, torch.float32, 8), (9_000, 128, 64, torch.float32, 6),
@@ -173,8 +187,10 @@ def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     _check_free_running(X, k, iters, idx, bf16=dtype == torch.bfloat16)
 
 
-def test_run_equals_its_steps_resumes_and_repeats():
-    w = synth.WORKLOADS["tiny"]
+@pytest.mark.parametrize("name,n", [("tiny", None), ("products_like", 20_011), ("papers_like", 9_001)])
+def test_run_equals_its_steps_resumes_and_repeats(name, n):
+    w = synth.WORKLOADS[name]
+    w = w if n is None else w.scaled(n)
     X = synth.embeddings(w, DEV)
     idx = oracle.init_indices(w.seed, w.n, w.k)
     full = Kmeans(X, w.k).init(idx).run(6)
