@@ -104,7 +104,7 @@ int kmeans_init(const ep_problem *p, const void *X, const int64_t *idx_host,
  * ||c_j||^2 - 2 x_i.c_j in fp32.  With EP_BF16 the centroids are rounded to
  * bf16 (nearest-even) for the x.c products, which accumulate in fp32.
  *   C         k x d fp32, read
- *   labels    n int32, written
+ *   labels    n int32, 16-byte aligned, written
  *   min_d2    n fp32 or NULL: ||x_i - c_label||^2 (clamped at 0), written
  *   objective 1 double or NULL: sum_i ||x_i - c_label||^2, written (not added to)
  */
@@ -129,7 +129,7 @@ int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels,
 /*
  * `iters` Lloyd rounds (assign, then update) starting from the centroids in C.
  *   C               k x d fp32: initial centroids in, final centroids out
- *   labels          n int32, written: the labels of the last assignment performed
+ *   labels          n int32, 16-byte aligned, written: the labels of the last assignment performed
  *   counts          k int64, written: cluster sizes of round `iters`, of which C holds the means
  *   objective_hist  iters + 1 doubles or NULL: [t] = objective of round t's assignment;
  *                   [iters] is written only with EP_RUN_FINAL_REASSIGN

@@ -157,7 +157,7 @@ int kmeans_assign(const ep_problem *p, const void *X, const float *C, int32_t *l
     int rc = check_problem(p);
     if (rc != EP_OK) return rc;
     if ((rc = check_x(p, X)) != EP_OK) return rc;
-    if (!C || !labels) return EP_EINVAL;
+    if (!C || !labels || !aligned(labels, 16)) return EP_EINVAL;
     if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
     return do_assign(*p, X, C, carve_kmeans_ws(*p, ws), labels, min_d2, objective, static_cast<hipStream_t>(stream));
 }
@@ -177,7 +177,8 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
     int rc = check_problem(p);
     if (rc != EP_OK) return rc;
     if ((rc = check_x(p, X)) != EP_OK) return rc;
-    if (!C || !labels || !counts || iters < 0 || (flags & ~EP_RUN_FINAL_REASSIGN)) return EP_EINVAL;
+    if (!C || !labels || !aligned(labels, 16) || !counts || iters < 0 || (flags & ~EP_RUN_FINAL_REASSIGN))
+        return EP_EINVAL;
     if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -185,7 +186,7 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
         if (iters > 0 && (rc = launch_small_half_norms(*p, C, w, s)) != EP_OK) return rc;
         for (int32_t t = 0; t < iters; ++t)
             if ((rc = launch_small_round(*p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
-                                         s)) != EP_OK)
+                                         t == 0, s)) != EP_OK)
                 return rc;
         if (flags & EP_RUN_FINAL_REASSIGN)
             rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);

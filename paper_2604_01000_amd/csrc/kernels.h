@@ -46,8 +46,10 @@ int launch_small_update(const ep_problem &p, const void *X, const int32_t *label
                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
 // One fused round: assign against C (whose half norms are in w.cnorm), sums, then C <- means
 // (in place), w.cnorm <- half norms of the new C, *objective <- this round's objective.
+// first_round: the data-only term of the objective (sum ||x||^2) is computed and kept in the
+// workspace; later rounds of the same kmeans_run reuse it.
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
-                       int64_t *counts, double *objective, hipStream_t s);
+                       int64_t *counts, double *objective, bool first_round, hipStream_t s);
 
 // ---- graph kernels (graph.hip) ---------------------------------------------------
 constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass

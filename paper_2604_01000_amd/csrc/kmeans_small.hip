@@ -29,10 +29,14 @@ namespace ep {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
 constexpr int kSub = 16;  // points per sub-tile
+constexpr int kLabelFlush = 64;                  // sub-tiles whose labels are written out together (4 KB)
+constexpr int kLabelBuf = kLabelFlush * kSub;  // ints per wave
 
 enum Mode { kAssignOnly = 0, kUpdateOnly = 1, kFused = 2 };
 
@@ -42,21 +46,51 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int D, int KT, int MODE>
+// Reductions over the 16 lanes of a DPP row; every lane of the row gets the result.
+// Steps: xor 1, xor 2 (quad permutes), then mirror within 8 and within 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ int row16_max(int v) {
+    v = max(v, dpp_i<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = max(v, dpp_i<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = max(v, dpp_i<0x141>(v));  // row_half_mirror
+    v = max(v, dpp_i<0x140>(v));  // row_mirror
+    return v;
+}
+__device__ __forceinline__ int row16_min(int v) {
+    v = min(v, dpp_i<0xB1>(v));
+    v = min(v, dpp_i<0x4E>(v));
+    v = min(v, dpp_i<0x141>(v));
+    v = min(v, dpp_i<0x140>(v));
+    return v;
+}
+// Order-preserving map between finite floats and signed integers (its own inverse).
+__device__ __forceinline__ int float_key(float f) {
+    const int b = __float_as_int(f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float key_float(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
+
+// XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
+template <int D, int KT, int MODE, bool XSQ>
 __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) void lloyd_small_kernel(
-    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wg, const float *__restrict__ X,
+    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const float *__restrict__ X,
     const float *__restrict__ C, const float *__restrict__ hneg, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
-    int32_t *__restrict__ pcnt, double *__restrict__ obj_part) {
+    int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part) {
     constexpr int NJ = D / 16;       // 16-byte pieces per lane in the transposed layout; also column tiles
     constexpr int NH = D / 64;       // 16-byte pieces per lane and point in the load layout
     constexpr int STRIDE = D + 4;    // padded LDS row: consecutive rows start 4 banks apart
     __shared__ float lds[kWaves * kSub * STRIDE];
+    __shared__ int32_t label_lds[MODE != kUpdateOnly ? kWaves * kLabelBuf : 1];
     __shared__ float xn_lds[kWaves][kSub];
-    __shared__ double red[kWaves];
+    __shared__ double red[2][kWaves];
     __shared__ int32_t cnt_lds[16 * KT];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: keeps the loop scalar
     const int g = lane >> 4, c = lane & 15;
     float *tile = lds + wave * kSub * STRIDE;
 
@@ -89,46 +123,80 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     }
     double obj_x = 0.0, obj_s = 0.0;
 
+    // Every wave owns a contiguous range of sub-tiles (a fixed function of n and the grid).
     const int64_t total_sub = (n + kSub - 1) / kSub;
-    const int64_t first = (int64_t)blockIdx.x * subtiles_per_wg;
-    const int64_t last = min(total_sub, first + subtiles_per_wg);
+    const int64_t first = ((int64_t)blockIdx.x * kWaves + wave) * subtiles_per_wave;
+    const int64_t last = min(total_sub, first + subtiles_per_wave);
 
-    f32x4 xcur[4][NH], xnext[4][NH];
-    auto load_subtile = [&](int64_t st, f32x4(&dst)[4][NH]) {
+    // Rows are read with buffer loads: the descriptor is rebuilt per sub-tile from a scalar base
+    // and covers exactly the sub-tile's valid bytes, so lanes that would read past the last row
+    // get zeros from the hardware bounds check and the loop needs no ragged special case.
+    // Two lane layouts (16 * ld * 4 < 2^31 is checked on the host):
+    //   point-per-lane (assignment operand): lane (g, c), piece j = row c, columns 16j + 4g .. + 3;
+    //     each 4-lane group reads one aligned 64-byte segment, pieces j, j + 1 share a cache line.
+    //   row-per-group (sum operand): lane (g, c), piece (r, h) = row 4g + r, columns 64h + 4c .. + 3.
+    constexpr int NX = NJ;  // 16-byte pieces per lane and sub-tile (NJ == 4 * NH)
+    constexpr bool kPointPerLane = MODE != kUpdateOnly;
+    int voff[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t row = min(st * kSub + 4 * g + r, n - 1);  // rows past the end re-read the last row
+    for (int r = 0; r < 4; ++r) voff[r] = (int)(((4 * g + r) * ld + 4 * c) * 4);
+    const int voff_a = (int)((c * ld + 4 * g) * 4);
+
+    auto load_subtile = [&](int64_t st, f32x4(&dst)[NX]) {
+        // A sub-tile past this workgroup's range gets an empty descriptor: the loads are still
+        // issued (so that the number of loads in flight is the same on every path and the waits
+        // before the first use stay exact) but touch no memory and return zeros.
+        const bool live = st < last;
+        const int64_t row0 = live ? st * kSub : 0;
+        const int rows_here = (int)min((int64_t)kSub, n - row0);
+        const int bytes = live ? (int)(((rows_here - 1) * ld + D) * 4) : 0;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(X + row0 * ld), 0, bytes, 0x00020000);
 #pragma unroll
-            for (int h = 0; h < NH; ++h)
-                dst[r][h] = *reinterpret_cast<const f32x4 *>(X + row * ld + 64 * h + 4 * c);
+        for (int q = 0; q < NX; ++q) {
+            const u32x4 raw = kPointPerLane
+                                  ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, 0)
+                                  : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), 0);
+            dst[q] = __builtin_bit_cast(f32x4, raw);
         }
     };
 
-    int64_t st = first + wave;
-    if (st < last) load_subtile(st, xcur);
-    for (; st < last; st += kWaves) {
+    // Labels are collected in a wave-private LDS buffer and written kLabelFlush sub-tiles at a
+    // time as whole, consecutive cache lines.  Single 64-byte label writes scattered through the
+    // read stream cost about a tenth of the kernel's time in DRAM read/write turnarounds; bursts
+    // of 4 KB cost almost nothing.
+    int32_t *lbuf = label_lds + (MODE != kUpdateOnly ? wave * kLabelBuf : 0);
+    int buffered = 0;  // sub-tiles in the buffer (uniform)
+    auto flush_labels = [&](int64_t next_st) {
+        if (MODE == kUpdateOnly || buffered == 0) return;
+        wave_lds_fence();
+        const int64_t base_row = (next_st - buffered) * kSub;
+        for (int q = lane; q < buffered * 4; q += 64) {
+            const i32x4 v = *reinterpret_cast<const i32x4 *>(lbuf + 4 * q);
+            const int64_t row = base_row + 4 * q;
+            if (row + 3 < n) {
+                *reinterpret_cast<i32x4 *>(labels_out + row) = v;
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (row + e < n) labels_out[row + e] = (int32_t)v[e];
+            }
+        }
+        wave_lds_fence();
+        buffered = 0;
+    };
+
+    auto process = [&](int64_t st, const f32x4(&x)[NX]) {
         const int64_t row0 = st * kSub;
-        if (st + kWaves < last) load_subtile(st + kWaves, xnext);
-
+        const int rows_here = (int)min((int64_t)kSub, n - row0);  // uniform
         int32_t lab[4];
+        f32x4 bt[NX];  // sum operand: piece r * NH + h
         if (MODE != kUpdateOnly) {
-            // transpose through LDS: write point-major rows, read lane c <- point c
+            // The sum product needs the other layout: the sub-tile goes through the wave's LDS tile
+            // (written point-per-lane, read row-per-group) in the shadow of the score product.
+            if (MODE == kFused) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int h = 0; h < NH; ++h)
-                    *reinterpret_cast<f32x4 *>(tile + (4 * g + r) * STRIDE + 64 * h + 4 * c) = xcur[r][h];
-            wave_lds_fence();
-            f32x4 areg[NJ];
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) areg[j] = *reinterpret_cast<const f32x4 *>(tile + c * STRIDE + 16 * j + 4 * g);
-            wave_lds_fence();  // the tile may be overwritten by the next sub-tile
-
-            float xpart = 0.f;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                xpart += areg[j][0] * areg[j][0] + areg[j][1] * areg[j][1] + areg[j][2] * areg[j][2] +
-                         areg[j][3] * areg[j][3];
+                for (int j = 0; j < NJ; ++j) *reinterpret_cast<f32x4 *>(tile + c * STRIDE + 16 * j + 4 * g) = x[j];
+            }
 
             // scores: two accumulation chains per centroid tile (even / odd j), added at the end
             f32x4 acc0[KT], acc1[KT];
@@ -143,59 +211,74 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int mt = 0; mt < KT; ++mt) {
-                        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(areg[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
-                        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(areg[j + 1][e], creg[mt][j + 1][e], acc1[mt],
-                                                                         0, 0, 0);
+                        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
+                        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j + 1][e], creg[mt][j + 1][e], acc1[mt], 0,
+                                                                         0, 0);
                     }
 
-            // argmax over centroids: inside the lane over tiles (ascending index), then over the row
-            float bs[4];
-            int32_t bi[4];
+            if (MODE == kFused) {
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int h = 0; h < NH; ++h)
+                        bt[r * NH + h] =
+                            *reinterpret_cast<const f32x4 *>(tile + (4 * g + r) * STRIDE + 64 * h + 4 * c);
+                wave_lds_fence();  // the tile is overwritten by the next sub-tile
+            }
+
+            float xpart = 0.f;
+            if (XSQ || min_d2) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    xpart += x[j][0] * x[j][0] + x[j][1] * x[j][1] + x[j][2] * x[j][2] + x[j][3] * x[j][3];
+            }
+
+            // argmax over centroids: inside the lane over tiles (ascending index, strict >), then a
+            // 16-lane butterfly on an order-preserving integer key: the maximum first, then the
+            // lowest index among the lanes that hold it.
+            int bkey[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                bs[v] = acc0[0][v] + acc1[0][v];
-                bi[v] = c;
+                float sc = acc0[0][v] + acc1[0][v];
+                int idx = c;
 #pragma unroll
                 for (int mt = 1; mt < KT; ++mt) {
-                    const float s = acc0[mt][v] + acc1[mt][v];
-                    if (s > bs[v]) { bs[v] = s; bi[v] = 16 * mt + c; }
+                    const float s2 = acc0[mt][v] + acc1[mt][v];
+                    if (s2 > sc) { sc = s2; idx = 16 * mt + c; }
                 }
-#pragma unroll
-                for (int off = 8; off > 0; off >>= 1) {
-                    const float os = __shfl_xor(bs[v], off, 64);
-                    const int32_t oi = __shfl_xor(bi[v], off, 64);
-                    if (os > bs[v] || (os == bs[v] && oi < bi[v])) { bs[v] = os; bi[v] = oi; }
-                }
-                lab[v] = (row0 + 4 * g + v < n) ? bi[v] : -1;
+                const int key = float_key(sc);
+                bkey[v] = row16_max(key);
+                const int win = row16_min(key == bkey[v] ? idx : 0x7fffffff);
+                lab[v] = (4 * g + v < rows_here) ? win : -1;
             }
 
             // lane c < 4 of every group owns point 4g + c for the stores and the objective
             const int sel = c & 3;
-            const float my_s = sel == 0 ? bs[0] : sel == 1 ? bs[1] : sel == 2 ? bs[2] : bs[3];
+            const float my_s = key_float(sel == 0 ? bkey[0] : sel == 1 ? bkey[1] : sel == 2 ? bkey[2] : bkey[3]);
             const int32_t my_l = sel == 0 ? lab[0] : sel == 1 ? lab[1] : sel == 2 ? lab[2] : lab[3];
-            const int64_t my_row = row0 + 4 * g + c;
-            const bool owner = c < 4 && my_row < n;
-            if (owner) {
-                labels_out[my_row] = my_l;
-                obj_s += (double)my_s;
-            }
-            if (row0 + c < n) obj_x += (double)xpart;
+            const bool owner = c < 4 && 4 * g + c < rows_here;
+            if (c < 4) lbuf[buffered * kSub + 4 * g + c] = my_l;
+            ++buffered;
+            if (owner) obj_s += (double)my_s;
+            if (XSQ && c < rows_here) obj_x += (double)xpart;
             if (min_d2) {  // uniform branch
                 float xn = xpart;
                 xn += __shfl_xor(xn, 16, 64);
                 xn += __shfl_xor(xn, 32, 64);
                 if (g == 0) xn_lds[wave][c] = xn;
                 wave_lds_fence();
-                if (owner) min_d2[my_row] = fmaxf(xn_lds[wave][4 * g + c] - 2.f * my_s, 0.f);
+                if (owner) min_d2[row0 + 4 * g + c] = fmaxf(xn_lds[wave][4 * g + c] - 2.f * my_s, 0.f);
                 wave_lds_fence();
             }
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int64_t row = row0 + 4 * g + v;
-                const int32_t l = row < n ? labels_in[row] : -1;
+                const int32_t l = (4 * g + v < rows_here) ? labels_in[row0 + 4 * g + v] : -1;
                 lab[v] = (l >= 0 && l < k) ? l : -1;
             }
+#pragma unroll
+            for (int q = 0; q < NX; ++q) bt[q] = x[q];
         }
 
         if (MODE != kAssignOnly) {
@@ -208,21 +291,42 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                     cnt[mt] += hit ? 1 : 0;
 #pragma unroll
                     for (int t = 0; t < NJ; ++t)
-                        accu[mt][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, xcur[r][t >> 2][t & 3], accu[mt][t], 0, 0, 0);
+                        accu[mt][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bt[r * NH + (t >> 2)][t & 3], accu[mt][t],
+                                                                           0, 0, 0);
                 }
         }
+    };
 
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int h = 0; h < NH; ++h) xcur[r][h] = xnext[r][h];
+    // Two register sets in ping-pong: while one sub-tile is processed, the next one is in flight.
+    f32x4 xa[NX], xb[NX];
+    int64_t st = first;
+    load_subtile(st, xa);
+    while (st < last) {
+        load_subtile(st + 1, xb);
+        __builtin_amdgcn_sched_barrier(0);  // keep the whole prefetch ahead of the arithmetic
+        process(st, xa);
+        ++st;
+        if (buffered == kLabelFlush) flush_labels(st);
+        if (st >= last) break;
+        load_subtile(st + 1, xa);
+        __builtin_amdgcn_sched_barrier(0);
+        process(st, xb);
+        ++st;
+        if (buffered == kLabelFlush) flush_labels(st);
     }
+    flush_labels(st);
 
-    // ---- objective partial of this workgroup (fixed order) ----
-    if (MODE != kUpdateOnly && obj_part) {
-        double o = obj_x - 2.0 * obj_s;
-        for (int off = 32; off > 0; off >>= 1) o += __shfl_down(o, off, 64);
-        if (lane == 0) red[wave] = o;
+    // ---- objective partials of this workgroup (fixed order) ----
+    if (MODE != kUpdateOnly && s_part) {
+        double os = obj_s, ox = obj_x;
+        for (int off = 32; off > 0; off >>= 1) {
+            os += __shfl_down(os, off, 64);
+            if (XSQ) ox += __shfl_down(ox, off, 64);
+        }
+        if (lane == 0) {
+            red[0][wave] = os;
+            red[1][wave] = ox;
+        }
     }
 
     // ---- partial sums of this workgroup: waves add their accumulators in wave order ----
@@ -260,10 +364,36 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     } else {
         __syncthreads();
     }
-    if (MODE != kUpdateOnly && obj_part && threadIdx.x == 0) {
-        double t = 0.0;
-        for (int w = 0; w < kWaves; ++w) t += red[w];
-        obj_part[blockIdx.x] = t;
+    if (MODE != kUpdateOnly && s_part && threadIdx.x == 0) {
+        double ts = 0.0, tx = 0.0;
+        for (int w = 0; w < kWaves; ++w) {
+            ts += red[0][w];
+            tx += red[1][w];
+        }
+        s_part[blockIdx.x] = ts;
+        if (XSQ) xsq_part[blockIdx.x] = tx;
+    }
+}
+
+// Lane l adds partials l, l + 64, ...; then a fixed shuffle tree.  Called by one full wave.
+__device__ __forceinline__ double wave_sum_fixed(const double *__restrict__ part, int count, int l) {
+    double o = 0.0;
+    for (int q = l; q < count; q += 64) o += part[q];
+    for (int off = 32; off > 0; off >>= 1) o += __shfl_down(o, off, 64);
+    return o;
+}
+
+// objective = sum ||x||^2 - 2 * sum best score.  The first term is taken from xsq_part when
+// `fresh` (and then stored in *xsq_total), otherwise from *xsq_total.
+__device__ __forceinline__ void write_objective(const double *__restrict__ s_part, const double *__restrict__ xsq_part,
+                                                int parts, int fresh, double *__restrict__ xsq_total,
+                                                double *__restrict__ objective, int l) {
+    const double s = wave_sum_fixed(s_part, parts, l);
+    double x2 = 0.0;
+    if (fresh) x2 = wave_sum_fixed(xsq_part, parts, l);
+    if (l == 0) {
+        if (fresh) *xsq_total = x2; else x2 = *xsq_total;
+        *objective = x2 - 2.0 * s;
     }
 }
 
@@ -282,32 +412,44 @@ __global__ __launch_bounds__(kBlock) void half_norms_kernel(int32_t d, int32_t k
     if (lane == 0) hneg[j] = (float)(-0.5 * acc);
 }
 
-// Second pass of a round.  Workgroup j forms centroid j: fp64 sum of the per-workgroup partials in
-// workgroup order (two interleaved halves, added in a fixed order), divide, round to fp32; an
-// empty cluster keeps its centroid.  It also leaves -||c_j||^2/2 for the next round and, in
-// workgroup 0, the round's objective.
-__global__ __launch_bounds__(kBlock) void lloyd_small_finalize_kernel(
+// Second pass of a round.  Workgroup j forms centroid j.  Thread (seg, m) adds the partials
+// b = seg, seg + S, ... of column m in fp64; the S segment sums are then added in segment order,
+// divided by the count and rounded to fp32; an empty cluster keeps its centroid.  The workgroup
+// also leaves -||c_j||^2/2 for the next round and, in workgroup 0, the round's objective (partials
+// added in a fixed tree order).
+constexpr int kFinBlock = 1024;
+__global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
     int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
-    const double *__restrict__ obj_part, int obj_parts, const float *__restrict__ C_prev, float *__restrict__ C_out,
+    const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
+    double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
     int64_t *__restrict__ counts, float *__restrict__ hneg, double *__restrict__ objective) {
-    __shared__ double half_sum[kBlock];
+    __shared__ double seg_sum[kFinBlock];
     __shared__ float cn[128];
-    __shared__ int64_t total_cnt;
+    __shared__ unsigned long long total_cnt;
     const int j = blockIdx.x, t = threadIdx.x;
-    const int m = t % 128, half = t / 128;  // d <= 128
-    if (t == 0) {
-        int64_t cc = 0;
-        for (int b = 0; b < parts; ++b) cc += pcnt[(int64_t)b * k + j];
-        total_cnt = cc;
+    const int m = t % d, seg = t / d, segs = kFinBlock / d;  // d in {64, 128}
+    if (t == 0) total_cnt = 0;
+    __syncthreads();
+    if (t < parts) {
+        const int32_t c = pcnt[(int64_t)t * k + j];
+        if (c) atomicAdd(&total_cnt, (unsigned long long)c);
     }
     double s = 0.0;
-    if (m < d)
-        for (int b = half; b < parts; b += 2) s += (double)psum[((int64_t)b * k + j) * d + m];
-    half_sum[t] = s;
+    const float *col = psum + (int64_t)j * d + m;
+    const int64_t stride = (int64_t)k * d;
+    int b = seg;
+    for (; b + 3 * segs < parts; b += 4 * segs) {  // four loads in flight, added in order
+        const float v0 = col[(int64_t)b * stride], v1 = col[(int64_t)(b + segs) * stride];
+        const float v2 = col[(int64_t)(b + 2 * segs) * stride], v3 = col[(int64_t)(b + 3 * segs) * stride];
+        s += (double)v0; s += (double)v1; s += (double)v2; s += (double)v3;
+    }
+    for (; b < parts; b += segs) s += (double)col[(int64_t)b * stride];
+    seg_sum[t] = s;
     __syncthreads();
-    if (half == 0 && m < d) {
-        const double tot = half_sum[t] + half_sum[t + 128];
-        const int64_t cc = total_cnt;
+    if (seg == 0) {
+        double tot = seg_sum[m];
+        for (int q = 1; q < segs; ++q) tot += seg_sum[q * d + m];
+        const int64_t cc = (int64_t)total_cnt;
         const float cnew = cc > 0 ? (float)(tot / (double)cc) : C_prev[(int64_t)j * d + m];
         C_out[(int64_t)j * d + m] = cnew;
         cn[m] = cnew;
@@ -322,46 +464,48 @@ __global__ __launch_bounds__(kBlock) void lloyd_small_finalize_kernel(
         for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
         if (t == 0) {
             hneg[j] = (float)(-0.5 * acc);
-            counts[j] = total_cnt;
-            if (j == 0 && objective) {
-                double o = 0.0;
-                for (int b = 0; b < obj_parts; ++b) o += obj_part[b];
-                *objective = o;
-            }
+            counts[j] = (int64_t)total_cnt;
         }
+    } else if (t < 128 && j == 0 && objective) {  // second wave
+        write_objective(s_part, xsq_part, parts, fresh_xsq, xsq_total, objective, t - 64);
     }
 }
 
-__global__ void sum_obj_kernel(const double *__restrict__ part, int count, double *__restrict__ out) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        double t = 0.0;
-        for (int b = 0; b < count; ++b) t += part[b];
-        *out = t;
-    }
+// The objective of a stand-alone assignment: the same additions as in the finalize kernel.
+__global__ __launch_bounds__(64) void sum_obj_kernel(const double *__restrict__ s_part,
+                                                      const double *__restrict__ xsq_part, int parts,
+                                                      double *__restrict__ xsq_total, double *__restrict__ out) {
+    write_objective(s_part, xsq_part, parts, 1, xsq_total, out, threadIdx.x);
 }
 
 struct Geometry {
     int blocks;
-    int64_t subtiles_per_wg;
+    int64_t subtiles_per_wave;
 };
 
 Geometry geometry(int64_t n) {
     const int64_t total_sub = ceil_div(n, kSub);
-    int64_t wgs = std::min<int64_t>(kSmallMaxBlocks, ceil_div(total_sub, kWaves));
-    const int64_t per = ceil_div(total_sub, wgs);
-    return Geometry{(int)ceil_div(total_sub, per), per};
+    const int64_t wgs = std::min<int64_t>(kSmallMaxBlocks, ceil_div(total_sub, kWaves));
+    const int64_t per_wave = ceil_div(total_sub, wgs * kWaves);
+    return Geometry{(int)ceil_div(total_sub, per_wave * kWaves), per_wave};
 }
 
-template <int MODE>
+// Workspace slots inside KmeansWs::obj_part (kObjBlocksMax doubles).
+double *s_part_of(const KmeansWs &w) { return w.obj_part; }
+double *xsq_part_of(const KmeansWs &w) { return w.obj_part + kSmallMaxBlocks; }
+double *xsq_total_of(const KmeansWs &w) { return w.obj_part + 2 * kSmallMaxBlocks; }
+
+template <int MODE, bool XSQ>
 int launch_mode(const ep_problem &p, const float *X, const float *C, const KmeansWs &w, int32_t *labels_out,
                 const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
-    double *obj = want_obj ? w.obj_part : nullptr;
+    double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s);
-#define EP_SMALL_LAUNCH(D_, KT_)                                                                                   \
-    lloyd_small_kernel<D_, KT_, MODE><<<geo.blocks, kBlock, 0, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wg, X, C, w.cnorm, \
-                                                                    labels_out, labels_in, min_d2, w.psum, w.pcnt, obj)
+#define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
+    lloyd_small_kernel<D_, KT_, MODE, XSQ><<<geo.blocks, kBlock, 0, s>>>(                                     \
+        p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, w.cnorm, labels_out, labels_in, min_d2, w.psum, w.pcnt, sp, \
+        xsq_part_of(w))
     if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
     } else {
@@ -375,7 +519,7 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
 }  // namespace
 
 bool small_path_supported(const ep_problem &p) {
-    return p.dtype == EP_F32 && (p.d == 64 || p.d == 128) && p.k <= 64;
+    return p.dtype == EP_F32 && (p.d == 64 || p.d == 128) && p.k <= 64 && p.ld < ((int64_t)1 << 24);
 }
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }
@@ -388,38 +532,43 @@ int launch_small_half_norms(const ep_problem &p, const float *C, const KmeansWs 
 
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s) {
-    int rc = launch_mode<kAssignOnly>(p, static_cast<const float *>(X), C, w, labels, nullptr, min_d2,
-                                      objective != nullptr, s);
+    const float *Xf = static_cast<const float *>(X);
+    int rc = objective ? launch_mode<kAssignOnly, true>(p, Xf, C, w, labels, nullptr, min_d2, true, s)
+                       : launch_mode<kAssignOnly, false>(p, Xf, C, w, labels, nullptr, min_d2, false, s);
     if (rc != EP_OK) return rc;
     if (objective) {
-        sum_obj_kernel<<<1, 64, 0, s>>>(w.obj_part, small_blocks(p), objective);
+        sum_obj_kernel<<<1, 64, 0, s>>>(s_part_of(w), xsq_part_of(w), small_blocks(p), xsq_total_of(w), objective);
         EP_LAUNCH_CHECK();
     }
     return EP_OK;
 }
 
-int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
-                          const KmeansWs &w, double *objective, hipStream_t s) {
+static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
+                                 const KmeansWs &w, double *objective, bool fresh_xsq, hipStream_t s) {
     const int parts = small_blocks(p);
-    lloyd_small_finalize_kernel<<<p.k, kBlock, 0, s>>>(p.d, p.k, parts, w.psum, w.pcnt, w.obj_part, parts, C_prev,
-                                                       C_out, counts, w.cnorm, objective);
+    lloyd_small_finalize_kernel<<<p.k, kFinBlock, 0, s>>>(p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w),
+                                                          xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
+                                                          C_out, counts, w.cnorm, objective);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
 
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
-    int rc = launch_mode<kUpdateOnly>(p, static_cast<const float *>(X), nullptr, w, nullptr, labels, nullptr, false, s);
+    int rc = launch_mode<kUpdateOnly, false>(p, static_cast<const float *>(X), nullptr, w, nullptr, labels, nullptr,
+                                             false, s);
     if (rc != EP_OK) return rc;
-    return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, s);
+    return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, s);
 }
 
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
-                       int64_t *counts, double *objective, hipStream_t s) {
-    int rc = launch_mode<kFused>(p, static_cast<const float *>(X), C, w, labels, nullptr, nullptr,
-                                 objective != nullptr, s);
+                       int64_t *counts, double *objective, bool first_round, hipStream_t s) {
+    const float *Xf = static_cast<const float *>(X);
+    const bool fresh = objective && first_round;  // sum ||x||^2 is computed in the first round and kept
+    int rc = fresh ? launch_mode<kFused, true>(p, Xf, C, w, labels, nullptr, nullptr, true, s)
+                   : launch_mode<kFused, false>(p, Xf, C, w, labels, nullptr, nullptr, objective != nullptr, s);
     if (rc != EP_OK) return rc;
-    return launch_small_finalize(p, C, C, counts, w, objective, s);
+    return launch_small_finalize(p, C, C, counts, w, objective, fresh, s);
 }
 
 }  // namespace ep
