@@ -148,7 +148,7 @@ int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host)
 /*
  * Quality of a partition over a CSR graph, in integers.
  *   rowptr   n + 1 offsets, int32 or int64 (rowptr_is_i64), rowptr[n] == nnz
- *   colidx   nnz int32 column indices in [0, n)
+ *   colidx   nnz int32 column indices in [0, n), 16-byte aligned
  *   labels   n int32 partition ids in [0, k)
  *   cut      1 int64, written: stored entries (u,v) with labels[u] != labels[v]
  *            (an undirected edge stored in both directions counts twice; divide

@@ -78,7 +78,7 @@ int do_update(const ep_problem &p, const void *X, const int32_t *labels, const f
 
 int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colidx) {
     if (n < 1 || n >= EP_MAX_N || nnz < 0 || !rowptr || (nnz > 0 && !colidx)) return EP_EINVAL;
-    if (!aligned(rowptr, 8) || !aligned(colidx, 4)) return EP_EINVAL;
+    if (!aligned(rowptr, 8) || !aligned(colidx, 16)) return EP_EINVAL;
     return EP_OK;
 }
 

@@ -58,6 +58,7 @@ struct GraphWs {
     int32_t *sort_hist;   // [kSortBlocksMax * 256]
     int32_t *order_tmp;   // [n]
     int32_t *order_tmp2;  // [n]
+    uint8_t *label8;      // [n] byte copy of the labels for the cut sweep (k <= 255)
     size_t bytes;
 };
 constexpr int kGraphBlocksMax = 8192;
