@@ -27,7 +27,10 @@ sys.path.insert(0, str(ROOT))
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/), scaled by the copy-kernel calibration; None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "arxiv_like": 89_732_715,        # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
+    "products_like": 1_268_679_032,  # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
+}
 
 
 class HipEvents:
@@ -53,28 +56,15 @@ class HipEvents:
             self.hip.hipEventDestroy(C.c_void_p(ev))
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="arxiv_like",
-                    help="tiny | arxiv_like | products_like | products_reorder | papers_like")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        return 2
-
+def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict:
     import numpy as np
     import torch
 
     from paper_2604_01000_amd import embedpart as ep
     from paper_2604_01000_amd import synth
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    w = synth.WORKLOADS[args.workload]
+    w = synth.WORKLOADS[name]
     reorder = w.name == "products_reorder"
 
     # ---- inputs, resident in HBM before anything is timed ----
@@ -105,29 +95,48 @@ def main() -> int:
             ep.partition_permutation(w.n, w.k, labels, new_id, order, gws)
             ep.edge_gap_sum(w.n, nnz, rowptr, colidx, new_id, gap, gws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = w.n * w.iters / (elapsed / args.steps) / 1e6
+    ms_per_step = 1e3 * elapsed / steps
+    value = w.n * w.iters / (elapsed / steps) / 1e6
 
-    # ---- second pass of the same steps with events around the kernel that reads X each round ----
-    launches = args.steps * w.iters
-    evs = HipEvents(2 * launches)
-    assert ep.lib().ep_profile_arm(evs.arr, 2 * launches, ep.EP_PROF_LLOYD_MAIN) == 0
-    for _ in range(args.steps):
-        step()
+    def timed_kernels(kernel_class: int, launches_per_step: int) -> float:
+        """Mean duration (ms) of one kernel class over a further pass of the same steps."""
+        launches = steps * launches_per_step
+        evs = HipEvents(2 * launches)
+        assert ep.lib().ep_profile_arm(evs.arr, 2 * launches, kernel_class) == 0
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        seen = ep.lib().ep_profile_count()
+        ep.lib().ep_profile_arm(None, 0, 0)
+        assert seen == launches, (seen, launches)
+        ms = float(np.mean([evs.elapsed_ms(2 * i, 2 * i + 1) for i in range(launches)]))
+        evs.destroy()
+        return ms
+
+    # ---- further passes of the same steps with events around one kernel class at a time ----
+    kernel_ms = timed_kernels(ep.EP_PROF_LLOYD_MAIN, w.iters)
+    sweep_ms = timed_kernels(ep.EP_PROF_EDGE_SWEEP, 2 if reorder else 1)
+
+    # ---- copy bandwidth of this machine, for context: a plain 16-byte-per-lane copy of X ----
+    Y = torch.empty_like(X)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ep.ep_bench_copy(Y, X)
+    a.record()
+    for _ in range(5):
+        ep.ep_bench_copy(Y, X)
+    b.record()
     torch.cuda.synchronize()
-    seen = ep.lib().ep_profile_count()
-    ep.lib().ep_profile_arm(None, 0, 0)
-    assert seen == launches, (seen, launches)
-    kernel_ms = float(np.mean([evs.elapsed_ms(2 * i, 2 * i + 1) for i in range(launches)]))
-    evs.destroy()
+    copy_ms = a.elapsed_time(b) / 5
+    x_bytes = X.numel() * X.element_size()
+    del Y
 
     elem = 2 if w.dtype == "bf16" else 4
     if reorder:   # dense contraction on the matrix cores: 2*n*k*d flop per launch
@@ -140,6 +149,10 @@ def main() -> int:
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
     roofline["kernel_ms"] = kernel_ms
     roofline["kernel"] = "lloyd round kernel that reads X (EP_PROF_LLOYD_MAIN)"
+    sweep_bytes = 4 * nnz + rowptr.element_size() * (w.n + 1) + 4 * w.n
+    reference = dict(copy_GBs=2 * x_bytes / (copy_ms * 1e-3) / 1e9, copy_bytes_moved=2 * x_bytes,
+                     edge_sweep_ms=sweep_ms, edge_sweep_GBs=sweep_bytes / (sweep_ms * 1e-3) / 1e9,
+                     edge_sweep_Gentries_per_s=nnz / (sweep_ms * 1e-3) / 1e9)
 
     torch.cuda.synchronize()
     result_labels = labels.cpu().numpy()
@@ -150,7 +163,7 @@ def main() -> int:
 
     # ---- the oracle on this machine's host cores ----
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         sample_n = min(w.n, 1 << 18 if w.k > 64 else 1 << 22)
         sample_iters = w.iters if w.k <= 64 else 1
@@ -163,14 +176,40 @@ def main() -> int:
         cpu = dict(value=sample_n * sample_iters / dt / 1e6, unit="Mpts*iter/s", cores=oracle.threads(), kind="oracle",
                    sample=f"first {sample_n} rows of the workload, k={kk}, {sample_iters} Lloyd rounds, {dt:.1f} s")
 
-    out = dict(metric="kmeans_point_iterations_per_s", value=value, unit="Mpts*iter/s", n_gpus=1, steps=args.steps,
-               warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="bf16" if w.dtype == "bf16" else "f32", data="synthetic",
-               config=dict(workload=w.name, n=w.n, d=w.d, k=w.k, iters=w.iters, nnz=nnz,
-                           step="kmeans_init + kmeans_run + partition_quality" +
-                                (" + partition_permutation + edge_gap_sum" if reorder else "")),
-               roofline=roofline, cpu_baseline=cpu, quality=quality,
-               labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
+    return dict(metric="kmeans_point_iterations_per_s", value=value, unit="Mpts*iter/s", n_gpus=1, steps=steps,
+                warmup=warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
+                dtype="bf16" if w.dtype == "bf16" else "f32", data="synthetic",
+                config=dict(workload=w.name, n=w.n, d=w.d, k=w.k, iters=w.iters, nnz=nnz,
+                            step="kmeans_init + kmeans_run + partition_quality" +
+                                 (" + partition_permutation + edge_gap_sum" if reorder else "")),
+                roofline=roofline, cpu_baseline=cpu, reference=reference, quality=quality,
+                labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="arxiv_like",
+                    help="tiny | arxiv_like | products_like | products_reorder | papers_like")
+    ap.add_argument("--also", default="products_like",
+                    help="comma-separated further workloads reported under 'more' (fewer steps); '' for none")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    out = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    more = []
+    for name in [v for v in args.also.split(",") if v and v != args.workload]:
+        torch.cuda.empty_cache()
+        more.append(run_workload(name, max(3, args.steps // 4), 1, False))
+    if more:
+        out["more"] = more
     print(json.dumps(out))
     return 0
 

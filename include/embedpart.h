@@ -202,6 +202,14 @@ int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_
 int ep_profile_arm(void **events_host, int capacity, int kernel_class);
 int ep_profile_count(void);
 
+/*
+ * Benchmark aid: plain streaming copy of `bytes` bytes (a multiple of 16, both pointers 16-byte
+ * aligned) with 16-byte loads and stores.  It gives benchmarks a kernel of exactly known traffic
+ * (bytes read + bytes written) to calibrate hardware counters and to quote the copy bandwidth of
+ * the machine at hand next to the roofline figures.
+ */
+int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -116,6 +116,11 @@ int ep_profile_arm(void **events_host, int capacity, int kernel_class) {
 
 int ep_profile_count(void) { return g_prof_count; }
 
+int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return EP_EINVAL;
+    return launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
 int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host) {
     if (!idx_host || n < 1 || k < 1 || (int64_t)k > n) return EP_EINVAL;
     uint64_t state = seed;

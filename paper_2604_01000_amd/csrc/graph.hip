@@ -34,6 +34,12 @@ __device__ __forceinline__ uint64_t block_sum_u64(uint64_t v, uint64_t *lds /* k
     return total;
 }
 
+__global__ __launch_bounds__(kBlock) void ep_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                          int64_t count) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += stride) dst[i] = src[i];
+}
+
 __global__ void fill_i64_kernel(int64_t *a, int64_t na, int64_t *b, int64_t nb) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < na) a[i] = 0;
@@ -376,6 +382,15 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(int64_t n, int64_t
 }
 
 }  // namespace
+
+int launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
+    const int64_t count = (int64_t)(bytes / 16);
+    if (count == 0) return EP_OK;
+    const unsigned grid = (unsigned)std::min<int64_t>(ceil_div(count, kBlock), 256 * 16);
+    ep_copy_kernel<<<grid, kBlock, 0, s>>>(static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), count);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
 
 size_t sort_hist_elems() { return (size_t)kSortBlocksMax * kRadix; }
 

@@ -22,7 +22,7 @@ SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
     "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
-    "ep_profile_arm", "ep_profile_count",
+    "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
 
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.edge_gap_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.vertex_bandwidth_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
+        L.ep_bench_copy.argtypes = [vp, vp, sz, vp]
         for name in SYMBOLS:
             if name not in ("ep_strerror",):
                 getattr(L, name).restype = C.c_int
@@ -177,3 +178,10 @@ def edge_gap_sum(n, nnz, rowptr, colidx, new_id, gap_sum, ws):
 def vertex_bandwidth_sum(n, nnz, rowptr, colidx, new_id, bw_sum, ws):
     _check(lib().vertex_bandwidth_sum(n, nnz, _ptr(rowptr), _is_i64(rowptr), _ptr(colidx), _ptr(new_id),
                                       _ptr(bw_sum), _ptr(ws), ws.numel(), _stream()), "vertex_bandwidth_sum")
+
+
+def ep_bench_copy(dst, src):
+    """Plain device copy of src into dst (same size, multiple of 16 bytes): a kernel of known traffic."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().ep_bench_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "ep_bench_copy")
