@@ -64,6 +64,7 @@ int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs
         if (rc != EP_OK) return rc;
         return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
     }
+    if (large_path_supported(p)) return launch_large_assign(p, X, C, w, labels, min_d2, objective, s);
     int rc = launch_prep_centroids(p, C, w, s);
     if (rc != EP_OK) return rc;
     return launch_assign_generic(p, X, C, w, labels, min_d2, objective, s);

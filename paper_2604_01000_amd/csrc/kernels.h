@@ -22,6 +22,8 @@ struct KmeansWs {
     int32_t *order_tmp;   // [n]
     int64_t *seg;         // [k+1] segment offsets               (large k)
     int32_t *sort_hist;   // radix-sort block histograms
+    unsigned char *records;  // centroid tile records of the large-k matrix-core path
+    int32_t *best_tile;   // [n] code of the 4 candidate centroid rows per point (large-k path)
     size_t bytes;
 };
 KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws);
@@ -50,6 +52,13 @@ int launch_small_update(const ep_problem &p, const void *X, const int32_t *label
 // workspace; later rounds of the same kmeans_run reuse it.
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
                        int64_t *counts, double *objective, bool first_round, hipStream_t s);
+
+// ---- K-Means, k > 64, bf16, d in {64,128}: bf16 matrix-core assignment (kmeans_large.hip) -------
+bool large_path_supported(const ep_problem &p);
+size_t large_record_bytes(const ep_problem &p);
+// Rounds C to bf16 (w.cq16), leaves -||c||^2/2 in w.cnorm, then labels / min_d2 / objective.
+int launch_large_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                        float *min_d2, double *objective, hipStream_t s);
 
 // ---- graph kernels (graph.hip) ---------------------------------------------------
 constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass

@@ -287,6 +287,10 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
         w.seg = c.take<int64_t>((size_t)p.k + 1);
         w.sort_hist = c.take<int32_t>(sort_hist_elems());
     }
+    if (large_path_supported(p)) {
+        w.records = c.take<unsigned char>(large_record_bytes(p));
+        w.best_tile = c.take<int32_t>((size_t)p.n);
+    }
     w.bytes = align_up(c.used, 256);
     return w;
 }

@@ -1,0 +1,393 @@
+// Assignment step for reordering-scale k (hundreds to 65,536 clusters), bf16 embeddings, d in
+// {64, 128}: x.c on the bf16 matrix cores with the arg-max folded into the product's epilogue,
+// so the n x k score matrix (160 GB at n = 2.45 M, k = 16,384) never exists.
+//
+// What it computes (EmbedPart paper, Alg. 3, step P <- KMeans(E, k), used at large k for the
+// reordering of Sec. "Adapting EmbedPart for Reordering"): labels[i] = argmin_j ||x_i - c_j||^2
+// = argmax_j (x_i.c_j - ||c_j||^2 / 2), lowest j on ties, with the centroids rounded to bf16 for
+// the products and fp32 accumulation.
+//
+// Three kernels:
+//  1. large_prep_kernel: rounds the centroids to bf16, forms -||c||^2/2 from the rounded values
+//     (fp64 accumulation) and writes one "tile record" per 32 centroids: the 32 x d block already
+//     in the lane order of the matrix instruction's operand (so staging is a straight copy and LDS
+//     reads are conflict-free) followed by the 32 biases.
+//  2. large_assign_kernel: a wave keeps 128 points (4 operand tiles of 32) in registers and walks
+//     all centroid tiles; records are staged through a 3-deep LDS ring shared by the 4 waves of a
+//     workgroup.  v_mfma_f32_32x32x16_bf16 with centroids as rows and points as columns leaves
+//     16 centroids of one point in each lane, as 4 groups of 4 consecutive rows.  Per tile and
+//     point the epilogue takes the 4 group maxima and their maximum, and keeps (best score, tile,
+//     group maxima) with one compare and selects: about one VALU operation per score, no
+//     per-score index bookkeeping.  The accumulators are preset to the bias from LDS.
+//  3. large_refine_kernel: the sweep names, per point, 4 consecutive centroid rows that hold the
+//     winner; they are evaluated again on the vector unit (v_dot2_f32_bf16) to name the winner
+//     itself (lowest index on ties) and to produce ||x - c||^2 for the objective: 1/4096 of the
+//     work of step 2, and 1 KB of centroid data per point instead of the whole tile.
+#include <algorithm>
+
+#include "kernels.h"
+
+namespace ep {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;
+constexpr int kWaves = 4;
+constexpr int kTile = 32;            // centroids per tile record, points per operand tile
+#ifndef EP_LARGE_POINT_TILES
+#define EP_LARGE_POINT_TILES 4
+#endif
+#ifndef EP_LARGE_OCC
+#define EP_LARGE_OCC 2
+#endif
+constexpr int kPointTiles = EP_LARGE_POINT_TILES;  // operand tiles of points a wave keeps in registers
+constexpr int kPointsPerWave = kTile * kPointTiles;
+constexpr int kPair = kPointTiles % 2 == 0 ? 2 : 1;  // point tiles accumulated together
+constexpr float kNever = -3.0e38f;   // bias of a padding centroid
+
+template <int D> constexpr int record_bytes() { return (D / 16) * 1024 + kTile * 4; }
+
+// ---- 1. tile records ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void large_prep_kernel(int32_t k, const float *__restrict__ C,
+                                                             bf16_t *__restrict__ cq16, float *__restrict__ hneg,
+                                                             unsigned char *__restrict__ records) {
+    constexpr int NS = D / 16;
+    __shared__ bf16_t rows[kTile][D + 8];
+    __shared__ float bias[kTile];
+    const int t = threadIdx.x, tile = blockIdx.x;
+    {   // 8 threads per centroid row, D/8 columns each; the norm is summed in fp64 in a fixed order
+        const int r = t >> 3, part = t & 7;
+        const int cent = tile * kTile + r;
+        double acc = 0.0;
+        for (int m = part * (D / 8); m < (part + 1) * (D / 8); ++m) {
+            bf16_t q = 0;
+            if (cent < k) {
+                q = f32_to_bf16_rne(C[(int64_t)cent * D + m]);
+                cq16[(int64_t)cent * D + m] = q;
+            }
+            rows[r][m] = q;
+            const double v = (double)bf16_to_f32(q);
+            acc += v * v;
+        }
+        acc += __shfl_xor(acc, 1, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        acc += __shfl_xor(acc, 4, 64);
+        if (part == 0) {
+            const float h = cent < k ? (float)(-0.5 * acc) : kNever;
+            bias[r] = h;
+            if (cent < k) hneg[cent] = h;
+        }
+    }
+    __syncthreads();
+    unsigned char *rec = records + (int64_t)tile * record_bytes<D>();
+    // operand order: piece (s, L) = row L % 32, columns 16 s + 8 (L / 32) .. + 7, at byte (64 s + L) * 16
+    for (int piece = t; piece < NS * 64; piece += kBlock) {
+        const int s = piece >> 6, L = piece & 63;
+        const bf16_t *src = &rows[L & 31][16 * s + 8 * (L >> 5)];
+        uint4 v;
+        v.x = src[0] | ((uint32_t)src[1] << 16);
+        v.y = src[2] | ((uint32_t)src[3] << 16);
+        v.z = src[4] | ((uint32_t)src[5] << 16);
+        v.w = src[6] | ((uint32_t)src[7] << 16);
+        *reinterpret_cast<uint4 *>(rec + (int64_t)piece * 16) = v;
+    }
+    if (t < kTile) reinterpret_cast<float *>(rec + NS * 1024)[t] = bias[t];
+}
+
+// ---- 2. matrix-core sweep ------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int64_t n, int64_t ld, int32_t tiles,
+                                                                  const bf16_t *__restrict__ X,
+                                                                  const unsigned char *__restrict__ records,
+                                                                  int32_t *__restrict__ best_code) {
+    constexpr int NS = D / 16;
+    constexpr int REC = record_bytes<D>();
+    constexpr int REC16 = REC / 16;                    // 16-byte pieces per record
+    constexpr int STAGE = (REC16 + kBlock - 1) / kBlock;  // pieces per thread
+    __shared__ __attribute__((aligned(16))) unsigned char ring[3][REC];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
+
+    const int64_t wave_blocks = (n + kPointsPerWave - 1) / kPointsPerWave;
+    const int64_t wg_blocks = (wave_blocks + kWaves - 1) / kWaves;
+
+    auto stage_load = [&](int tile, uint4(&regs)[STAGE]) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(records + (int64_t)tile * REC);
+#pragma unroll
+        for (int q = 0; q < STAGE; ++q) {
+            const int piece = q * kBlock + threadIdx.x;
+            regs[q] = piece < REC16 ? src[piece] : uint4{0, 0, 0, 0};
+        }
+    };
+    auto stage_store = [&](int slot, const uint4(&regs)[STAGE]) {
+        uint4 *dst = reinterpret_cast<uint4 *>(ring[slot]);
+#pragma unroll
+        for (int q = 0; q < STAGE; ++q) {
+            const int piece = q * kBlock + threadIdx.x;
+            if (piece < REC16) dst[piece] = regs[q];
+        }
+    };
+
+    for (int64_t wb = blockIdx.x; wb < wg_blocks; wb += gridDim.x) {
+        const int64_t row0 = (wb * kWaves + wave) * kPointsPerWave;
+        // Point operand: piece (p, s) of lane (half, col) = row row0 + 32 p + col, columns 16 s + 8 half .. + 7.
+        // Buffer loads with a descriptor that ends at the last valid row: rows past n read as zeros.
+        bf16x8 xb[kPointTiles][NS];
+        {
+            const int64_t rows_here = min((int64_t)kPointsPerWave, n - row0);
+            const bool live = rows_here > 0;
+            const int bytes = live ? (int)(((rows_here - 1) * ld + D) * 2) : 0;
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<bf16_t *>(X + (live ? row0 : 0) * ld), 0, bytes, 0x00020000);
+#pragma unroll
+            for (int p = 0; p < kPointTiles; ++p) {
+                const int voff = (int)(((32 * p + col) * ld + 8 * half) * 2);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 32 * s, 0);
+                    xb[p][s] = __builtin_bit_cast(bf16x8, raw);
+                }
+            }
+        }
+        float best[kPointTiles], bquad[kPointTiles][4];   // best score, and the group maxima of the tile it came from
+        int32_t btile[kPointTiles];
+#pragma unroll
+        for (int p = 0; p < kPointTiles; ++p) {
+            best[p] = kNever;
+            btile[p] = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bquad[p][j] = kNever;
+        }
+
+        // ring prologue: records 0 and 1
+        __syncthreads();  // the previous block's readers are done with the ring
+        {
+            uint4 regs[STAGE];
+            stage_load(0, regs);
+            stage_store(0, regs);
+            if (tiles > 1) {
+                stage_load(1, regs);
+                stage_store(1, regs);
+            }
+        }
+        __syncthreads();
+
+        for (int t = 0; t < tiles; ++t) {
+            uint4 staged[STAGE];
+            const bool more = t + 2 < tiles;
+            if (more) stage_load(t + 2, staged);
+
+            const unsigned char *rec = ring[t % 3];
+            // bias of the 16 centroid rows this lane's accumulators stand for (rows 8 (v/4) + 4 half + v%4):
+            // read straight into the accumulators of every pair, so it occupies no registers of its own
+            auto load_bias = [&]() {
+                f32x16 b;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 b4 = *reinterpret_cast<const f32x4 *>(rec + NS * 1024 + (8 * q + 4 * half) * 4);
+                    b[4 * q + 0] = b4[0];
+                    b[4 * q + 1] = b4[1];
+                    b[4 * q + 2] = b4[2];
+                    b[4 * q + 3] = b4[3];
+                }
+                return b;
+            };
+            // The centroid operand of the whole tile stays in registers while the point tiles are
+            // taken two at a time, so only two accumulators are live at once.
+            bf16x8 a[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(rec + (64 * s + lane) * 16);
+#pragma unroll
+            for (int p0 = 0; p0 < kPointTiles; p0 += kPair) {
+                f32x16 acc[kPair];
+#pragma unroll
+                for (int q = 0; q < kPair; ++q) acc[q] = load_bias();
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int q = 0; q < kPair; ++q)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], xb[p0 + q][s], acc[q], 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < kPair; ++q) {
+                    // maxima of the four groups of 4 accumulators (4 consecutive centroid rows each)
+                    float qm[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        qm[j] = fmaxf(fmaxf(acc[q][4 * j], acc[q][4 * j + 1]), fmaxf(acc[q][4 * j + 2], acc[q][4 * j + 3]));
+                    const float m = fmaxf(fmaxf(qm[0], qm[1]), fmaxf(qm[2], qm[3]));
+                    const bool better = m > best[p0 + q];   // strict: the earliest tile keeps a tie
+                    best[p0 + q] = better ? m : best[p0 + q];
+                    btile[p0 + q] = better ? t : btile[p0 + q];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) bquad[p0 + q][j] = better ? qm[j] : bquad[p0 + q][j];
+                }
+            }
+            if (more) stage_store((t + 2) % 3, staged);
+            __syncthreads();
+        }
+
+        // Name the group of 4 consecutive centroid rows that holds the winner: code = 8 tile + 2 group + half
+        // (rows 8 group + 4 half .. + 3 of the tile).  Codes ascend with the centroid index, so the
+        // smaller code wins a tie, here and between the two halves of a column.
+#pragma unroll
+        for (int p = 0; p < kPointTiles; ++p) {
+            const int grp = bquad[p][0] == best[p] ? 0 : bquad[p][1] == best[p] ? 1 : bquad[p][2] == best[p] ? 2 : 3;
+            int32_t code = 8 * btile[p] + 2 * grp + half;
+            const float ob = __shfl_xor(best[p], 32, 64);
+            const int32_t oc = __shfl_xor(code, 32, 64);
+            if (ob > best[p] || (ob == best[p] && oc < code)) { best[p] = ob; code = oc; }
+            const int64_t row = row0 + 32 * p + col;
+            if (half == 0 && row < n) best_code[row] = code;
+        }
+    }
+}
+
+// ---- 3. winner inside the winning tile, distance, objective -------------------------------------
+// 32 lanes per point.  The sweep names 4 consecutive centroid rows (4 * d contiguous bf16 values);
+// they are read 512 bytes at a time across the 32 lanes, and the d/8 lanes that hold one
+// centroid's pieces add their partial products with DPP row operations.  Rows come by in
+// ascending order for every lane, so a strict > keeps the lowest index inside a lane group; the
+// groups are merged with the same rule.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int LANES>  // sum over aligned groups of LANES (<= 16) consecutive lanes
+__device__ __forceinline__ float group_sum(float v) {
+    if (LANES >= 2) v = dpp_add<0xB1>(v);    // xor 1
+    if (LANES >= 4) v = dpp_add<0x4E>(v);    // xor 2
+    if (LANES >= 8) v = dpp_add<0x141>(v);   // mirror within 8
+    if (LANES >= 16) v = dpp_add<0x140>(v);  // mirror within 16
+    return v;
+}
+__device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b, float acc) {
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), acc, false);
+    return acc;
+}
+
+template <int D>
+__global__ __launch_bounds__(kBlock) void large_refine_kernel(int64_t n, int64_t ld, int32_t k,
+                                                               const bf16_t *__restrict__ X,
+                                                               const bf16_t *__restrict__ cq16,
+                                                               const float *__restrict__ hneg,
+                                                               const int32_t *__restrict__ best_code,
+                                                               int32_t *__restrict__ labels,
+                                                               float *__restrict__ min_d2,
+                                                               double *__restrict__ obj_part) {
+    constexpr int CH = D / 8;          // 16-byte pieces per row = lanes per centroid
+    constexpr int ROWS = 32 / CH;      // centroid rows covered by one 512-byte read
+    constexpr int CAND = 4;            // candidate rows named by the sweep
+    __shared__ double red[kBlock / 64];
+    const int r = threadIdx.x & 31;
+    const int chunk = r % CH, sub = r / CH;
+    const int64_t group = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 5;
+    const int64_t groups = ((int64_t)gridDim.x * kBlock) >> 5;
+    double obj = 0.0;
+    for (int64_t i0 = 0; i0 < n; i0 += groups) {   // uniform trip count: the lane exchanges need every lane
+        const int64_t i = i0 + group;
+        const bool valid = i < n;
+        const int code = valid ? best_code[i] : 0;
+        const uint4 xc = *reinterpret_cast<const uint4 *>(X + (valid ? i : 0) * ld + 8 * chunk);
+        // candidates: rows 8 group + 4 half .. + 3 of tile code / 8
+        const int64_t first_row = (int64_t)(code >> 3) * kTile + 8 * ((code >> 1) & 3) + 4 * (code & 1);
+        const uint4 *base = reinterpret_cast<const uint4 *>(cq16 + first_row * D);
+        float best = kNever;
+        int bidx = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < (CAND + ROWS - 1) / ROWS; ++q) {
+            const int row = q * ROWS + sub;
+            const bool real = row < CAND && first_row + row < k;   // rows of the padded last tile are never read
+            const uint4 cc = real ? base[q * 32 + r] : uint4{0, 0, 0, 0};
+            const float dot = group_sum<CH>(dot8(xc, cc, 0.f));
+            const float score = real ? dot + hneg[first_row + row] : kNever;
+            if (score > best) { best = score; bidx = (int)(first_row + row); }
+        }
+#pragma unroll
+        for (int off = CH; off < 32; off <<= 1) {   // merge the lane groups (different rows)
+            const float os = __shfl_xor(best, off, 64);
+            const int oi = __shfl_xor(bidx, off, 64);
+            if (os > best || (os == best && oi < bidx)) { best = os; bidx = oi; }
+        }
+        const float xx = group_sum<CH>(dot8(xc, xc, 0.f));
+        if (valid && r == 0) {
+            labels[i] = bidx;
+            const float d2 = fmaxf(xx - 2.f * best, 0.f);
+            if (min_d2) min_d2[i] = d2;
+            obj += (double)d2;
+        }
+    }
+    if (obj_part) {
+        for (int off = 32; off > 0; off >>= 1) obj += __shfl_down(obj, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = obj;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+            obj_part[blockIdx.x] = t;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void large_sum_obj_kernel(const double *__restrict__ part, int count,
+                                                            double *__restrict__ out) {
+    const int l = threadIdx.x;
+    double o = 0.0;
+    for (int q = l; q < count; q += 64) o += part[q];
+    for (int off = 32; off > 0; off >>= 1) o += __shfl_down(o, off, 64);
+    if (l == 0) *out = o;
+}
+
+template <int D>
+int launch_large(const ep_problem &p, const bf16_t *X, const float *C, const KmeansWs &w, int32_t *labels,
+                 float *min_d2, double *objective, hipStream_t s) {
+    const int tiles = (int)ceil_div(p.k, kTile);
+    large_prep_kernel<D><<<tiles, kBlock, 0, s>>>(p.k, C, w.cq16, w.cnorm, w.records);
+    EP_LAUNCH_CHECK();
+    {
+        const int64_t wg_blocks = ceil_div(ceil_div(p.n, kPointsPerWave), kWaves);
+        const int grid = (int)std::min<int64_t>(wg_blocks, 256 * EP_LARGE_OCC);
+        ProfScope prof(EP_PROF_LLOYD_MAIN, s);
+        large_assign_kernel<D><<<grid, kBlock, 0, s>>>(p.n, p.ld, tiles, X, w.records, w.best_tile);
+        EP_LAUNCH_CHECK();
+    }
+    const int blocks = (int)std::min<int64_t>(kObjBlocksMax, ceil_div(p.n, kBlock / 32));
+    large_refine_kernel<D><<<blocks, kBlock, 0, s>>>(p.n, p.ld, p.k, X, w.cq16, w.cnorm, w.best_tile, labels, min_d2,
+                                                     objective ? w.obj_part : nullptr);
+    EP_LAUNCH_CHECK();
+    if (objective) {
+        large_sum_obj_kernel<<<1, 64, 0, s>>>(w.obj_part, blocks, objective);
+        EP_LAUNCH_CHECK();
+    }
+    return EP_OK;
+}
+
+}  // namespace
+
+bool large_path_supported(const ep_problem &p) {
+    return p.dtype == EP_BF16 && (p.d == 64 || p.d == 128) && p.k > 64 && p.ld < ((int64_t)1 << 23);
+}
+
+size_t large_record_bytes(const ep_problem &p) {
+    return (size_t)ceil_div(p.k, kTile) * (p.d == 128 ? record_bytes<128>() : record_bytes<64>());
+}
+
+int launch_large_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                        float *min_d2, double *objective, hipStream_t s) {
+    const bf16_t *Xb = static_cast<const bf16_t *>(X);
+    return p.d == 128 ? launch_large<128>(p, Xb, C, w, labels, min_d2, objective, s)
+                      : launch_large<64>(p, Xb, C, w, labels, min_d2, objective, s);
+}
+
+}  // namespace ep

@@ -12,7 +12,9 @@ from pathlib import Path
 
 import torch
 
-_LIB_PATH = Path(__file__).resolve().parent / "libembedpart.so"
+import os as _os
+
+_LIB_PATH = Path(__file__).resolve().parent / _os.environ.get("EP_LIB_VARIANT", "libembedpart.so")
 
 EP_F32, EP_BF16 = 0, 1
 EP_RUN_FINAL_REASSIGN = 1
