@@ -313,20 +313,20 @@ __global__ __launch_bounds__(kBlock) void sort_hist_kernel(int64_t n, int64_t ro
     hist[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];  // digit-major
 }
 
-// Exclusive scan, in place, of hist[256][blocks] read as one sequence (digit-major, so the
-// result is the first output position of each (digit, block) pair).  One workgroup: every thread
-// sums a contiguous chunk, the chunk sums are scanned through LDS, then the chunk is rewritten.
-constexpr int kScanThreads = 1024;
-__global__ __launch_bounds__(kScanThreads) void sort_scan_kernel(int32_t *__restrict__ hist, int total) {
-    __shared__ int32_t part[kScanThreads];
+// hist is [256][blocks] (digit-major).  Workgroup d scans row d in place (exclusive) and writes the
+// row total; the scatter kernel adds the totals of the lower digits itself.
+__global__ __launch_bounds__(kRadix) void sort_scan_kernel(int32_t *__restrict__ hist, int blocks,
+                                                            int32_t *__restrict__ digit_total) {
+    __shared__ int32_t part[kRadix];
     const int t = threadIdx.x;
-    const int chunk = (total + kScanThreads - 1) / kScanThreads;
-    const int b = min(t * chunk, total), e = min(b + chunk, total);
+    int32_t *row = hist + (int64_t)blockIdx.x * blocks;
+    const int chunk = (blocks + kRadix - 1) / kRadix;
+    const int b = min(t * chunk, blocks), e = min(b + chunk, blocks);
     int32_t sum = 0;
-    for (int i = b; i < e; ++i) sum += hist[i];
+    for (int i = b; i < e; ++i) sum += row[i];
     part[t] = sum;
     __syncthreads();
-    for (int off = 1; off < kScanThreads; off <<= 1) {  // inclusive scan of the chunk sums
+    for (int off = 1; off < kRadix; off <<= 1) {  // inclusive scan of the chunk sums
         const int32_t add = t >= off ? part[t - off] : 0;
         __syncthreads();
         part[t] += add;
@@ -334,22 +334,37 @@ __global__ __launch_bounds__(kScanThreads) void sort_scan_kernel(int32_t *__rest
     }
     int32_t run = part[t] - sum;
     for (int i = b; i < e; ++i) {
-        const int32_t c = hist[i];
-        hist[i] = run;
+        const int32_t c = row[i];
+        row[i] = run;
         run += c;
     }
+    if (t == kRadix - 1) digit_total[blockIdx.x] = part[t];
 }
 
 __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(int64_t n, int64_t rows_per_block,
                                                                const int32_t *__restrict__ labels,
                                                                const int32_t *__restrict__ order_in, int shift,
                                                                const int32_t *__restrict__ offsets,
+                                                               const int32_t *__restrict__ digit_total,
                                                                int32_t *__restrict__ order_out,
                                                                int32_t *__restrict__ new_id) {
     __shared__ int32_t running[kRadix];
     __shared__ int32_t wcnt[kSortWaves][kRadix];
     const int t = threadIdx.x, wave = t >> 6;
-    running[t] = offsets[(int64_t)t * gridDim.x + blockIdx.x];
+    {   // first output position of digit t: the totals of the digits below it (exclusive scan in LDS)
+        const int32_t mine = digit_total[t];
+        running[t] = mine;
+        __syncthreads();
+        for (int off = 1; off < kRadix; off <<= 1) {
+            const int32_t add = t >= off ? running[t - off] : 0;
+            __syncthreads();
+            running[t] += add;
+            __syncthreads();
+        }
+        const int32_t base = running[t] - mine;
+        __syncthreads();
+        running[t] = base + offsets[(int64_t)t * gridDim.x + blockIdx.x];
+    }
     for (int w = 0; w < kSortWaves; ++w) wcnt[w][t] = 0;
     __syncthreads();
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
@@ -392,7 +407,7 @@ int launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
     return EP_OK;
 }
 
-size_t sort_hist_elems() { return (size_t)kSortBlocksMax * kRadix; }
+size_t sort_hist_elems() { return (size_t)kSortBlocksMax * kRadix + kRadix; }  // histograms + digit totals
 
 GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws) {
     (void)nnz; (void)k;
@@ -448,9 +463,10 @@ int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *n
         const bool last = pass == passes - 1;
         sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, labels, src, 8 * pass, hist);
         EP_LAUNCH_CHECK();
-        sort_scan_kernel<<<1, kScanThreads, 0, s>>>(hist, blocks * kRadix);
+        sort_scan_kernel<<<kRadix, kRadix, 0, s>>>(hist, blocks, hist + (size_t)kSortBlocksMax * kRadix);
         EP_LAUNCH_CHECK();
-        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, labels, src, 8 * pass, hist, dst,
+        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, labels, src, 8 * pass, hist,
+                                                      hist + (size_t)kSortBlocksMax * kRadix, dst,
                                                       last ? new_id : nullptr);
         EP_LAUNCH_CHECK();
         src = dst;

@@ -228,7 +228,26 @@ __global__ void segment_offsets_kernel(int64_t n, int32_t k, uint32_t key_mask, 
     for (int32_t j = prev + 1; j <= cur; ++j) seg[j] = i;
 }
 
+// One wave per cluster.  kLanes = d / 8 lanes share a row (8 consecutive columns each, one or two
+// 16-byte loads), so a wave reads 64 / kLanes rows per step; sums are fp64 from the start.  The row
+// groups are added in a fixed order at the end.  kLanes == 0 selects a shape-generic variant.
 template <typename XT>
+__device__ __forceinline__ void load8(const XT *p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8<float>(const float *p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const bf16_t *p, float (&v)[8]) {
+    const uint4 r = *reinterpret_cast<const uint4 *>(p);
+    v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xFFFF0000u);
+    v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xFFFF0000u);
+}
+
+template <typename XT, int kLanes>
 __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t k, int64_t ld,
                                                                const XT *__restrict__ X,
                                                                const int32_t *__restrict__ order,
@@ -242,7 +261,41 @@ __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t
     const int64_t b = seg[j], e = seg[j + 1];
     const int64_t cnt = e - b;
     if (lane == 0) counts[j] = cnt;
-    for (int m0 = 0; m0 < d; m0 += 128) {  // two columns per lane per sweep
+    if (kLanes > 0) {
+        constexpr int kRows = kLanes > 0 ? 64 / (kLanes > 0 ? kLanes : 1) : 1;
+        const int chunk = lane % (kLanes > 0 ? kLanes : 1), sub = lane / (kLanes > 0 ? kLanes : 1);
+        double acc[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = 0.0;
+        int64_t t = b + sub;
+        for (; t + kRows < e; t += 2 * kRows) {   // two rows in flight per lane
+            float v0[8], v1[8];
+            load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
+            load8(X + (int64_t)order[t + kRows] * ld + 8 * chunk, v1);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += (double)v1[q];
+        }
+        if (t < e) {
+            float v0[8];
+            load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
+        }
+#pragma unroll
+        for (int off = (kLanes > 0 ? kLanes : 64); off < 64; off <<= 1)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += __shfl_xor(acc[q], off, 64);
+        if (sub == 0) {
+            float *co = C_out + (int64_t)j * d + 8 * chunk;
+            const float *cp = C_prev + (int64_t)j * d + 8 * chunk;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) co[q] = cnt > 0 ? (float)(acc[q] / (double)cnt) : cp[q];
+        }
+        return;
+    }
+    for (int m0 = 0; m0 < d; m0 += 128) {  // shape-generic: two columns per lane per sweep
         const int m = m0 + 2 * lane;
         double s0 = 0.0, s1 = 0.0;
         if (m < d) {
@@ -368,8 +421,14 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
     return by_dtype(p, [&](auto *tag) {
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
         ProfScope prof(EP_PROF_UPDATE_SUMS, s);
-        segment_mean_kernel<XT><<<(unsigned)ceil_div(p.k, kBlock / 64), kBlock, 0, s>>>(
-            p.d, p.k, p.ld, static_cast<const XT *>(X), w.order, w.seg, C_prev, C_out, counts);
+        const unsigned grid = (unsigned)ceil_div(p.k, kBlock / 64);
+        const XT *Xt = static_cast<const XT *>(X);
+        if (p.d == 128)
+            segment_mean_kernel<XT, 16><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
+        else if (p.d == 64)
+            segment_mean_kernel<XT, 8><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
+        else
+            segment_mean_kernel<XT, 0><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
         EP_LAUNCH_CHECK();
         return EP_OK;
     });
