@@ -36,7 +36,6 @@ constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
 constexpr int kSub = 16;  // points per sub-tile
 constexpr int kLabelFlush = 64;                  // sub-tiles whose labels are written out together (4 KB)
-constexpr int kLabelBuf = kLabelFlush * kSub;  // ints per wave
 
 enum Mode { kAssignOnly = 0, kUpdateOnly = 1, kFused = 2 };
 
@@ -73,6 +72,54 @@ __device__ __forceinline__ int float_key(float f) {
 }
 __device__ __forceinline__ float key_float(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
 
+// Dynamic LDS of lloyd_small_kernel: floats (transposition tiles, or per-wave tables of sums for
+// k > 16) followed by the per-wave label buffers.
+template <int D, int KT>
+struct SmallLds {
+    static constexpr int kStride = D + 4;
+    static constexpr int kFlush = KT >= 2 ? 16 : kLabelFlush;   // sub-tiles per label flush
+    static constexpr int kFloatBytes = (KT >= 2 ? kWaves * 16 * KT * kStride : kWaves * kSub * kStride) * 4;
+    static constexpr int kBytes = kFloatBytes + kWaves * kFlush * kSub * 4;
+};
+
+// sums[label of point c][:] += x_c for the 16 points of a sub-tile, in LDS, without atomics and in
+// a fixed order.  Lane (g, c) holds a quarter of point c's row (columns 16 j + 4 g .. + 3).  Points
+// of the sub-tile that share a label must not update the same row at once, so every point gets
+// its rank among the earlier points with the same label (15 DPP row shifts) and round r handles
+// the points of rank r: rows touched in one round are distinct, and every row receives its
+// points in ascending order.  The padded row stride spreads different labels over the banks.
+template <int CTRL>
+__device__ __forceinline__ int row_shr(int v) {
+    return __builtin_amdgcn_update_dpp(-2, v, CTRL, 0xF, 0xF, false);   // lanes shifted in from outside keep -2
+}
+template <int R>
+__device__ __forceinline__ int same_label_before(int lab, int acc) {
+    if constexpr (R > 15) {
+        return acc;
+    } else {
+        acc += row_shr<0x110 + R>(lab) == lab ? 1 : 0;
+        return same_label_before<R + 1>(lab, acc);
+    }
+}
+template <int NJ, int STRIDE>
+__device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32_t lab_c, int g, float *wsums,
+                                                     int32_t *cnt_lds) {
+    int rank = same_label_before<1>(lab_c, 0);
+    if (lab_c < 0) rank = -1;
+    if (g == 0 && lab_c >= 0) atomicAdd(&cnt_lds[lab_c], 1);   // integer: order does not matter
+    float *row = wsums + (lab_c < 0 ? 0 : lab_c) * STRIDE + 4 * g;
+    for (int r = 0; __ballot(rank >= r) != 0; ++r) {
+        if (rank == r) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                f32x4 *p = reinterpret_cast<f32x4 *>(row + 16 * j);
+                *p = *p + x[j];
+            }
+        }
+        wave_lds_fence();
+    }
+}
+
 // XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
 template <int D, int KT, int MODE, bool XSQ>
 __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) void lloyd_small_kernel(
@@ -83,8 +130,14 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     constexpr int NJ = D / 16;       // 16-byte pieces per lane in the transposed layout; also column tiles
     constexpr int NH = D / 64;       // 16-byte pieces per lane and point in the load layout
     constexpr int STRIDE = D + 4;    // padded LDS row: consecutive rows start 4 banks apart
-    __shared__ float lds[kWaves * kSub * STRIDE];
-    __shared__ int32_t label_lds[MODE != kUpdateOnly ? kWaves * kLabelBuf : 1];
+    // k <= 16: sums on the matrix cores (register accumulators).  Larger k: the matrix cores would
+    // spend k/16 times the work of the scores on mostly-zero one-hot products, so every wave keeps
+    // its own padded k x d table of sums in LDS and adds rows to it (see add_rows_to_lds_sums).
+    constexpr bool kLdsSums = KT >= 2;
+    constexpr int kFlush = SmallLds<D, KT>::kFlush;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+    float *lds = reinterpret_cast<float *>(dyn_lds);                       // transposition tiles | per-wave sums
+    int32_t *label_lds = reinterpret_cast<int32_t *>(dyn_lds + SmallLds<D, KT>::kFloatBytes);
     __shared__ float xn_lds[kWaves][kSub];
     __shared__ double red[2][kWaves];
     __shared__ int32_t cnt_lds[16 * KT];
@@ -92,7 +145,13 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: keeps the loop scalar
     const int g = lane >> 4, c = lane & 15;
-    float *tile = lds + wave * kSub * STRIDE;
+    float *tile = lds + wave * kSub * STRIDE;                // !kLdsSums
+    float *wsums = lds + wave * (16 * KT) * STRIDE;           // kLdsSums: this wave's sums, row stride STRIDE
+    if (kLdsSums && MODE != kAssignOnly) {
+        for (int i = lane; i < 16 * KT * STRIDE; i += 64) wsums[i] = 0.f;
+        if (threadIdx.x < 16 * KT) cnt_lds[threadIdx.x] = 0;
+        __syncthreads();
+    }
 
     // Centroid operand of the assignment product: lane (g, c) holds, for centroid 16*mt + c,
     // columns 16j + 4g .. 16j + 4g + 3 for every j.  Padding centroids can never win.
@@ -136,7 +195,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     //     each 4-lane group reads one aligned 64-byte segment, pieces j, j + 1 share a cache line.
     //   row-per-group (sum operand): lane (g, c), piece (r, h) = row 4g + r, columns 64h + 4c .. + 3.
     constexpr int NX = NJ;  // 16-byte pieces per lane and sub-tile (NJ == 4 * NH)
-    constexpr bool kPointPerLane = MODE != kUpdateOnly;
+    constexpr bool kPointPerLane = MODE != kUpdateOnly || KT >= 2;
     int voff[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) voff[r] = (int)(((4 * g + r) * ld + 4 * c) * 4);
@@ -165,7 +224,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     // time as whole, consecutive cache lines.  Single 64-byte label writes scattered through the
     // read stream cost about a tenth of the kernel's time in DRAM read/write turnarounds; bursts
     // of 4 KB cost almost nothing.
-    int32_t *lbuf = label_lds + (MODE != kUpdateOnly ? wave * kLabelBuf : 0);
+    int32_t *lbuf = label_lds + wave * kFlush * kSub;
     int buffered = 0;  // sub-tiles in the buffer (uniform)
     auto flush_labels = [&](int64_t next_st) {
         if (MODE == kUpdateOnly || buffered == 0) return;
@@ -193,7 +252,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         if (MODE != kUpdateOnly) {
             // The sum product needs the other layout: the sub-tile goes through the wave's LDS tile
             // (written point-per-lane, read row-per-group) in the shadow of the score product.
-            if (MODE == kFused) {
+            if (MODE == kFused && !kLdsSums) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) *reinterpret_cast<f32x4 *>(tile + c * STRIDE + 16 * j + 4 * g) = x[j];
             }
@@ -216,7 +275,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                                                                          0, 0);
                     }
 
-            if (MODE == kFused) {
+            if (MODE == kFused && !kLdsSums) {
                 wave_lds_fence();
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -271,7 +330,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 if (owner) min_d2[row0 + 4 * g + c] = fmaxf(xn_lds[wave][4 * g + c] - 2.f * my_s, 0.f);
                 wave_lds_fence();
             }
-        } else {
+        } else if (!kLdsSums) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int32_t l = (4 * g + v < rows_here) ? labels_in[row0 + 4 * g + v] : -1;
@@ -281,7 +340,20 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             for (int q = 0; q < NX; ++q) bt[q] = x[q];
         }
 
-        if (MODE != kAssignOnly) {
+        if (MODE != kAssignOnly && kLdsSums) {
+            // label of point c (this lane's point in the point-per-lane layout)
+            int32_t lab_c;
+            if (MODE == kFused) {
+                wave_lds_fence();
+                lab_c = lbuf[(buffered - 1) * kSub + c];
+            } else {
+                const int32_t l = c < rows_here ? labels_in[row0 + c] : -1;
+                lab_c = (l >= 0 && l < k) ? l : -1;
+            }
+            add_rows_to_lds_sums<NJ, STRIDE>(x, lab_c, g, wsums, cnt_lds);
+        }
+
+        if (MODE != kAssignOnly && !kLdsSums) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -306,13 +378,13 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         __builtin_amdgcn_sched_barrier(0);  // keep the whole prefetch ahead of the arithmetic
         process(st, xa);
         ++st;
-        if (buffered == kLabelFlush) flush_labels(st);
+        if (buffered == kFlush) flush_labels(st);
         if (st >= last) break;
         load_subtile(st + 1, xa);
         __builtin_amdgcn_sched_barrier(0);
         process(st, xb);
         ++st;
-        if (buffered == kLabelFlush) flush_labels(st);
+        if (buffered == kFlush) flush_labels(st);
     }
     flush_labels(st);
 
@@ -330,7 +402,17 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     }
 
     // ---- partial sums of this workgroup: waves add their accumulators in wave order ----
-    if (MODE != kAssignOnly) {
+    if (MODE != kAssignOnly && kLdsSums) {
+        __syncthreads();  // every wave's table is complete
+        for (int i = threadIdx.x; i < k * D; i += kBlock) {
+            const int at = (i / D) * STRIDE + (i % D);
+            float v = lds[at];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) v += lds[w * (16 * KT) * STRIDE + at];   // wave order
+            psum[(int64_t)blockIdx.x * k * D + i] = v;
+        }
+        if ((int)threadIdx.x < k) pcnt[(int64_t)blockIdx.x * k + threadIdx.x] = cnt_lds[threadIdx.x];
+    } else if (MODE != kAssignOnly) {
         __syncthreads();  // every wave has left its tile
         float *sums = lds;  // 16*KT x D floats
 #pragma unroll 1
@@ -503,9 +585,16 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
     double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s);
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
-    lloyd_small_kernel<D_, KT_, MODE, XSQ><<<geo.blocks, kBlock, 0, s>>>(                                     \
-        p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, w.cnorm, labels_out, labels_in, min_d2, w.psum, w.pcnt, sp, \
-        xsq_part_of(w))
+    do {                                                                                                      \
+        constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
+        auto kern = lloyd_small_kernel<D_, KT_, MODE, XSQ>;                                                   \
+        if (lds_bytes > 64 * 1024)                                                                            \
+            EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
+        kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, w.cnorm,     \
+                                                   labels_out, labels_in, min_d2, w.psum, w.pcnt, sp,        \
+                                                   xsq_part_of(w));                                           \
+    } while (0)
     if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
     } else {

@@ -1,0 +1,130 @@
+"""The benchmark configurations at full size, in the launch configuration bench.py times.
+
+Where the oracle can follow the whole run it does (products_like); where it cannot (k = 16,384:
+1e14 flop per run; 111 M points: 57 GB of embeddings), the device results are checked on sampled
+outputs the oracle computes one by one (nearest centroid of sampled points against all centroids,
+means of sampled clusters) and through properties that hold at any size (counts = histogram of
+labels, sizes sum to n, objective non-increasing); the integer graph outputs are compared in full.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_01000_amd import embedpart as ep
+from paper_2604_01000_amd import synth
+
+from parity import (CENTROID_RTOL, DEV, Graph, Kmeans, centroid_rel_err, centroids_used, check_free_running,
+                    label_mismatches)
+
+pytestmark = pytest.mark.gpu
+
+
+def _sampled_round_check(X, km, C_before, got, k, bf16, rng, n_points=4096, n_clusters=24):
+    """One device round checked on samples: labels of sampled points against the oracle's search over
+    all k centroids, and the means / counts of sampled clusters against the oracle's update."""
+    n = X.shape[0]
+    rows = np.unique(np.concatenate([rng.integers(0, n, size=n_points), np.arange(min(n, 257)),
+                                     np.arange(max(0, n - 131), n)]))
+    Xs = X[torch.from_numpy(rows).to(DEV)].to("cpu", torch.float32).numpy()
+    used = centroids_used(C_before, bf16)
+    want, best, _, _ = oracle.assign(Xs, used)
+    differing, unexcused = label_mismatches(Xs, used, got["labels"][rows], want, best)
+    assert unexcused == 0, f"{unexcused} of {differing} sampled labels differ and are not near-ties"
+    labels = got["labels"]
+    assert labels.min() >= 0 and labels.max() < k
+    counts = np.bincount(labels, minlength=k)
+    np.testing.assert_array_equal(got["counts"], counts)
+    assert counts.sum() == n
+    labels_dev = torch.from_numpy(labels).to(DEV)
+    for j in rng.choice(k, size=min(k, n_clusters), replace=False):
+        members = torch.nonzero(labels_dev == int(j)).squeeze(1)
+        if members.numel() == 0:
+            np.testing.assert_array_equal(got["C"][j], np.asarray(C_before, dtype=np.float32)[j])
+            continue
+        Xm = X[members].to("cpu", torch.float32).numpy()
+        C_or, cnt_or, _ = oracle.update(Xm, np.zeros(len(Xm), dtype=np.int32), np.zeros((1, X.shape[1])))
+        assert cnt_or[0] == counts[j]
+        assert centroid_rel_err(got["C"][j:j + 1], C_or) <= CENTROID_RTOL
+    return differing
+
+
+def _graph_check(w, labels_np, k, reorder=False):
+    rowptr, colidx, _ = synth.sbm_graph(w, DEV)
+    gr = Graph(rowptr, colidx, k_max=max(k, 1))
+    labels = torch.from_numpy(labels_np).to(DEV)
+    cut, sizes = gr.quality(labels, k)
+    cut_or, sizes_or = oracle.partition_quality(gr.rp_np, gr.ci_np, labels_np, k)
+    assert cut == cut_or
+    np.testing.assert_array_equal(sizes, sizes_or)
+    if reorder:
+        new_id, order = gr.permutation(labels, k)
+        new_or, order_or = oracle.permutation(labels_np, k)
+        np.testing.assert_array_equal(new_id.cpu().numpy(), new_or)
+        np.testing.assert_array_equal(order.cpu().numpy(), order_or)
+        assert gr.gap_sum(new_id) == oracle.edge_gap_sum(gr.rp_np, gr.ci_np, new_or)
+        assert gr.gap_sum(None) == oracle.edge_gap_sum(gr.rp_np, gr.ci_np)
+    return cut_or / max(gr.nnz, 1)
+
+
+def test_products_like_full():
+    w = synth.WORKLOADS["products_like"]
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    flips = check_free_running(X, w.k, w.iters, idx)
+    print(f"products_like: {flips} labels differed from the oracle over {w.iters} rounds")
+    got = Kmeans(X, w.k).init(idx).run(w.iters)
+    ecr = _graph_check(w, got["labels"], w.k)
+    print(f"products_like: edge-cut ratio {ecr:.4f}")
+
+
+def test_products_reorder_full():
+    w = synth.WORKLOADS["products_reorder"]
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    rng = np.random.default_rng(7)
+    km = Kmeans(X, w.k).init(idx)
+    objs = []
+    for t in range(3):                                   # three rounds, each checked on samples
+        C_before = km.C.cpu().numpy().astype(np.float64)
+        got = km.run(1)
+        d = _sampled_round_check(X, km, C_before, got, w.k, True, rng)
+        objs.append(got["obj_hist"][0])
+        print(f"products_reorder round {t}: objective {objs[-1]:.6e}, sampled labels differing {d}, "
+              f"empty clusters {int((got['counts'] == 0).sum())}")
+    assert objs[1] <= objs[0] and objs[2] <= objs[1]
+    full = Kmeans(X, w.k).init(idx).run(3)               # the driver equals the three steps
+    np.testing.assert_array_equal(full["labels"], got["labels"])
+    np.testing.assert_array_equal(full["C"], got["C"])
+    _graph_check(w, got["labels"], w.k, reorder=True)
+
+
+def test_papers_like_full():
+    w = synth.WORKLOADS["papers_like"]
+    free, total = torch.cuda.mem_get_info()
+    if free < 150 * 2**30:
+        pytest.skip("needs about 150 GB of free device memory")
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    rng = np.random.default_rng(11)
+    km = Kmeans(X, w.k).init(idx)
+    objs = []
+    for t in range(2):
+        C_before = km.C.cpu().numpy().astype(np.float64)
+        got = km.run(1)
+        d = _sampled_round_check(X, km, C_before, got, w.k, False, rng, n_points=16384, n_clusters=3)
+        objs.append(got["obj_hist"][0])
+        print(f"papers_like round {t}: objective {objs[-1]:.6e}, sampled labels differing {d}")
+    assert objs[1] <= objs[0]
+    # a contiguous slice follows the oracle exactly: same rows, same centroids, lockstep
+    lo, hi = 55_000_000, 55_000_000 + (1 << 18)
+    Xs = X[lo:hi].to("cpu", torch.float32).numpy()
+    used = centroids_used(C_before, False)
+    want, best, _, _ = oracle.assign(Xs, used)
+    differing, unexcused = label_mismatches(Xs, used, got["labels"][lo:hi], want, best)
+    assert unexcused == 0
+    labels_np = got["labels"]
+    del X, km
+    torch.cuda.empty_cache()
+    ecr = _graph_check(w, labels_np, w.k)
+    print(f"papers_like: edge-cut ratio {ecr:.4f}")

@@ -15,7 +15,8 @@ import oracle
 from paper_2604_01000_amd import embedpart as ep
 from paper_2604_01000_amd import synth
 
-from parity import (CENTROID_RTOL, DEV, Kmeans, centroid_rel_err, centroids_used, label_mismatches, to_np32)
+from parity import (CENTROID_RTOL, DEV, Kmeans, centroid_rel_err, centroids_used, check_free_running, label_mismatches,
+                    to_np32)
 
 pytestmark = pytest.mark.gpu
 
@@ -122,59 +123,12 @@ def test_update_skips_out_of_range_labels():
     assert centroid_rel_err(C_got, C_or) <= CENTROID_RTOL
 
 
-def _check_free_running(X, k, iters, idx, bf16=False):
-    """Free-running device Lloyd against the oracle.
-
-    Every round of the device's own trajectory is checked: its labels against the oracle's
-    assignment from the centroids the device held (differences only at near-ties), its new
-    centroids against the oracle's means of the device's labels, its objective against the
-    oracle's.  A near-tie resolved differently moves a centroid by about |x - c| / n_j, which
-    can be more than the centroid tolerance for small clusters and then moves other points, so
-    the device's and the oracle's own trajectories are compared at the end only when no label
-    differed on the way; otherwise their final objectives must still agree closely.
-    Returns the number of labels that differed over all rounds."""
-    X32 = to_np32(X)
-    n = X32.shape[0]
-    free = Kmeans(X, k).init(idx).run(iters)
-    km = Kmeans(X, k).init(idx)
-    C_prev = km.C.cpu().numpy().astype(np.float64)
-    np.testing.assert_array_equal(C_prev, X32[idx].astype(np.float64))
-    flips = 0
-    for t in range(iters):
-        got = km.run(1)
-        used = centroids_used(C_prev, bf16)
-        want, best, _, obj_or = oracle.assign(X32, used)
-        differing, unexcused = label_mismatches(X32, used, got["labels"], want, best)
-        assert unexcused == 0, f"round {t}: {unexcused} of {differing} differing labels are not near-ties"
-        flips += differing
-        C_or, counts_or, _ = oracle.update(X32, got["labels"], C_prev)
-        np.testing.assert_array_equal(got["counts"], counts_or)
-        assert centroid_rel_err(got["C"], C_or) <= CENTROID_RTOL, f"round {t}"
-        assert abs(got["obj_hist"][0] - obj_or) <= 1e-5 * obj_or
-        assert abs(free["obj_hist"][t] - got["obj_hist"][0]) == 0.0       # stepping = running
-        C_prev = got["C"].astype(np.float64)
-    for key in ("C", "labels", "counts"):
-        np.testing.assert_array_equal(free[key], got[key])
-    assert np.isnan(free["obj_hist"][iters])                                # written only with the re-assign flag
-    assert free["counts"].sum() == n
-    assert np.all(np.diff(free["obj_hist"][:iters]) <= 1e-6 * free["obj_hist"][:iters - 1])   # non-increasing
-    ref = oracle.lloyd(X32, k, iters, idx, flags=oracle.FLAG_BF16_CENTROIDS if bf16 else 0)
-    if flips == 0:
-        np.testing.assert_array_equal(free["labels"], ref["labels"])
-        np.testing.assert_array_equal(free["counts"], ref["counts"])
-        assert centroid_rel_err(free["C"], ref["C"]) <= CENTROID_RTOL
-        assert np.all(np.abs(free["obj_hist"][:iters] - ref["obj_hist"]) <= 1e-5 * ref["obj_hist"])
-    else:
-        assert abs(free["obj_hist"][iters - 1] - ref["obj_hist"][-1]) <= 1e-3 * ref["obj_hist"][-1]
-    return flips
-
-
 @pytest.mark.parametrize("name", ["tiny", "arxiv_like"])
 def test_run_matches_oracle_full_size(name):
     w = synth.WORKLOADS[name]
     X = synth.embeddings(w, DEV)
     idx = oracle.init_indices(w.seed, w.n, w.k)
-    flips = _check_free_running(X, w.k, w.iters, idx)
+    flips = check_free_running(X, w.k, w.iters, idx)
     assert flips == 0, "the benchmark configurations are expected to follow the oracle's trajectory exactly"
 
 
@@ -184,7 +138,7 @@ def test_run_matches_oracle_full_size(name):
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
     idx = oracle.init_indices(n + 1, n, k)
-    _check_free_running(X, k, iters, idx, bf16=dtype == torch.bfloat16)
+    check_free_running(X, k, iters, idx, bf16=dtype == torch.bfloat16)
 
 
 @pytest.mark.parametrize("name,n", [("tiny", None), ("products_like", 20_011), ("papers_like", 9_001)])
