@@ -459,8 +459,13 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
 
 // Lane l adds partials l, l + 64, ...; then a fixed shuffle tree.  Called by one full wave.
 __device__ __forceinline__ double wave_sum_fixed(const double *__restrict__ part, int count, int l) {
+    constexpr int kPerLane = kSmallMaxBlocks / 64;
+    double v[kPerLane];
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) v[q] = l + 64 * q < count ? part[l + 64 * q] : 0.0;   // one round trip
     double o = 0.0;
-    for (int q = l; q < count; q += 64) o += part[q];
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) o += v[q];
     for (int off = 32; off > 0; off >>= 1) o += __shfl_down(o, off, 64);
     return o;
 }
@@ -494,47 +499,63 @@ __global__ __launch_bounds__(kBlock) void half_norms_kernel(int32_t d, int32_t k
     if (lane == 0) hneg[j] = (float)(-0.5 * acc);
 }
 
-// Second pass of a round.  Workgroup j forms centroid j.  Thread (seg, m) adds the partials
-// b = seg, seg + S, ... of column m in fp64; the S segment sums are then added in segment order,
-// divided by the count and rounded to fp32; an empty cluster keeps its centroid.  The workgroup
-// also leaves -||c_j||^2/2 for the next round and, in workgroup 0, the round's objective (partials
-// added in a fixed tree order).
-constexpr int kFinBlock = 1024;
+// Second pass of a round.  Workgroup j forms centroid j.  Thread (seg, m4) reads columns 4 m4 .. + 3
+// of the partials b = seg, seg + S, ... with 16-byte loads, 16 at a time in flight, and adds them in
+// fp64 in ascending order; the S segment sums are then added in segment order, divided by the
+// count and rounded to fp32; an empty cluster keeps its centroid.  The workgroup also leaves
+// -||c_j||^2/2 for the next round and, in workgroup 0, the round's objective.
+constexpr int kFinBlock = 512;
 __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
     int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
     const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
     double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
     int64_t *__restrict__ counts, float *__restrict__ hneg, double *__restrict__ objective) {
-    __shared__ double seg_sum[kFinBlock];
+    __shared__ double seg_sum[kFinBlock * 4];
     __shared__ float cn[128];
     __shared__ unsigned long long total_cnt;
     const int j = blockIdx.x, t = threadIdx.x;
-    const int m = t % d, seg = t / d, segs = kFinBlock / d;  // d in {64, 128}
+    const int quads = d / 4;                          // 16-byte column groups per row: 32 or 16
+    const int m4 = t % quads, seg = t / quads, segs = kFinBlock / quads;
+    // The loads of this thread are issued before anything is waited for: its partial count, then
+    // the partial sums 16 at a time (parts <= 512, segs >= 16: at most two batches).
+    const int32_t my_cnt = t < parts ? pcnt[(int64_t)t * k + j] : 0;
+    const float4 *col = reinterpret_cast<const float4 *>(psum + (int64_t)j * d) + m4;
+    const int64_t stride4 = (int64_t)k * d / 4;
     if (t == 0) total_cnt = 0;
     __syncthreads();
-    if (t < parts) {
-        const int32_t c = pcnt[(int64_t)t * k + j];
-        if (c) atomicAdd(&total_cnt, (unsigned long long)c);
+    {   // counts: added per wave, then one LDS atomic per wave (integers: order-free)
+        int32_t c = my_cnt;
+        for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off, 64);
+        if ((t & 63) == 0 && c) atomicAdd(&total_cnt, (unsigned long long)c);
     }
-    double s = 0.0;
-    const float *col = psum + (int64_t)j * d + m;
-    const int64_t stride = (int64_t)k * d;
-    int b = seg;
-    for (; b + 3 * segs < parts; b += 4 * segs) {  // four loads in flight, added in order
-        const float v0 = col[(int64_t)b * stride], v1 = col[(int64_t)(b + segs) * stride];
-        const float v2 = col[(int64_t)(b + 2 * segs) * stride], v3 = col[(int64_t)(b + 3 * segs) * stride];
-        s += (double)v0; s += (double)v1; s += (double)v2; s += (double)v3;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    for (int b0 = seg; b0 < parts; b0 += 16 * segs) {
+        float4 v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int b = b0 + q * segs;
+            v[q] = b < parts ? col[(int64_t)b * stride4] : float4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {   // ascending workgroup order; missing partials add +0.0
+            s0 += (double)v[q].x;
+            s1 += (double)v[q].y;
+            s2 += (double)v[q].z;
+            s3 += (double)v[q].w;
+        }
     }
-    for (; b < parts; b += segs) s += (double)col[(int64_t)b * stride];
-    seg_sum[t] = s;
+    seg_sum[(seg * quads + m4) * 4 + 0] = s0;
+    seg_sum[(seg * quads + m4) * 4 + 1] = s1;
+    seg_sum[(seg * quads + m4) * 4 + 2] = s2;
+    seg_sum[(seg * quads + m4) * 4 + 3] = s3;
     __syncthreads();
-    if (seg == 0) {
-        double tot = seg_sum[m];
-        for (int q = 1; q < segs; ++q) tot += seg_sum[q * d + m];
+    if (t < d) {
+        double tot = seg_sum[t];
+        for (int q = 1; q < segs; ++q) tot += seg_sum[q * d + t];
         const int64_t cc = (int64_t)total_cnt;
-        const float cnew = cc > 0 ? (float)(tot / (double)cc) : C_prev[(int64_t)j * d + m];
-        C_out[(int64_t)j * d + m] = cnew;
-        cn[m] = cnew;
+        const float cnew = cc > 0 ? (float)(tot / (double)cc) : C_prev[(int64_t)j * d + t];
+        C_out[(int64_t)j * d + t] = cnew;
+        cn[t] = cnew;
     }
     __syncthreads();
     if (t < 64) {  // same operations, in the same order, as half_norms_kernel
