@@ -21,6 +21,7 @@
 //   * At the end the four waves of a workgroup add their accumulators in wave order through LDS
 //     and store one partial per workgroup; update_finalize_kernel reduces those in fp64.
 #include <algorithm>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -78,7 +79,7 @@ template <int D, int KT>
 struct SmallLds {
     static constexpr int kStride = D + 4;
     static constexpr int kFlush = KT >= 2 ? 16 : kLabelFlush;   // sub-tiles per label flush
-    static constexpr int kFloatBytes = (KT >= 2 ? kWaves * 16 * KT * kStride : kWaves * kSub * kStride) * 4;
+    static constexpr int kFloatBytes = (KT >= 2 ? kWaves * (16 * KT + 1) * kStride : kWaves * kSub * kStride) * 4;
     static constexpr int kBytes = kFloatBytes + kWaves * kFlush * kSub * 4;
 };
 
@@ -92,13 +93,13 @@ template <int CTRL>
 __device__ __forceinline__ int row_shr(int v) {
     return __builtin_amdgcn_update_dpp(-2, v, CTRL, 0xF, 0xF, false);   // lanes shifted in from outside keep -2
 }
-template <int R>
+template <int R, int R_LAST = 15>
 __device__ __forceinline__ int same_label_before(int lab, int acc) {
-    if constexpr (R > 15) {
+    if constexpr (R > R_LAST) {
         return acc;
     } else {
         acc += row_shr<0x110 + R>(lab) == lab ? 1 : 0;
-        return same_label_before<R + 1>(lab, acc);
+        return same_label_before<R + 1, R_LAST>(lab, acc);
     }
 }
 template <int NJ, int STRIDE>
@@ -146,9 +147,9 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: keeps the loop scalar
     const int g = lane >> 4, c = lane & 15;
     float *tile = lds + wave * kSub * STRIDE;                // !kLdsSums
-    float *wsums = lds + wave * (16 * KT) * STRIDE;           // kLdsSums: this wave's sums, row stride STRIDE
+    float *wsums = lds + wave * (16 * KT + 1) * STRIDE;       // kLdsSums: this wave's sums (+ one idle row), row stride STRIDE
     if (kLdsSums && MODE != kAssignOnly) {
-        for (int i = lane; i < 16 * KT * STRIDE; i += 64) wsums[i] = 0.f;
+        for (int i = lane; i < (16 * KT + 1) * STRIDE; i += 64) wsums[i] = 0.f;
         if (threadIdx.x < 16 * KT) cnt_lds[threadIdx.x] = 0;
         __syncthreads();
     }
@@ -369,6 +370,170 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         }
     };
 
+    if constexpr (kLdsSums && MODE == kFused) {
+        // k > 16, fused round, one wave per SIMD: everything that is not a matrix instruction (arg-max,
+        // labels, ranks, the row adds into the LDS sums) is done one sub-tile late, in the issue slots
+        // between the matrix instructions of the next sub-tile.  A sub-tile's scores need KT * D / 4
+        // matrix instructions of 32 cycles each; the deferred work of the previous sub-tile is cut into
+        // D / 4 slices that are placed, in program order, one after every group of KT instructions.
+        // The slices hold no branch (lanes with nothing to do write to scrap words instead), so the
+        // whole step is one basic block whose order the scheduling barriers fix.
+        constexpr int kFixedRounds = D >= 128 ? 3 : 2;   // these ranks without branches; higher ranks (rare) in a loop
+        constexpr int kFirstAdd = 7;                       // slices 0 .. 6: arg-max (4), labels, rank (2)
+        __shared__ __attribute__((aligned(16))) int32_t scrap[4 * kBlock];   // 16 bytes per lane, written by idle lanes, never read
+        float *dummy = wsums + 16 * KT * STRIDE + 4 * g;   // the extra row idle lanes add to; never read
+        f32x4 scp[KT];         // previous sub-tile: scores (sum of the two chains)
+        int prev_rows = 0;     // rows of the previous sub-tile
+        int bkeyp[4];
+        int32_t labp[4];
+        int32_t lab_c = -1;
+        int rank = -1;
+        float *rowp = dummy;
+        f32x4 pending = {0.f, 0.f, 0.f, 0.f};   // LDS read of the next row-add piece, in flight
+
+        auto slice = [&](int b, const f32x4(&xp)[NX]) {   // b = 0 .. D/4 - 1, uniform
+            if (b < 4) {   // arg-max of point group v = b
+                const int v = b;
+                float sc = scp[0][v];
+                int idx = c;
+#pragma unroll
+                for (int mt = 1; mt < KT; ++mt)
+                    if (scp[mt][v] > sc) { sc = scp[mt][v]; idx = 16 * mt + c; }
+                const int key = float_key(sc);
+                bkeyp[v] = row16_max(key);
+                const int win = row16_min(key == bkeyp[v] ? idx : 0x7fffffff);
+                labp[v] = (4 * g + v < prev_rows) ? win : -1;
+            } else if (b == 4) {   // labels to the LDS buffer, objective terms
+                // every lane of a 16-lane row holds the row's four results: lane c == 0 stores them,
+                // and every lane keeps the running sum of best scores (only lane c == 0's is used)
+                i32x4 *dst = reinterpret_cast<i32x4 *>(c == 0 ? lbuf + buffered * kSub + 4 * g : scrap + 4 * threadIdx.x);
+                *dst = i32x4{labp[0], labp[1], labp[2], labp[3]};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) obj_s += (double)(4 * g + v < prev_rows ? key_float(bkeyp[v]) : 0.f);
+                if (XSQ) {
+                    float xpart = 0.f;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        xpart += xp[j][0] * xp[j][0] + xp[j][1] * xp[j][1] + xp[j][2] * xp[j][2] + xp[j][3] * xp[j][3];
+                    obj_x += (double)(c < prev_rows ? xpart : 0.f);
+                }
+                wave_lds_fence();
+            } else if (b == 5) {   // label of this lane's point; first half of its rank among earlier equal labels
+                lab_c = lbuf[buffered * kSub + c];
+                ++buffered;
+                rank = same_label_before<1, 8>(lab_c, 0);
+                int32_t *cp = (g == 0 && lab_c >= 0) ? cnt_lds + lab_c : scrap + threadIdx.x;
+                atomicAdd(cp, 1);   // integer: order does not matter
+            } else if (b == 6) {
+                rank = same_label_before<9, 15>(lab_c, rank);
+                if (lab_c < 0) rank = -1;
+                rowp = wsums + (lab_c < 0 ? 0 : lab_c) * STRIDE + 4 * g;
+                pending = *reinterpret_cast<const f32x4 *>((rank == 0 ? rowp : dummy));   // read of piece 0
+            } else if (b < kFirstAdd + kFixedRounds * NJ) {
+                // one 16-byte piece of one round of row adds; its read was issued one slice earlier, the
+                // next piece's read is issued here (a round never touches a column group twice, and the
+                // same column group of the next round comes NJ slices later)
+                const int q = b - kFirstAdd, r = q / NJ, j = q % NJ;
+                f32x4 *p = reinterpret_cast<f32x4 *>((rank == r ? rowp : dummy) + 16 * j);
+                const f32x4 sum = pending + xp[j];
+                if (q + 1 < kFixedRounds * NJ) {
+                    const int r1 = (q + 1) / NJ, j1 = (q + 1) % NJ;
+                    pending = *reinterpret_cast<const f32x4 *>((rank == r1 ? rowp : dummy) + 16 * j1);
+                }
+                *p = sum;
+            }
+        };
+        auto finish_prev = [&](const f32x4(&xp)[NX]) {   // ranks beyond the fixed rounds
+            for (int r = kFixedRounds; __ballot(rank >= r) != 0; ++r) {
+                if (rank == r) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        f32x4 *p = reinterpret_cast<f32x4 *>(rowp + 16 * j);
+                        *p = *p + xp[j];
+                    }
+                }
+                wave_lds_fence();
+            }
+        };
+        static_assert(kFirstAdd + kFixedRounds * NJ <= D / 4, "the deferred work must fit the slices");
+
+        // scores of sub-tile st (in x); with DEFERRED, the previous sub-tile's (in xp) other work in between
+        auto step = [&](int64_t st, const f32x4(&x)[NX], const f32x4(&xp)[NX], auto deferred) {
+            constexpr bool DEFERRED = decltype(deferred)::value;
+            f32x4 acc0[KT], acc1[KT];
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                acc0[mt] = f32x4{hn[mt], hn[mt], hn[mt], hn[mt]};
+                acc1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int b = 0; b < D / 4; ++b) {
+                const int j = b >> 2, e = b & 3;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    if (j & 1) acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
+                    else acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
+                }
+                if (DEFERRED) {
+                    slice(b, xp);
+                    __builtin_amdgcn_sched_barrier(0);   // pin the interleaving
+                }
+            }
+            // the sums of the chains are formed here, in the block of the matrix instructions, so that
+            // no later block is a better place for them in the compiler's eyes
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                scp[mt] = acc0[mt] + acc1[mt];
+                asm volatile("" : "+v"(scp[mt]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (DEFERRED) finish_prev(xp);
+            prev_rows = (int)min((int64_t)kSub, n - st * kSub);
+        };
+        auto drain = [&](const f32x4(&xp)[NX]) {   // the last sub-tile's deferred work, no matrix work to hide in
+#pragma unroll
+            for (int b = 0; b < D / 4; ++b) slice(b, xp);
+            finish_prev(xp);
+        };
+        using std::false_type;
+        using std::true_type;
+
+        // three register sets in rotation: current, previous (still needed for its row adds), next (in flight)
+        f32x4 x0[NX], x1[NX], x2[NX];
+        int64_t st = first;
+        if (first < last) {
+            load_subtile(st, x0);
+            load_subtile(st + 1, x1);
+            __builtin_amdgcn_sched_barrier(0);
+            step(st, x0, x0, false_type{});
+            ++st;
+            int phase = 0;   // which set holds the previous sub-tile when the loop ends
+            while (st < last) {
+                load_subtile(st + 1, x2);
+                __builtin_amdgcn_sched_barrier(0);
+                step(st, x1, x0, true_type{});
+                ++st;
+                if (buffered == kFlush) flush_labels(st - 1);
+                phase = 1;
+                if (st >= last) break;
+                load_subtile(st + 1, x0);
+                __builtin_amdgcn_sched_barrier(0);
+                step(st, x2, x1, true_type{});
+                ++st;
+                if (buffered == kFlush) flush_labels(st - 1);
+                phase = 2;
+                if (st >= last) break;
+                load_subtile(st + 1, x1);
+                __builtin_amdgcn_sched_barrier(0);
+                step(st, x0, x2, true_type{});
+                ++st;
+                if (buffered == kFlush) flush_labels(st - 1);
+                phase = 0;
+            }
+            if (phase == 0) drain(x0); else if (phase == 1) drain(x1); else drain(x2);
+            flush_labels(st);
+        }
+    } else {
     // Two register sets in ping-pong: while one sub-tile is processed, the next one is in flight.
     f32x4 xa[NX], xb[NX];
     int64_t st = first;
@@ -387,10 +552,12 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         if (buffered == kFlush) flush_labels(st);
     }
     flush_labels(st);
+    }
 
     // ---- objective partials of this workgroup (fixed order) ----
     if (MODE != kUpdateOnly && s_part) {
         double os = obj_s, ox = obj_x;
+        if (kLdsSums && MODE == kFused && c != 0) os = 0.0;   // that path keeps the same sum in all 16 lanes of a row
         for (int off = 32; off > 0; off >>= 1) {
             os += __shfl_down(os, off, 64);
             if (XSQ) ox += __shfl_down(ox, off, 64);
@@ -408,7 +575,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             const int at = (i / D) * STRIDE + (i % D);
             float v = lds[at];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) v += lds[w * (16 * KT) * STRIDE + at];   // wave order
+            for (int w = 1; w < kWaves; ++w) v += lds[w * (16 * KT + 1) * STRIDE + at];   // wave order
             psum[(int64_t)blockIdx.x * k * D + i] = v;
         }
         if ((int)threadIdx.x < k) pcnt[(int64_t)blockIdx.x * k + threadIdx.x] = cnt_lds[threadIdx.x];
