@@ -258,7 +258,10 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 for (int j = 0; j < NJ; ++j) *reinterpret_cast<f32x4 *>(tile + c * STRIDE + 16 * j + 4 * g) = x[j];
             }
 
-            // scores: two accumulation chains per centroid tile (even / odd j), added at the end
+            // scores: two accumulation chains per centroid tile (even / odd j), added at the end; with
+            // four tiles one chain, since KT - 1 other instructions already separate dependent ones
+            // (the same arithmetic as the pipelined loop below: both give the same scores bit for bit)
+            constexpr bool kTwoChains = KT < 4;
             f32x4 acc0[KT], acc1[KT];
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
@@ -266,15 +269,20 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 acc1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
-            for (int j = 0; j < NJ; j += 2)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int mt = 0; mt < KT; ++mt) {
-                        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
-                        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j + 1][e], creg[mt][j + 1][e], acc1[mt], 0,
-                                                                         0, 0);
+                        if (kTwoChains && (j & 1))
+                            acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
+                        else
+                            acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
                     }
+            if (kTwoChains) {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) acc0[mt] += acc1[mt];
+            }
 
             if (MODE == kFused && !kLdsSums) {
                 wave_lds_fence();
@@ -300,11 +308,11 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             int bkey[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float sc = acc0[0][v] + acc1[0][v];
+                float sc = acc0[0][v];
                 int idx = c;
 #pragma unroll
                 for (int mt = 1; mt < KT; ++mt) {
-                    const float s2 = acc0[mt][v] + acc1[mt][v];
+                    const float s2 = acc0[mt][v];
                     if (s2 > sc) { sc = s2; idx = 16 * mt + c; }
                 }
                 const int key = float_key(sc);
@@ -320,7 +328,12 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             const bool owner = c < 4 && 4 * g + c < rows_here;
             if (c < 4) lbuf[buffered * kSub + 4 * g + c] = my_l;
             ++buffered;
-            if (owner) obj_s += (double)my_s;
+            if (kLdsSums) {   // every lane of a 16-lane row keeps the row's sum; lane c == 0's is used
+#pragma unroll
+                for (int v = 0; v < 4; ++v) obj_s += (double)(4 * g + v < rows_here ? key_float(bkey[v]) : 0.f);
+            } else if (owner) {
+                obj_s += (double)my_s;
+            }
             if (XSQ && c < rows_here) obj_x += (double)xpart;
             if (min_d2) {  // uniform branch
                 float xn = xpart;
@@ -460,6 +473,9 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         // scores of sub-tile st (in x); with DEFERRED, the previous sub-tile's (in xp) other work in between
         auto step = [&](int64_t st, const f32x4(&x)[NX], const f32x4(&xp)[NX], auto deferred) {
             constexpr bool DEFERRED = decltype(deferred)::value;
+            // KT independent accumulators already separate dependent matrix instructions by KT - 1
+            // others; a second chain per tile is only needed when that is too few.
+            constexpr bool kTwoChains = KT < 4;
             f32x4 acc0[KT], acc1[KT];
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
@@ -471,19 +487,21 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 const int j = b >> 2, e = b & 3;
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt) {
-                    if (j & 1) acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
-                    else acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
+                    if (kTwoChains && (j & 1))
+                        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
+                    else
+                        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
                 }
                 if (DEFERRED) {
                     slice(b, xp);
                     __builtin_amdgcn_sched_barrier(0);   // pin the interleaving
                 }
             }
-            // the sums of the chains are formed here, in the block of the matrix instructions, so that
-            // no later block is a better place for them in the compiler's eyes
+            // the scores are pinned here, in the block of the matrix instructions, so that no later
+            // block is a better place for them in the compiler's eyes
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
-                scp[mt] = acc0[mt] + acc1[mt];
+                scp[mt] = kTwoChains ? acc0[mt] + acc1[mt] : acc0[mt];
                 asm volatile("" : "+v"(scp[mt]));
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -498,39 +516,37 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         using std::false_type;
         using std::true_type;
 
-        // three register sets in rotation: current, previous (still needed for its row adds), next (in flight)
-        f32x4 x0[NX], x1[NX], x2[NX];
+        // Four register sets in rotation: current, previous (still needed for its row adds) and the
+        // next two, in flight.  With one wave per SIMD a single sub-tile in flight per wave does not
+        // cover the memory latency (8 KB x 1024 waves in flight moves about 3 TB/s).
+        f32x4 x0[NX], x1[NX], x2[NX], x3[NX];
         int64_t st = first;
         if (first < last) {
             load_subtile(st, x0);
             load_subtile(st + 1, x1);
+            load_subtile(st + 2, x2);
             __builtin_amdgcn_sched_barrier(0);
             step(st, x0, x0, false_type{});
             ++st;
             int phase = 0;   // which set holds the previous sub-tile when the loop ends
+#define EP_PIPE_STEP(CUR, PREV, FREE, PHASE)              \
+    load_subtile(st + 2, FREE);                           \
+    __builtin_amdgcn_sched_barrier(0);                    \
+    step(st, CUR, PREV, true_type{});                     \
+    ++st;                                                 \
+    if (buffered == kFlush) flush_labels(st - 1);         \
+    phase = PHASE;
             while (st < last) {
-                load_subtile(st + 1, x2);
-                __builtin_amdgcn_sched_barrier(0);
-                step(st, x1, x0, true_type{});
-                ++st;
-                if (buffered == kFlush) flush_labels(st - 1);
-                phase = 1;
+                EP_PIPE_STEP(x1, x0, x3, 1)
                 if (st >= last) break;
-                load_subtile(st + 1, x0);
-                __builtin_amdgcn_sched_barrier(0);
-                step(st, x2, x1, true_type{});
-                ++st;
-                if (buffered == kFlush) flush_labels(st - 1);
-                phase = 2;
+                EP_PIPE_STEP(x2, x1, x0, 2)
                 if (st >= last) break;
-                load_subtile(st + 1, x1);
-                __builtin_amdgcn_sched_barrier(0);
-                step(st, x0, x2, true_type{});
-                ++st;
-                if (buffered == kFlush) flush_labels(st - 1);
-                phase = 0;
+                EP_PIPE_STEP(x3, x2, x1, 3)
+                if (st >= last) break;
+                EP_PIPE_STEP(x0, x3, x2, 0)
             }
-            if (phase == 0) drain(x0); else if (phase == 1) drain(x1); else drain(x2);
+#undef EP_PIPE_STEP
+            if (phase == 0) drain(x0); else if (phase == 1) drain(x1); else if (phase == 2) drain(x2); else drain(x3);
             flush_labels(st);
         }
     } else {
@@ -557,7 +573,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     // ---- objective partials of this workgroup (fixed order) ----
     if (MODE != kUpdateOnly && s_part) {
         double os = obj_s, ox = obj_x;
-        if (kLdsSums && MODE == kFused && c != 0) os = 0.0;   // that path keeps the same sum in all 16 lanes of a row
+        if (kLdsSums && c != 0) os = 0.0;   // k > 16: all 16 lanes of a row hold the same sum
         for (int off = 32; off > 0; off >>= 1) {
             os += __shfl_down(os, off, 64);
             if (XSQ) ox += __shfl_down(ox, off, 64);
