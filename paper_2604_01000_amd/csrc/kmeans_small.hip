@@ -73,6 +73,29 @@ __device__ __forceinline__ int float_key(float f) {
 }
 __device__ __forceinline__ float key_float(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
 
+// x0 = h0 + m0 + l0 and x1 = h1 + m1 + l1 exactly, every term a bf16: each term is what is left,
+// rounded to nearest even (fp32 has 24 significant bits, bf16 has 8, and both remainders are exact
+// in fp32).  The results are packed two to a word, x0's in the low half.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+struct Split3 {
+    unsigned h, m, l;
+};
+__device__ __forceinline__ Split3 split3_pair(float x0, float x1) {
+    Split3 t;
+    t.h = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{x0, x1}, bf16x2_t));
+    const float r0 = x0 - __uint_as_float(t.h << 16), r1 = x1 - __uint_as_float(t.h & 0xffff0000u);
+    t.m = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{r0, r1}, bf16x2_t));
+    const float s0 = r0 - __uint_as_float(t.m << 16), s1 = r1 - __uint_as_float(t.m & 0xffff0000u);
+    t.l = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{s0, s1}, bf16x2_t));
+    return t;
+}
+__device__ __forceinline__ f32x4 mfma_bf16_k32(const u32x4 &a, const u32x4 &b, const f32x4 &acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                   acc, 0, 0, 0);
+}
+
 // Dynamic LDS of lloyd_small_kernel: floats (transposition tiles, or per-wave tables of sums for
 // k > 16) followed by the per-wave label buffers.
 template <int D, int KT>
@@ -156,7 +179,17 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
 
     // Centroid operand of the assignment product: lane (g, c) holds, for centroid 16*mt + c,
     // columns 16j + 4g .. 16j + 4g + 3 for every j.  Padding centroids can never win.
-    f32x4 creg[KT][NJ];
+    //
+    // k > 16 (kSplit): the fp32 matrix instructions would bound the kernel (2 k d flop per point at a
+    // sixteenth of the bf16 rate), so x and c are each written as an exact sum of three bf16 terms
+    // h + m + l and x.c is taken as the six bf16 products hh + hm + mh + hl + lh + mm with fp32
+    // accumulation.  The dropped products (ml, lm, ll) are below 2^-23 |x_i c_i|, the size of fp32
+    // rounding itself.  One bf16 instruction covers 32 columns: columns 16(2s) + 4g .. + 3 and
+    // 16(2s+1) + 4g .. + 3 for K-step s, the same for both operands (the reduction index is free).
+    constexpr bool kSplit = KT >= 2;
+    constexpr int KS = D / 32;       // K-steps of the bf16 instruction
+    f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
+    u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kSplit ? KT : 1][kSplit ? KS : 1], cl[kSplit ? KT : 1][kSplit ? KS : 1];
     float hn[KT];
     if (MODE != kUpdateOnly) {
 #pragma unroll
@@ -168,7 +201,14 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             for (int j = 0; j < NJ; ++j) {
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
                 if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
-                creg[mt][j] = v;
+                if constexpr (kSplit) {
+                    const int s = j >> 1, w = 2 * (j & 1);
+                    const Split3 lo = split3_pair(v[0], v[1]), hi = split3_pair(v[2], v[3]);
+                    ch[mt][s][w] = lo.h, cm[mt][s][w] = lo.m, cl[mt][s][w] = lo.l;
+                    ch[mt][s][w + 1] = hi.h, cm[mt][s][w + 1] = hi.m, cl[mt][s][w + 1] = hi.l;
+                } else {
+                    creg[mt][j] = v;
+                }
             }
         }
     }
@@ -245,6 +285,33 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         buffered = 0;
     };
 
+    // Scores of a sub-tile on the bf16 instructions (kSplit): acc[mt] += x . c over all columns, small
+    // products first.  The operands of K-step s + 1 are split while the products of K-step s are
+    // issued; after_group(i) is called after each of the 6 * KS groups of KT instructions.
+    u32x4 xh[2], xm[2], xl[2];
+    auto split_x = [&](const f32x4(&x)[NX], int s, int pr) {   // pair pr (0..3) of K-step s
+        const f32x4 &v = x[2 * s + (pr >> 1)];
+        const Split3 t = split3_pair(v[2 * (pr & 1)], v[2 * (pr & 1) + 1]);
+        xh[s & 1][pr] = t.h, xm[s & 1][pr] = t.m, xl[s & 1][pr] = t.l;
+    };
+    auto split_scores = [&](const f32x4(&x)[NX], f32x4(&acc)[KT], auto &&after_group) {
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) split_x(x, 0, pr);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int pp = 0; pp < 6; ++pp) {   // xh.cl, xl.ch, xm.cm, xh.cm, xm.ch, xh.ch
+                const u32x4 &a = pp == 1 ? xl[s & 1] : (pp == 2 || pp == 4) ? xm[s & 1] : xh[s & 1];
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    const u32x4 &b = pp == 0 ? cl[mt][s] : (pp == 2 || pp == 3) ? cm[mt][s] : ch[mt][s];
+                    acc[mt] = mfma_bf16_k32(a, b, acc[mt]);
+                }
+                if (pp < 4 && s + 1 < KS) split_x(x, s + 1, pp);
+                after_group(s * 6 + pp);
+            }
+    };
+
     auto process = [&](int64_t st, const f32x4(&x)[NX]) {
         const int64_t row0 = st * kSub;
         const int rows_here = (int)min((int64_t)kSub, n - row0);  // uniform
@@ -258,28 +325,29 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 for (int j = 0; j < NJ; ++j) *reinterpret_cast<f32x4 *>(tile + c * STRIDE + 16 * j + 4 * g) = x[j];
             }
 
-            // scores: two accumulation chains per centroid tile (even / odd j), added at the end; with
-            // four tiles one chain, since KT - 1 other instructions already separate dependent ones
-            // (the same arithmetic as the pipelined loop below: both give the same scores bit for bit)
-            constexpr bool kTwoChains = KT < 4;
+            // scores.  k <= 16: fp32 matrix instructions, two accumulation chains per centroid tile
+            // (even / odd j), added at the end.  k > 16: bf16 split products (the same arithmetic as the
+            // pipelined loop below: both give the same scores bit for bit)
             f32x4 acc0[KT], acc1[KT];
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
                 acc0[mt] = f32x4{hn[mt], hn[mt], hn[mt], hn[mt]};
                 acc1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
+            if constexpr (kSplit) {
+                split_scores(x, acc0, [](int) {});
+            } else {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int mt = 0; mt < KT; ++mt) {
-                        if (kTwoChains && (j & 1))
-                            acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
-                        else
-                            acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
-                    }
-            if (kTwoChains) {
+                        for (int mt = 0; mt < KT; ++mt) {
+                            if (j & 1)
+                                acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
+                            else
+                                acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
+                        }
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt) acc0[mt] += acc1[mt];
             }
@@ -384,18 +452,20 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     };
 
     if constexpr (kLdsSums && MODE == kFused) {
-        // k > 16, fused round, one wave per SIMD: everything that is not a matrix instruction (arg-max,
-        // labels, ranks, the row adds into the LDS sums) is done one sub-tile late, in the issue slots
-        // between the matrix instructions of the next sub-tile.  A sub-tile's scores need KT * D / 4
-        // matrix instructions of 32 cycles each; the deferred work of the previous sub-tile is cut into
-        // D / 4 slices that are placed, in program order, one after every group of KT instructions.
-        // The slices hold no branch (lanes with nothing to do write to scrap words instead), so the
-        // whole step is one basic block whose order the scheduling barriers fix.
+        // k > 16, fused round, one wave per SIMD: everything that is not part of the score product
+        // (arg-max, labels, ranks, the row adds into the LDS sums) is done one sub-tile late, in the
+        // issue slots between the matrix instructions of the next sub-tile.  The deferred work of the
+        // previous sub-tile is a list of items (4 arg-max, label store, 2 rank halves, one per 16-byte
+        // piece of the fixed row-add rounds) spread evenly, in program order, over the 6 * KS groups of
+        // matrix instructions.  The items hold no branch (lanes with nothing to do write to scrap
+        // words instead), so the whole step is one basic block whose order the scheduling barriers fix.
         constexpr int kFixedRounds = D >= 128 ? 3 : 2;   // these ranks without branches; higher ranks (rare) in a loop
-        constexpr int kFirstAdd = 7;                       // slices 0 .. 6: arg-max (4), labels, rank (2)
+        constexpr int kFirstAdd = 7;                       // items 0 .. 6: arg-max (4), labels, rank (2)
+        constexpr int kItems = kFirstAdd + kFixedRounds * NJ;
+        constexpr int kGroups = 6 * KS;
         __shared__ __attribute__((aligned(16))) int32_t scrap[4 * kBlock];   // 16 bytes per lane, written by idle lanes, never read
         float *dummy = wsums + 16 * KT * STRIDE + 4 * g;   // the extra row idle lanes add to; never read
-        f32x4 scp[KT];         // previous sub-tile: scores (sum of the two chains)
+        f32x4 scp[KT];         // previous sub-tile: scores
         int prev_rows = 0;     // rows of the previous sub-tile
         int bkeyp[4];
         int32_t labp[4];
@@ -404,7 +474,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         float *rowp = dummy;
         f32x4 pending = {0.f, 0.f, 0.f, 0.f};   // LDS read of the next row-add piece, in flight
 
-        auto slice = [&](int b, const f32x4(&xp)[NX]) {   // b = 0 .. D/4 - 1, uniform
+        auto item = [&](int b, const f32x4(&xp)[NX]) {   // b = 0 .. kItems - 1, uniform
             if (b < 4) {   // arg-max of point group v = b
                 const int v = b;
                 float sc = scp[0][v];
@@ -442,10 +512,10 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 if (lab_c < 0) rank = -1;
                 rowp = wsums + (lab_c < 0 ? 0 : lab_c) * STRIDE + 4 * g;
                 pending = *reinterpret_cast<const f32x4 *>((rank == 0 ? rowp : dummy));   // read of piece 0
-            } else if (b < kFirstAdd + kFixedRounds * NJ) {
-                // one 16-byte piece of one round of row adds; its read was issued one slice earlier, the
+            } else {
+                // one 16-byte piece of one round of row adds; its read was issued one item earlier, the
                 // next piece's read is issued here (a round never touches a column group twice, and the
-                // same column group of the next round comes NJ slices later)
+                // same column group of the next round comes NJ items later)
                 const int q = b - kFirstAdd, r = q / NJ, j = q % NJ;
                 f32x4 *p = reinterpret_cast<f32x4 *>((rank == r ? rowp : dummy) + 16 * j);
                 const f32x4 sum = pending + xp[j];
@@ -468,40 +538,25 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 wave_lds_fence();
             }
         };
-        static_assert(kFirstAdd + kFixedRounds * NJ <= D / 4, "the deferred work must fit the slices");
 
         // scores of sub-tile st (in x); with DEFERRED, the previous sub-tile's (in xp) other work in between
         auto step = [&](int64_t st, const f32x4(&x)[NX], const f32x4(&xp)[NX], auto deferred) {
             constexpr bool DEFERRED = decltype(deferred)::value;
-            // KT independent accumulators already separate dependent matrix instructions by KT - 1
-            // others; a second chain per tile is only needed when that is too few.
-            constexpr bool kTwoChains = KT < 4;
-            f32x4 acc0[KT], acc1[KT];
+            f32x4 acc[KT];
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt) {
-                acc0[mt] = f32x4{hn[mt], hn[mt], hn[mt], hn[mt]};
-                acc1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int b = 0; b < D / 4; ++b) {
-                const int j = b >> 2, e = b & 3;
-#pragma unroll
-                for (int mt = 0; mt < KT; ++mt) {
-                    if (kTwoChains && (j & 1))
-                        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc1[mt], 0, 0, 0);
-                    else
-                        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[j][e], creg[mt][j][e], acc0[mt], 0, 0, 0);
-                }
+            for (int mt = 0; mt < KT; ++mt) acc[mt] = f32x4{hn[mt], hn[mt], hn[mt], hn[mt]};
+            split_scores(x, acc, [&](int grp) {
                 if (DEFERRED) {
-                    slice(b, xp);
+#pragma unroll
+                    for (int b = grp * kItems / kGroups; b < (grp + 1) * kItems / kGroups; ++b) item(b, xp);
                     __builtin_amdgcn_sched_barrier(0);   // pin the interleaving
                 }
-            }
+            });
             // the scores are pinned here, in the block of the matrix instructions, so that no later
             // block is a better place for them in the compiler's eyes
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
-                scp[mt] = kTwoChains ? acc0[mt] + acc1[mt] : acc0[mt];
+                scp[mt] = acc[mt];
                 asm volatile("" : "+v"(scp[mt]));
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -510,43 +565,39 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         };
         auto drain = [&](const f32x4(&xp)[NX]) {   // the last sub-tile's deferred work, no matrix work to hide in
 #pragma unroll
-            for (int b = 0; b < D / 4; ++b) slice(b, xp);
+            for (int b = 0; b < kItems; ++b) item(b, xp);
             finish_prev(xp);
         };
         using std::false_type;
         using std::true_type;
 
-        // Four register sets in rotation: current, previous (still needed for its row adds) and the
-        // next two, in flight.  With one wave per SIMD a single sub-tile in flight per wave does not
-        // cover the memory latency (8 KB x 1024 waves in flight moves about 3 TB/s).
-        f32x4 x0[NX], x1[NX], x2[NX], x3[NX];
+        // Three register sets in rotation: current, previous (still needed for its row adds), next (in
+        // flight).  A fourth set (two sub-tiles in flight) was measured and bought nothing.
+        f32x4 x0[NX], x1[NX], x2[NX];
         int64_t st = first;
         if (first < last) {
             load_subtile(st, x0);
             load_subtile(st + 1, x1);
-            load_subtile(st + 2, x2);
             __builtin_amdgcn_sched_barrier(0);
             step(st, x0, x0, false_type{});
             ++st;
             int phase = 0;   // which set holds the previous sub-tile when the loop ends
 #define EP_PIPE_STEP(CUR, PREV, FREE, PHASE)              \
-    load_subtile(st + 2, FREE);                           \
+    load_subtile(st + 1, FREE);                           \
     __builtin_amdgcn_sched_barrier(0);                    \
     step(st, CUR, PREV, true_type{});                     \
     ++st;                                                 \
     if (buffered == kFlush) flush_labels(st - 1);         \
     phase = PHASE;
             while (st < last) {
-                EP_PIPE_STEP(x1, x0, x3, 1)
+                EP_PIPE_STEP(x1, x0, x2, 1)
                 if (st >= last) break;
                 EP_PIPE_STEP(x2, x1, x0, 2)
                 if (st >= last) break;
-                EP_PIPE_STEP(x3, x2, x1, 3)
-                if (st >= last) break;
-                EP_PIPE_STEP(x0, x3, x2, 0)
+                EP_PIPE_STEP(x0, x2, x1, 0)
             }
 #undef EP_PIPE_STEP
-            if (phase == 0) drain(x0); else if (phase == 1) drain(x1); else if (phase == 2) drain(x2); else drain(x3);
+            if (phase == 0) drain(x0); else if (phase == 1) drain(x1); else drain(x2);
             flush_labels(st);
         }
     } else {
