@@ -211,6 +211,20 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                 }
             }
         }
+        if constexpr (kSplit) {
+            // The 3 * KT * KS operands are only ever read by matrix instructions: pin them to the
+            // accumulation registers, which those instructions read directly.  Left to itself the
+            // register allocator parks them there as spilled vector registers and copies four
+            // words back before every instruction.
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    asm volatile("" : "+a"(ch[mt][s]));
+                    asm volatile("" : "+a"(cm[mt][s]));
+                    asm volatile("" : "+a"(cl[mt][s]));
+                }
+        }
     }
 
     f32x4 accu[KT][NJ];  // sums: lane (g, c), register v <-> centroid 16*mt + 4g + v, column col(t, c)
