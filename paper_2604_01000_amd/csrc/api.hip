@@ -59,11 +59,7 @@ bool small_k(const ep_problem &p) { return (int64_t)p.k * p.d <= kSmallKElems; }
 
 int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
               float *min_d2, double *objective, hipStream_t s) {
-    if (small_path_supported(p)) {
-        int rc = launch_small_half_norms(p, C, w, s);
-        if (rc != EP_OK) return rc;
-        return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
-    }
+    if (small_path_supported(p)) return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
     if (large_path_supported(p)) return launch_large_assign(p, X, C, w, labels, min_d2, objective, s);
     int rc = launch_prep_centroids(p, C, w, s);
     if (rc != EP_OK) return rc;
@@ -189,7 +185,6 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (small_path_supported(*p)) {  // fused rounds: X is read once per round
-        if (iters > 0 && (rc = launch_small_half_norms(*p, C, w, s)) != EP_OK) return rc;
         for (int32_t t = 0; t < iters; ++t)
             if ((rc = launch_small_round(*p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
                                          t == 0, s)) != EP_OK)

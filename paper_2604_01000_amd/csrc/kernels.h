@@ -40,14 +40,12 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
 // ---- K-Means, k <= 64, d in {64,128}, fp32: fused matrix-core kernels (kmeans_small.hip) --------
 constexpr int kSmallMaxBlocks = 512;  // workgroups (= partial sums) per launch; <= kUpdBlocksMax
 bool small_path_supported(const ep_problem &p);
-// w.cnorm holds -||c||^2/2 on this path.
-int launch_small_half_norms(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s);
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s);
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
-// One fused round: assign against C (whose half norms are in w.cnorm), sums, then C <- means
-// (in place), w.cnorm <- half norms of the new C, *objective <- this round's objective.
+// One fused round: assign against C, sums, then C <- means (in place), *objective <- this
+// round's objective.
 // first_round: the data-only term of the objective (sum ||x||^2) is computed and kept in the
 // workspace; later rounds of the same kmeans_run reuse it.
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,

@@ -148,7 +148,7 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 template <int D, int KT, int MODE, bool XSQ>
 __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) void lloyd_small_kernel(
     int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const float *__restrict__ X,
-    const float *__restrict__ C, const float *__restrict__ hneg, int32_t *__restrict__ labels_out,
+    const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
     int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part) {
     constexpr int NJ = D / 16;       // 16-byte pieces per lane in the transposed layout; also column tiles
@@ -190,17 +190,19 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     constexpr int KS = D / 32;       // K-steps of the bf16 instruction
     f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
     u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kSplit ? KT : 1][kSplit ? KS : 1], cl[kSplit ? KT : 1][kSplit ? KS : 1];
-    float hn[KT];
+    float hn[KT];   // -||c||^2 / 2 of centroid 16*mt + c: the value the score accumulators start from
     if (MODE != kUpdateOnly) {
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) {
             const int cent = 16 * mt + c;
             const bool real = cent < k;
-            hn[mt] = real ? hneg[cent] : -3.0e38f;
+            double nacc = 0.0;   // this lane's quarter of ||c||^2, in fp64, columns in ascending order
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
                 if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) nacc = fma((double)v[e], (double)v[e], nacc);
                 if constexpr (kSplit) {
                     const int s = j >> 1, w = 2 * (j & 1);
                     const Split3 lo = split3_pair(v[0], v[1]), hi = split3_pair(v[2], v[3]);
@@ -210,6 +212,11 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
                     creg[mt][j] = v;
                 }
             }
+            // the four lanes (g = 0..3) that hold the centroid add their quarters pairwise; the two
+            // additions commute, so all four get the same bits
+            nacc += __shfl_xor(nacc, 16, 64);
+            nacc += __shfl_xor(nacc, 32, 64);
+            hn[mt] = real ? (float)(-0.5 * nacc) : -3.0e38f;
         }
         if constexpr (kSplit) {
             // The 3 * KT * KS operands are only ever read by matrix instructions: pin them to the
@@ -732,43 +739,35 @@ __device__ __forceinline__ void write_objective(const double *__restrict__ s_par
     }
 }
 
-// hneg[j] = -||c_j||^2 / 2, accumulated in fp64.  One wave per centroid.
-__global__ __launch_bounds__(kBlock) void half_norms_kernel(int32_t d, int32_t k, const float *__restrict__ C,
-                                                             float *__restrict__ hneg) {
-    const int j = blockIdx.x * kWaves + (threadIdx.x >> 6);
-    if (j >= k) return;
-    const int lane = threadIdx.x & 63;
-    double acc = 0.0;
-    for (int m = lane; m < d; m += 64) {
-        const double v = (double)C[(int64_t)j * d + m];
-        acc += v * v;
-    }
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-    if (lane == 0) hneg[j] = (float)(-0.5 * acc);
-}
-
-// Second pass of a round.  Workgroup j forms centroid j.  Thread (seg, m4) reads columns 4 m4 .. + 3
-// of the partials b = seg, seg + S, ... with 16-byte loads, 16 at a time in flight, and adds them in
-// fp64 in ascending order; the S segment sums are then added in segment order, divided by the
-// count and rounded to fp32; an empty cluster keeps its centroid.  The workgroup also leaves
-// -||c_j||^2/2 for the next round and, in workgroup 0, the round's objective.
+// Second pass of a round.  Workgroup (j, slice) forms 32 columns of centroid j.  Thread (seg, m4)
+// reads columns 4 m4 .. + 3 of the slice from the partials b = seg, seg + 64, ... with 16-byte
+// loads, all in flight at once (parts <= 512: at most 8), and adds them in fp64 in ascending
+// order; the 64 segment sums are then added in segment order, divided by the count and rounded
+// to fp32; an empty cluster keeps its centroid.  Workgroup 0 also forms the round's objective.
 constexpr int kFinBlock = 512;
+constexpr int kFinCols = 32;                       // columns per workgroup
+constexpr int kFinSegs = kFinBlock / (kFinCols / 4);
+constexpr int kFinBatch = kSmallMaxBlocks / kFinSegs;
 __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
     int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
     const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
     double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
-    int64_t *__restrict__ counts, float *__restrict__ hneg, double *__restrict__ objective) {
-    __shared__ double seg_sum[kFinBlock * 4];
-    __shared__ float cn[128];
+    int64_t *__restrict__ counts, double *__restrict__ objective) {
+    __shared__ double seg_sum[kFinSegs * kFinCols];
     __shared__ unsigned long long total_cnt;
-    const int j = blockIdx.x, t = threadIdx.x;
-    const int quads = d / 4;                          // 16-byte column groups per row: 32 or 16
-    const int m4 = t % quads, seg = t / quads, segs = kFinBlock / quads;
-    // The loads of this thread are issued before anything is waited for: its partial count, then
-    // the partial sums 16 at a time (parts <= 512, segs >= 16: at most two batches).
+    const int slices = d / kFinCols;
+    const int j = blockIdx.x / slices, col0 = kFinCols * (blockIdx.x % slices), t = threadIdx.x;
+    const int m4 = t % (kFinCols / 4), seg = t / (kFinCols / 4);
+    // every load of this thread is issued before anything is waited for
     const int32_t my_cnt = t < parts ? pcnt[(int64_t)t * k + j] : 0;
-    const float4 *col = reinterpret_cast<const float4 *>(psum + (int64_t)j * d) + m4;
+    const float4 *col = reinterpret_cast<const float4 *>(psum + (int64_t)j * d + col0) + m4;
     const int64_t stride4 = (int64_t)k * d / 4;
+    float4 v[kFinBatch];
+#pragma unroll
+    for (int q = 0; q < kFinBatch; ++q) {
+        const int b = seg + q * kFinSegs;
+        v[q] = b < parts ? col[(int64_t)b * stride4] : float4{0.f, 0.f, 0.f, 0.f};
+    }
     if (t == 0) total_cnt = 0;
     __syncthreads();
     {   // counts: added per wave, then one LDS atomic per wave (integers: order-free)
@@ -777,47 +776,26 @@ __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
         if ((t & 63) == 0 && c) atomicAdd(&total_cnt, (unsigned long long)c);
     }
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    for (int b0 = seg; b0 < parts; b0 += 16 * segs) {
-        float4 v[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int b = b0 + q * segs;
-            v[q] = b < parts ? col[(int64_t)b * stride4] : float4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {   // ascending workgroup order; missing partials add +0.0
-            s0 += (double)v[q].x;
-            s1 += (double)v[q].y;
-            s2 += (double)v[q].z;
-            s3 += (double)v[q].w;
-        }
+    for (int q = 0; q < kFinBatch; ++q) {   // ascending workgroup order; missing partials add +0.0
+        s0 += (double)v[q].x;
+        s1 += (double)v[q].y;
+        s2 += (double)v[q].z;
+        s3 += (double)v[q].w;
     }
-    seg_sum[(seg * quads + m4) * 4 + 0] = s0;
-    seg_sum[(seg * quads + m4) * 4 + 1] = s1;
-    seg_sum[(seg * quads + m4) * 4 + 2] = s2;
-    seg_sum[(seg * quads + m4) * 4 + 3] = s3;
+    seg_sum[seg * kFinCols + 4 * m4 + 0] = s0;
+    seg_sum[seg * kFinCols + 4 * m4 + 1] = s1;
+    seg_sum[seg * kFinCols + 4 * m4 + 2] = s2;
+    seg_sum[seg * kFinCols + 4 * m4 + 3] = s3;
     __syncthreads();
-    if (t < d) {
+    if (t < kFinCols) {
         double tot = seg_sum[t];
-        for (int q = 1; q < segs; ++q) tot += seg_sum[q * d + t];
+        for (int q = 1; q < kFinSegs; ++q) tot += seg_sum[q * kFinCols + t];
         const int64_t cc = (int64_t)total_cnt;
-        const float cnew = cc > 0 ? (float)(tot / (double)cc) : C_prev[(int64_t)j * d + t];
-        C_out[(int64_t)j * d + t] = cnew;
-        cn[t] = cnew;
-    }
-    __syncthreads();
-    if (t < 64) {  // same operations, in the same order, as half_norms_kernel
-        double acc = 0.0;
-        for (int mm = t; mm < d; mm += 64) {
-            const double v = (double)cn[mm];
-            acc += v * v;
-        }
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-        if (t == 0) {
-            hneg[j] = (float)(-0.5 * acc);
-            counts[j] = (int64_t)total_cnt;
-        }
-    } else if (t < 128 && j == 0 && objective) {  // second wave
+        const int64_t at = (int64_t)j * d + col0 + t;
+        C_out[at] = cc > 0 ? (float)(tot / (double)cc) : C_prev[at];
+        if (t == 0 && col0 == 0) counts[j] = cc;
+    } else if (t >= 64 && t < 128 && blockIdx.x == 0 && objective) {  // second wave
         write_objective(s_part, xsq_part, parts, fresh_xsq, xsq_total, objective, t - 64);
     }
 }
@@ -860,9 +838,8 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
         if (lds_bytes > 64 * 1024)                                                                            \
             EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
-        kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, w.cnorm,     \
-                                                   labels_out, labels_in, min_d2, w.psum, w.pcnt, sp,        \
-                                                   xsq_part_of(w));                                           \
+        kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, labels_out,  \
+                                                   labels_in, min_d2, w.psum, w.pcnt, sp, xsq_part_of(w));    \
     } while (0)
     if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
@@ -882,12 +859,6 @@ bool small_path_supported(const ep_problem &p) {
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }
 
-int launch_small_half_norms(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s) {
-    half_norms_kernel<<<(unsigned)ceil_div(p.k, kWaves), kBlock, 0, s>>>(p.d, p.k, C, w.cnorm);
-    EP_LAUNCH_CHECK();
-    return EP_OK;
-}
-
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s) {
     const float *Xf = static_cast<const float *>(X);
@@ -904,9 +875,9 @@ int launch_small_assign(const ep_problem &p, const void *X, const float *C, cons
 static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
                                  const KmeansWs &w, double *objective, bool fresh_xsq, hipStream_t s) {
     const int parts = small_blocks(p);
-    lloyd_small_finalize_kernel<<<p.k, kFinBlock, 0, s>>>(p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w),
-                                                          xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
-                                                          C_out, counts, w.cnorm, objective);
+    lloyd_small_finalize_kernel<<<p.k * (p.d / kFinCols), kFinBlock, 0, s>>>(
+        p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
+        C_out, counts, objective);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
