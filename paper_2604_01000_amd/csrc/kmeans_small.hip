@@ -191,48 +191,51 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
     u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kSplit ? KT : 1][kSplit ? KS : 1], cl[kSplit ? KT : 1][kSplit ? KS : 1];
     float hn[KT];   // -||c||^2 / 2 of centroid 16*mt + c: the value the score accumulators start from
-    if (MODE != kUpdateOnly) {
+    // Called after the first sub-tile's loads have been issued, so that the two latencies overlap.
+    auto load_centroids = [&]() {
+        if (MODE != kUpdateOnly) {
 #pragma unroll
-        for (int mt = 0; mt < KT; ++mt) {
-            const int cent = 16 * mt + c;
-            const bool real = cent < k;
-            double nacc = 0.0;   // this lane's quarter of ||c||^2, in fp64, columns in ascending order
+            for (int mt = 0; mt < KT; ++mt) {
+                const int cent = 16 * mt + c;
+                const bool real = cent < k;
+                double nacc = 0.0;   // this lane's quarter of ||c||^2, in fp64, columns in ascending order
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
+                for (int j = 0; j < NJ; ++j) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) nacc = fma((double)v[e], (double)v[e], nacc);
-                if constexpr (kSplit) {
-                    const int s = j >> 1, w = 2 * (j & 1);
-                    const Split3 lo = split3_pair(v[0], v[1]), hi = split3_pair(v[2], v[3]);
-                    ch[mt][s][w] = lo.h, cm[mt][s][w] = lo.m, cl[mt][s][w] = lo.l;
-                    ch[mt][s][w + 1] = hi.h, cm[mt][s][w + 1] = hi.m, cl[mt][s][w + 1] = hi.l;
-                } else {
-                    creg[mt][j] = v;
+                    for (int e = 0; e < 4; ++e) nacc = fma((double)v[e], (double)v[e], nacc);
+                    if constexpr (kSplit) {
+                        const int s = j >> 1, w = 2 * (j & 1);
+                        const Split3 lo = split3_pair(v[0], v[1]), hi = split3_pair(v[2], v[3]);
+                        ch[mt][s][w] = lo.h, cm[mt][s][w] = lo.m, cl[mt][s][w] = lo.l;
+                        ch[mt][s][w + 1] = hi.h, cm[mt][s][w + 1] = hi.m, cl[mt][s][w + 1] = hi.l;
+                    } else {
+                        creg[mt][j] = v;
+                    }
                 }
+                // the four lanes (g = 0..3) that hold the centroid add their quarters pairwise; the two
+                // additions commute, so all four get the same bits
+                nacc += __shfl_xor(nacc, 16, 64);
+                nacc += __shfl_xor(nacc, 32, 64);
+                hn[mt] = real ? (float)(-0.5 * nacc) : -3.0e38f;
             }
-            // the four lanes (g = 0..3) that hold the centroid add their quarters pairwise; the two
-            // additions commute, so all four get the same bits
-            nacc += __shfl_xor(nacc, 16, 64);
-            nacc += __shfl_xor(nacc, 32, 64);
-            hn[mt] = real ? (float)(-0.5 * nacc) : -3.0e38f;
-        }
-        if constexpr (kSplit) {
-            // The 3 * KT * KS operands are only ever read by matrix instructions: pin them to the
-            // accumulation registers, which those instructions read directly.  Left to itself the
-            // register allocator parks them there as spilled vector registers and copies four
-            // words back before every instruction.
+            if constexpr (kSplit) {
+                // The 3 * KT * KS operands are only ever read by matrix instructions: pin them to the
+                // accumulation registers, which those instructions read directly.  Left to itself the
+                // register allocator parks them there as spilled vector registers and copies four
+                // words back before every instruction.
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
+                for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    asm volatile("" : "+a"(ch[mt][s]));
-                    asm volatile("" : "+a"(cm[mt][s]));
-                    asm volatile("" : "+a"(cl[mt][s]));
-                }
+                    for (int s = 0; s < KS; ++s) {
+                        asm volatile("" : "+a"(ch[mt][s]));
+                        asm volatile("" : "+a"(cm[mt][s]));
+                        asm volatile("" : "+a"(cl[mt][s]));
+                    }
+            }
         }
-    }
+    };
 
     f32x4 accu[KT][NJ];  // sums: lane (g, c), register v <-> centroid 16*mt + 4g + v, column col(t, c)
     int32_t cnt[KT];
@@ -600,6 +603,7 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
             load_subtile(st, x0);
             load_subtile(st + 1, x1);
             __builtin_amdgcn_sched_barrier(0);
+            load_centroids();
             step(st, x0, x0, false_type{});
             ++st;
             int phase = 0;   // which set holds the previous sub-tile when the loop ends
@@ -626,6 +630,8 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
     f32x4 xa[NX], xb[NX];
     int64_t st = first;
     load_subtile(st, xa);
+    __builtin_amdgcn_sched_barrier(0);
+    load_centroids();
     while (st < last) {
         load_subtile(st + 1, xb);
         __builtin_amdgcn_sched_barrier(0);  // keep the whole prefetch ahead of the arithmetic
@@ -668,33 +674,32 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         }
         if ((int)threadIdx.x < k) pcnt[(int64_t)blockIdx.x * k + threadIdx.x] = cnt_lds[threadIdx.x];
     } else if (MODE != kAssignOnly) {
-        __syncthreads();  // every wave has left its tile
-        float *sums = lds;  // 16*KT x D floats
-#pragma unroll 1
-        for (int w = 0; w < kWaves; ++w) {
-            if (wave == w) {
+        // k <= 16: every wave stores its accumulators to its own LDS tile (the transposition tile, no
+        // longer needed), then all threads add the four copies in wave order.
+        static_assert(kSub * STRIDE >= 16 * D, "a wave's tile holds its 16 x D sums");
+        wave_lds_fence();
+        float *mine = lds + wave * kSub * STRIDE;
 #pragma unroll
-                for (int mt = 0; mt < KT; ++mt)
+        for (int v = 0; v < 4; ++v)
 #pragma unroll
-                    for (int t = 0; t < NJ; ++t)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            float *p = sums + (16 * mt + 4 * g + v) * D + 64 * (t >> 2) + 4 * c + (t & 3);
-                            *p = (w == 0 ? 0.f : *p) + accu[mt][t][v];
-                        }
-            }
-            __syncthreads();
-        }
-        for (int i = threadIdx.x; i < k * D; i += kBlock) psum[(int64_t)blockIdx.x * k * D + i] = sums[i];
-        // counts: lanes of a column hold the counts of the 4 groups' points
+            for (int h = 0; h < NH; ++h)   // columns 64h + 4c .. + 3 of row 4g + v are tiles t = 4h .. 4h + 3
+                *reinterpret_cast<f32x4 *>(mine + (4 * g + v) * D + 64 * h + 4 * c) =
+                    f32x4{accu[0][4 * h][v], accu[0][4 * h + 1][v], accu[0][4 * h + 2][v], accu[0][4 * h + 3][v]};
         if (threadIdx.x < 16 * KT) cnt_lds[threadIdx.x] = 0;
         __syncthreads();
+        // counts: lanes of a column hold the counts of the 4 groups' points
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) {
             int32_t v = cnt[mt];
             v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
             if (g == 0 && v) atomicAdd(&cnt_lds[16 * mt + c], v);
+        }
+        for (int i = threadIdx.x; i < k * D / 4; i += kBlock) {
+            f32x4 v = *reinterpret_cast<const f32x4 *>(lds + 4 * i);
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) v += *reinterpret_cast<const f32x4 *>(lds + w * kSub * STRIDE + 4 * i);
+            *reinterpret_cast<f32x4 *>(psum + (int64_t)blockIdx.x * k * D + 4 * i) = v;
         }
         __syncthreads();
         if ((int)threadIdx.x < k) pcnt[(int64_t)blockIdx.x * k + threadIdx.x] = cnt_lds[threadIdx.x];
