@@ -46,9 +46,7 @@ constexpr int kTile = 32;            // centroids per tile record, points per op
 #ifndef EP_LARGE_OCC
 #define EP_LARGE_OCC 2
 #endif
-constexpr int kPointTiles = EP_LARGE_POINT_TILES;  // operand tiles of points a wave keeps in registers
-constexpr int kPointsPerWave = kTile * kPointTiles;
-constexpr int kPair = kPointTiles % 2 == 0 ? 2 : 1;  // point tiles accumulated together
+constexpr int kMainPointTiles = EP_LARGE_POINT_TILES;  // operand tiles of points a wave keeps in registers
 constexpr float kNever = -3.0e38f;   // bias of a padding centroid
 
 template <int D> constexpr int record_bytes() { return (D / 16) * 1024 + kTile * 4; }
@@ -102,11 +100,15 @@ __global__ __launch_bounds__(kBlock) void large_prep_kernel(int32_t k, const flo
 }
 
 // ---- 2. matrix-core sweep ------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int64_t n, int64_t ld, int32_t tiles,
-                                                                  const bf16_t *__restrict__ X,
+// Rows [row_begin, n) in blocks of PT * 32 rows per wave, PT even.
+template <int D, int PT>
+__global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int64_t row_begin, int64_t n, int64_t ld,
+                                                                  int32_t tiles, const bf16_t *__restrict__ X,
                                                                   const unsigned char *__restrict__ records,
                                                                   int32_t *__restrict__ best_code) {
+    constexpr int kPointTiles = PT;
+    constexpr int kPointsPerWave = kTile * kPointTiles;
+    static_assert(kPointTiles % 2 == 0, "two accumulators alternate over the point tiles");
     constexpr int NS = D / 16;
     constexpr int REC = record_bytes<D>();
     constexpr int REC16 = REC / 16;                    // 16-byte pieces per record
@@ -117,37 +119,42 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 31, half = lane >> 5;
 
-    const int64_t wave_blocks = (n + kPointsPerWave - 1) / kPointsPerWave;
+    const int64_t wave_blocks = (n - row_begin + kPointsPerWave - 1) / kPointsPerWave;
     const int64_t wg_blocks = (wave_blocks + kWaves - 1) / kWaves;
 
-    auto stage_load = [&](int tile, uint4(&regs)[STAGE]) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(records + (int64_t)tile * REC);
-#pragma unroll
-        for (int q = 0; q < STAGE; ++q) {
-            const int piece = q * kBlock + threadIdx.x;
-            regs[q] = piece < REC16 ? src[piece] : uint4{0, 0, 0, 0};
-        }
+    // A record travels global -> registers -> LDS, STAGE (<= 3) 16-byte pieces per thread.
+    static_assert(STAGE <= 3, "three staging registers per thread");
+    struct Staged {
+        uint4 v0, v1, v2;
     };
-    auto stage_store = [&](int slot, const uint4(&regs)[STAGE]) {
+    auto stage_load = [&](int tile) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(records + (int64_t)tile * REC);
+        const int t0 = threadIdx.x;   // always a valid address; the store drops the excess
+        Staged r;
+        r.v0 = src[t0 < REC16 ? t0 : REC16 - 1];
+        r.v1 = STAGE > 1 ? src[t0 + kBlock < REC16 ? t0 + kBlock : REC16 - 1] : uint4{0, 0, 0, 0};
+        r.v2 = STAGE > 2 ? src[t0 + 2 * kBlock < REC16 ? t0 + 2 * kBlock : REC16 - 1] : uint4{0, 0, 0, 0};
+        return r;
+    };
+    auto stage_store = [&](int slot, const Staged &r) {
         uint4 *dst = reinterpret_cast<uint4 *>(ring[slot]);
-#pragma unroll
-        for (int q = 0; q < STAGE; ++q) {
-            const int piece = q * kBlock + threadIdx.x;
-            if (piece < REC16) dst[piece] = regs[q];
-        }
+        const int t0 = threadIdx.x;
+        if (t0 < REC16) dst[t0] = r.v0;
+        if (STAGE > 1 && t0 + kBlock < REC16) dst[t0 + kBlock] = r.v1;
+        if (STAGE > 2 && t0 + 2 * kBlock < REC16) dst[t0 + 2 * kBlock] = r.v2;
     };
 
     for (int64_t wb = blockIdx.x; wb < wg_blocks; wb += gridDim.x) {
-        const int64_t row0 = (wb * kWaves + wave) * kPointsPerWave;
+        const int64_t row0 = row_begin + (wb * kWaves + wave) * kPointsPerWave;
         // Point operand: piece (p, s) of lane (half, col) = row row0 + 32 p + col, columns 16 s + 8 half .. + 7.
         // Buffer loads with a descriptor that ends at the last valid row: rows past n read as zeros.
         bf16x8 xb[kPointTiles][NS];
         {
             const int64_t rows_here = min((int64_t)kPointsPerWave, n - row0);
-            const bool live = rows_here > 0;
-            const int bytes = live ? (int)(((rows_here - 1) * ld + D) * 2) : 0;
+            const bool any = rows_here > 0;
+            const int bytes = any ? (int)(((rows_here - 1) * ld + D) * 2) : 0;
             __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<bf16_t *>(X + (live ? row0 : 0) * ld), 0, bytes, 0x00020000);
+                const_cast<bf16_t *>(X + (any ? row0 : 0) * ld), 0, bytes, 0x00020000);
 #pragma unroll
             for (int p = 0; p < kPointTiles; ++p) {
                 const int voff = (int)(((32 * p + col) * ld + 8 * half) * 2);
@@ -158,90 +165,109 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
                 }
             }
         }
-        float best[kPointTiles], bquad[kPointTiles][4];   // best score, and the group maxima of the tile it came from
-        int32_t btile[kPointTiles];
+        // Per point tile: the best score so far and the code of the group of 4 consecutive centroid
+        // rows it came from, code = 8 tile + 2 group (+ half, added at the end).
+        float best[kPointTiles];
+        int32_t bcode[kPointTiles];
 #pragma unroll
         for (int p = 0; p < kPointTiles; ++p) {
             best[p] = kNever;
-            btile[p] = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bquad[p][j] = kNever;
+            bcode[p] = 0;
         }
 
         // ring prologue: records 0 and 1
         __syncthreads();  // the previous block's readers are done with the ring
         {
-            uint4 regs[STAGE];
-            stage_load(0, regs);
-            stage_store(0, regs);
-            if (tiles > 1) {
-                stage_load(1, regs);
-                stage_store(1, regs);
-            }
+            stage_store(0, stage_load(0));
+            if (tiles > 1) stage_store(1, stage_load(1));
         }
         __syncthreads();
 
+        // Epilogue of one 32 x 32 product: this lane holds 16 centroid rows of one point as 4 groups of
+        // 4 consecutive rows.  Group maxima, their maximum, one compare, two selects.  Ties keep
+        // the earlier tile (strict >) and, inside a tile, the lower group.
+        float qm[4];
+        auto fold = [&](int piece, const f32x16 &acc, int p, int t) {   // pieces 0 .. 4, in order
+            if (piece < 4) {
+                const int j = piece;
+                qm[j] = fmaxf(fmaxf(fmaxf(acc[4 * j], acc[4 * j + 1]), acc[4 * j + 2]), acc[4 * j + 3]);
+            } else {
+                const float m = fmaxf(fmaxf(fmaxf(qm[0], qm[1]), qm[2]), qm[3]);
+                // lowest group that holds the maximum, as 0/1 arithmetic (a chain of selects here is
+                // turned into branches by the compiler, which would split the instruction stream)
+                const int e0 = qm[0] == m, e1 = qm[1] == m, e2 = qm[2] == m;
+                const int grp = (1 - e0) * (1 + (1 - e1) * (2 - e2));
+                const bool better = m > best[p];
+                best[p] = better ? m : best[p];
+                bcode[p] = better ? 8 * t + 2 * grp : bcode[p];
+            }
+        };
+
+        // One accumulation chain per point tile (a chain of dependent matrix instructions runs at
+        // the full rate), two accumulators in alternation: while the chain of point tile p runs, the
+        // finished accumulator of the previous point tile is folded on the vector unit, so a wave
+        // keeps the matrix pipe fed by itself instead of relying on the other wave of its SIMD
+        // being out of phase.
+        f32x16 acc[2];
+        // bias of the 16 centroid rows this lane's accumulators stand for (rows 8 (v/4) + 4 half + v%4),
+        // read from the record straight into the accumulator that the next chain starts from
+        auto load_bias = [&](const unsigned char *rec) {
+            f32x16 b;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 b4 = *reinterpret_cast<const f32x4 *>(rec + NS * 1024 + (8 * q + 4 * half) * 4);
+                b[4 * q + 0] = b4[0];
+                b[4 * q + 1] = b4[1];
+                b[4 * q + 2] = b4[2];
+                b[4 * q + 3] = b4[3];
+            }
+            return b;
+        };
         for (int t = 0; t < tiles; ++t) {
-            uint4 staged[STAGE];
             const bool more = t + 2 < tiles;
-            if (more) stage_load(t + 2, staged);
+            const Staged staged = stage_load(more ? t + 2 : t);   // unconditional: the same loads in flight on every path
 
             const unsigned char *rec = ring[t % 3];
-            // bias of the 16 centroid rows this lane's accumulators stand for (rows 8 (v/4) + 4 half + v%4):
-            // read straight into the accumulators of every pair, so it occupies no registers of its own
-            auto load_bias = [&]() {
-                f32x16 b;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 b4 = *reinterpret_cast<const f32x4 *>(rec + NS * 1024 + (8 * q + 4 * half) * 4);
-                    b[4 * q + 0] = b4[0];
-                    b[4 * q + 1] = b4[1];
-                    b[4 * q + 2] = b4[2];
-                    b[4 * q + 3] = b4[3];
-                }
-                return b;
-            };
-            // The centroid operand of the whole tile stays in registers while the point tiles are
-            // taken two at a time, so only two accumulators are live at once.
             bf16x8 a[NS];
 #pragma unroll
             for (int s = 0; s < NS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(rec + (64 * s + lane) * 16);
+            if (t == 0) acc[0] = load_bias(rec);
 #pragma unroll
-            for (int p0 = 0; p0 < kPointTiles; p0 += kPair) {
-                f32x16 acc[kPair];
+            for (int p = 0; p < kPointTiles; ++p) {
+                // acc[p & 1] holds the bias; the other accumulator holds the previous chain's scores,
+                // which are folded piece by piece behind the matrix instructions of this chain (the
+                // scheduling barriers keep the pieces there: left alone, the compiler issues the chain
+                // first, and a wave cannot issue past a matrix instruction that waits for the pipe)
+                const bool have_prev = p > 0 || t > 0;
+                const int pp = p > 0 ? p - 1 : kPointTiles - 1, pt = p > 0 ? t : t - 1;
 #pragma unroll
-                for (int q = 0; q < kPair; ++q) acc[q] = load_bias();
+                for (int s = 0; s < NS; ++s) {
+                    acc[p & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], xb[p][s], acc[p & 1], 0, 0, 0);
+                    constexpr int NF = NS - 1 < 5 ? NS - 1 : 5;   // chain slots that carry fold pieces
+                    if (have_prev && s < NF) {
 #pragma unroll
-                for (int s = 0; s < NS; ++s)
-#pragma unroll
-                    for (int q = 0; q < kPair; ++q)
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], xb[p0 + q][s], acc[q], 0, 0, 0);
-#pragma unroll
-                for (int q = 0; q < kPair; ++q) {
-                    // maxima of the four groups of 4 accumulators (4 consecutive centroid rows each)
-                    float qm[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        qm[j] = fmaxf(fmaxf(acc[q][4 * j], acc[q][4 * j + 1]), fmaxf(acc[q][4 * j + 2], acc[q][4 * j + 3]));
-                    const float m = fmaxf(fmaxf(qm[0], qm[1]), fmaxf(qm[2], qm[3]));
-                    const bool better = m > best[p0 + q];   // strict: the earliest tile keeps a tie
-                    best[p0 + q] = better ? m : best[p0 + q];
-                    btile[p0 + q] = better ? t : btile[p0 + q];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) bquad[p0 + q][j] = better ? qm[j] : bquad[p0 + q][j];
+                        for (int piece = s * 5 / NF; piece < (s + 1) * 5 / NF; ++piece)
+                            fold(piece, acc[(p + 1) & 1], pp, pt);
+                    }
+                    // the folded accumulator is free: preset it for the next chain while this one runs
+                    if (s == NF && p + 1 < kPointTiles) acc[(p + 1) & 1] = load_bias(rec);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (more) stage_store((t + 2) % 3, staged);
             __syncthreads();
+            // first chain of the next tile starts from that tile's bias (its record is published by the barrier)
+            if (t + 1 < tiles) acc[0] = load_bias(ring[(t + 1) % 3]);
         }
+#pragma unroll
+        for (int piece = 0; piece < 5; ++piece) fold(piece, acc[(kPointTiles - 1) & 1], kPointTiles - 1, tiles - 1);
 
-        // Name the group of 4 consecutive centroid rows that holds the winner: code = 8 tile + 2 group + half
-        // (rows 8 group + 4 half .. + 3 of the tile).  Codes ascend with the centroid index, so the
-        // smaller code wins a tie, here and between the two halves of a column.
+        // The code names the group of 4 consecutive centroid rows that holds the winner (rows
+        // 8 group + 4 half .. + 3 of the tile).  Codes ascend with the centroid index, so the smaller
+        // code wins a tie between the two halves of a column.
 #pragma unroll
         for (int p = 0; p < kPointTiles; ++p) {
-            const int grp = bquad[p][0] == best[p] ? 0 : bquad[p][1] == best[p] ? 1 : bquad[p][2] == best[p] ? 2 : 3;
-            int32_t code = 8 * btile[p] + 2 * grp + half;
+            int32_t code = bcode[p] + half;
             const float ob = __shfl_xor(best[p], 32, 64);
             const int32_t oc = __shfl_xor(code, 32, 64);
             if (ob > best[p] || (ob == best[p] && oc < code)) { best[p] = ob; code = oc; }
@@ -356,10 +382,14 @@ int launch_large(const ep_problem &p, const bf16_t *X, const float *C, const Kme
     large_prep_kernel<D><<<tiles, kBlock, 0, s>>>(p.k, C, w.cq16, w.cnorm, w.records);
     EP_LAUNCH_CHECK();
     {
-        const int64_t wg_blocks = ceil_div(ceil_div(p.n, kPointsPerWave), kWaves);
+        // A grid of resident workgroups loops over the workgroup-blocks of 512 rows.  (Splitting off
+        // the last, partly filled round into a launch of its own with half-size blocks was measured
+        // and is slower: the chip is power-limited in this kernel, and the clock rises while the
+        // last round drains.)
+        const int64_t wg_blocks = ceil_div(ceil_div(p.n, (int64_t)kTile * kMainPointTiles), kWaves);
         const int grid = (int)std::min<int64_t>(wg_blocks, 256 * EP_LARGE_OCC);
         ProfScope prof(EP_PROF_LLOYD_MAIN, s);
-        large_assign_kernel<D><<<grid, kBlock, 0, s>>>(p.n, p.ld, tiles, X, w.records, w.best_tile);
+        large_assign_kernel<D, kMainPointTiles><<<grid, kBlock, 0, s>>>(0, p.n, p.ld, tiles, X, w.records, w.best_tile);
         EP_LAUNCH_CHECK();
     }
     const int blocks = (int)std::min<int64_t>(kObjBlocksMax, ceil_div(p.n, kBlock / 32));
