@@ -118,6 +118,8 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 31, half = lane >> 5;
+    float pos_inf = __builtin_inff();
+    asm volatile("" : "+s"(pos_inf));
 
     const int64_t wave_blocks = (n - row_begin + kPointsPerWave - 1) / kPointsPerWave;
     const int64_t wg_blocks = (wave_blocks + kWaves - 1) / kWaves;
@@ -186,13 +188,21 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
         // Epilogue of one 32 x 32 product: this lane holds 16 centroid rows of one point as 4 groups of
         // 4 consecutive rows.  Group maxima, their maximum, one compare, two selects.  Ties keep
         // the earlier tile (strict >) and, inside a tile, the lower group.
+        // Maxima of 4 values in two instructions: a 3-input maximum, then the median of (that, the
+        // fourth, +infinity), which is their maximum for ordered inputs.  A plain 2-input maximum of
+        // matrix-instruction results costs three instructions (the compiler first quiets both
+        // inputs); the median is a target operation it leaves alone.  +infinity is kept opaque in a
+        // scalar register so that the median is not folded back into a maximum.
         float qm[4];
+        auto max4 = [&](float v0, float v1, float v2, float v3) {
+            return __builtin_amdgcn_fmed3f(fmaxf(fmaxf(v0, v1), v2), v3, pos_inf);
+        };
         auto fold = [&](int piece, const f32x16 &acc, int p, int t) {   // pieces 0 .. 4, in order
             if (piece < 4) {
                 const int j = piece;
-                qm[j] = fmaxf(fmaxf(fmaxf(acc[4 * j], acc[4 * j + 1]), acc[4 * j + 2]), acc[4 * j + 3]);
+                qm[j] = max4(acc[4 * j], acc[4 * j + 1], acc[4 * j + 2], acc[4 * j + 3]);
             } else {
-                const float m = fmaxf(fmaxf(fmaxf(qm[0], qm[1]), qm[2]), qm[3]);
+                const float m = max4(qm[0], qm[1], qm[2], qm[3]);
                 // lowest group that holds the maximum, as 0/1 arithmetic (a chain of selects here is
                 // turned into branches by the compiler, which would split the instruction stream)
                 const int e0 = qm[0] == m, e1 = qm[1] == m, e2 = qm[2] == m;
