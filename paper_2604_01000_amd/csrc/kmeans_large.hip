@@ -124,26 +124,18 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
     const int64_t wave_blocks = (n - row_begin + kPointsPerWave - 1) / kPointsPerWave;
     const int64_t wg_blocks = (wave_blocks + kWaves - 1) / kWaves;
 
-    // A record travels global -> registers -> LDS, STAGE (<= 3) 16-byte pieces per thread.
-    static_assert(STAGE <= 3, "three staging registers per thread");
-    struct Staged {
-        uint4 v0, v1, v2;
-    };
-    auto stage_load = [&](int tile) {
+    // A record travels from global memory straight into its ring slot (LDS-direct loads: lane l of a
+    // wave delivers its 16 bytes to the wave's LDS base + 16 l), STAGE pieces per thread; no
+    // staging registers.  The loads count in vmcnt; the compiler waits for them before a barrier.
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+    auto stage = [&](int tile, int slot) {
         const uint4 *src = reinterpret_cast<const uint4 *>(records + (int64_t)tile * REC);
-        const int t0 = threadIdx.x;   // always a valid address; the store drops the excess
-        Staged r;
-        r.v0 = src[t0 < REC16 ? t0 : REC16 - 1];
-        r.v1 = STAGE > 1 ? src[t0 + kBlock < REC16 ? t0 + kBlock : REC16 - 1] : uint4{0, 0, 0, 0};
-        r.v2 = STAGE > 2 ? src[t0 + 2 * kBlock < REC16 ? t0 + 2 * kBlock : REC16 - 1] : uint4{0, 0, 0, 0};
-        return r;
-    };
-    auto stage_store = [&](int slot, const Staged &r) {
-        uint4 *dst = reinterpret_cast<uint4 *>(ring[slot]);
-        const int t0 = threadIdx.x;
-        if (t0 < REC16) dst[t0] = r.v0;
-        if (STAGE > 1 && t0 + kBlock < REC16) dst[t0 + kBlock] = r.v1;
-        if (STAGE > 2 && t0 + 2 * kBlock < REC16) dst[t0 + 2 * kBlock] = r.v2;
+#pragma unroll
+        for (int q = 0; q < STAGE; ++q) {
+            const int wave_piece = q * kBlock + wave * 64;   // uniform
+            if (wave_piece + lane < REC16)
+                __builtin_amdgcn_global_load_lds(src + wave_piece + lane, (lds_ptr)(ring[slot] + wave_piece * 16), 16, 0, 0);
+        }
     };
 
     for (int64_t wb = blockIdx.x; wb < wg_blocks; wb += gridDim.x) {
@@ -180,8 +172,8 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
         // ring prologue: records 0 and 1
         __syncthreads();  // the previous block's readers are done with the ring
         {
-            stage_store(0, stage_load(0));
-            if (tiles > 1) stage_store(1, stage_load(1));
+            stage(0, 0);
+            if (tiles > 1) stage(1, 1);
         }
         __syncthreads();
 
@@ -234,8 +226,7 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
             return b;
         };
         for (int t = 0; t < tiles; ++t) {
-            const bool more = t + 2 < tiles;
-            const Staged staged = stage_load(more ? t + 2 : t);   // unconditional: the same loads in flight on every path
+            if (t + 2 < tiles) stage(t + 2, (t + 2) % 3);   // that slot's readers passed the last barrier
 
             const unsigned char *rec = ring[t % 3];
             bf16x8 a[NS];
@@ -264,7 +255,6 @@ __global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int6
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (more) stage_store((t + 2) % 3, staged);
             __syncthreads();
             // first chain of the next tile starts from that tile's bias (its record is published by the barrier)
             if (t + 1 < tiles) acc[0] = load_bias(ring[(t + 1) % 3]);
