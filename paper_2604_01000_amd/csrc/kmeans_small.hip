@@ -36,6 +36,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
 constexpr int kSub = 16;  // points per sub-tile
+constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;   // MI355X: 256 MB memory-side cache
 constexpr int kLabelFlush = 64;                  // sub-tiles whose labels are written out together (4 KB)
 
 enum Mode { kAssignOnly = 0, kUpdateOnly = 1, kFused = 2 };
@@ -145,7 +146,7 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 }
 
 // XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
-template <int D, int KT, int MODE, bool XSQ>
+template <int D, int KT, int MODE, bool XSQ, bool STREAM>
 __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) void lloyd_small_kernel(
     int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const float *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
@@ -276,11 +277,15 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         const int bytes = live ? (int)(((rows_here - 1) * ld + D) * 4) : 0;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float *>(X + row0 * ld), 0, bytes, 0x00020000);
+        // STREAM: a matrix larger than the last-level cache is read with the non-temporal hint (it
+        // cannot be there again next round, and the hint buys ~2% of stream rate); a smaller one is
+        // left to the caches, which serve it in the later rounds.
+        constexpr int kAux = STREAM ? 2 : 0;
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
             const u32x4 raw = kPointPerLane
-                                  ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, 0)
-                                  : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), 0);
+                                  ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, kAux)
+                                  : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), kAux);
             dst[q] = __builtin_bit_cast(f32x4, raw);
         }
     };
@@ -834,12 +839,14 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
                 const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
+    const bool stream_x = (double)p.n * (double)p.ld * 4.0 > kLastLevelCacheBytes;
     double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s);
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
         constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
-        auto kern = lloyd_small_kernel<D_, KT_, MODE, XSQ>;                                                   \
+        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true>                                   \
+                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false>;                                 \
         if (lds_bytes > 64 * 1024)                                                                            \
             EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
