@@ -28,10 +28,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/), scaled by the copy-kernel calibration; None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "arxiv_like": 89_725_007,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
-    "products_like": 1_268_651_233,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
-    "products_reorder": 1_044_234_903,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
-    "papers_like": 57_292_842_539,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
+    "arxiv_like": 89_705_751,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
+    "products_like": 1_281_901_216,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
+    "products_reorder": 1_159_370_670,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
+    "papers_like": 57_369_040_283,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
 }
 
 
