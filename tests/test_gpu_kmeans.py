@@ -55,12 +55,16 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (5003, 128, 8, True, torch.float32, None),
     (7777, 128, 16, True, torch.float32, 132),
     (4099, 128, 64, True, torch.float32, None),
+    (3001, 128, 30, True, torch.float32, None),      # two centroid tiles
+    (2999, 64, 24, True, torch.float32, None),       # d = 64, two centroid tiles
+    (3003, 64, 50, False, torch.float32, 68),        # d = 64, four centroid tiles, padded rows
     (3001, 20, 5, False, torch.float32, None),
     (2500, 7, 3, False, torch.float32, 8),
     (1500, 516, 9, True, torch.float32, None),
     (4097, 128, 300, True, torch.bfloat16, None),
     (2049, 64, 33, True, torch.bfloat16, 72),
     (6000, 128, 1024, True, torch.bfloat16, None),
+    (5000, 64, 200, True, torch.bfloat16, None),     # matrix-core path at d = 64
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -134,6 +138,8 @@ def test_run_matches_oracle_full_size(name):
 
 @pytest.mark.parametrize("n,d,k,dtype,iters", [(20_011, 128, 16, torch.float32, 8), (9_000, 128, 64, torch.float32, 6),
                                                (12_345, 128, 700, torch.bfloat16, 4),
+                                               (6_007, 128, 24, torch.float32, 6), (6_011, 64, 40, torch.float32, 6),
+                                               (8_009, 64, 300, torch.bfloat16, 4),
                                                (5_000, 48, 6, torch.float32, 10)])
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
