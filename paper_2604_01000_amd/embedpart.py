@@ -19,6 +19,7 @@ _LIB_PATH = Path(__file__).resolve().parent / _os.environ.get("EP_LIB_VARIANT", 
 EP_F32, EP_BF16 = 0, 1
 EP_RUN_FINAL_REASSIGN = 1
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
+EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the header
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",

@@ -31,6 +31,16 @@ def test_library_exports_every_declared_symbol():
     assert ep.strerror(-99) == "unknown error code"
 
 
+def test_binding_constants_equal_the_header():
+    text = HEADER.read_text()
+    defines = dict(re.findall(r"#define\s+(EP_\w+)\s+\(?(-?\d+)\)?\s", text))
+    for name in ("EP_OK", "EP_EINVAL", "EP_EUNSUPPORTED", "EP_EWORKSPACE", "EP_EHIP", "EP_F32", "EP_BF16",
+                 "EP_RUN_FINAL_REASSIGN", "EP_MAX_D", "EP_MAX_K", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
+                 "EP_PROF_EDGE_SWEEP"):
+        assert int(defines[name]) == getattr(ep, name), name
+    assert "((int64_t)1 << 31)" in text and ep.EP_MAX_N == 1 << 31
+
+
 def _prob(**kw):
     base = dict(n=1000, ld=128, d=128, k=8, dtype=ep.EP_F32, reserved=0)
     base.update(kw)

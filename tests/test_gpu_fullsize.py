@@ -128,3 +128,23 @@ def test_papers_like_full():
     torch.cuda.empty_cache()
     ecr = _graph_check(w, labels_np, w.k)
     print(f"papers_like: edge-cut ratio {ecr:.4f}")
+
+
+def test_maximum_k_and_maximum_d():
+    """The limits of the header: k = 65,536 clusters (bf16 matrix-core path: 2,048 centroid tiles, codes up to
+    8 * 2047 + 7) checked on sampled points and clusters, and d = 1,024 columns (generic path) in full."""
+    rng = np.random.default_rng(65536)
+    k, d, n = ep.EP_MAX_K, 64, ep.EP_MAX_K + 4_123
+    gen = torch.Generator().manual_seed(99)
+    X = (2.0 * torch.randn((64, d), generator=gen)[torch.randint(0, 64, (n,), generator=gen)]
+         + torch.randn((n, d), generator=gen)).clamp_min(0).to(torch.bfloat16).to(DEV)
+    idx = oracle.init_indices(5, n, k)
+    km = Kmeans(X, k).init(idx)
+    C0 = km.C.cpu().numpy().astype(np.float64)
+    got = km.run(1)
+    _sampled_round_check(X, km, C0, got, k, True, rng, n_points=1024, n_clusters=64)
+    assert np.isfinite(got["obj_hist"][0])
+
+    n2, d2, k2 = 700, ep.EP_MAX_D, 7
+    X2 = torch.randn((n2, d2), generator=gen).to(DEV)
+    check_free_running(X2, k2, 3, oracle.init_indices(6, n2, k2))
