@@ -55,6 +55,9 @@ def lib():
         L.or_lloyd.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, C.c_int32, p, C.c_int,
                                p, p, p, p, p]
         L.or_lloyd.restype = C.c_int
+        L.or_sampled_kmeans.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, C.c_int64, p, C.c_int32,
+                                        C.c_int, p, p, p, p, p]
+        L.or_sampled_kmeans.restype = C.c_int
         L.or_partition_quality.argtypes = [C.c_int64, C.c_int32, p, p, p, p, p]
         L.or_partition_quality.restype = C.c_int
         L.or_edge_cut_ratio.argtypes = [C.c_int64, C.c_int64]
@@ -143,6 +146,25 @@ def lloyd(X, k: int, iters: int, idx, flags: int = 0):
     if rc != 0:
         raise ValueError("lloyd: bad arguments")
     return dict(C=Cc, labels=labels, counts=counts, obj_hist=hist[:iters], obj_final=fin.value)
+
+
+def sampled_kmeans(X, k: int, iters: int, rows, flags: int = 0):
+    """Centroids trained on the rows `rows` of X (first k of them as initial centroids), then every row
+    assigned.  Returns dict(C, labels, counts, obj_hist, obj_full)."""
+    X, ld = _x32(X)
+    n, d = X.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    m = rows.shape[0]
+    Cc = np.empty((k, d), dtype=np.float64)
+    labels = np.empty(n, dtype=np.int32)
+    counts = np.zeros(k, dtype=np.int64)
+    hist = np.empty(max(iters, 1), dtype=np.float64)
+    full = C.c_double(float("nan"))
+    rc = lib().or_sampled_kmeans(n, d, k, _ptr(X), ld, m, _ptr(rows), iters, flags, _ptr(Cc), _ptr(labels),
+                                 _ptr(counts), _ptr(hist), C.addressof(full))
+    if rc != 0:
+        raise ValueError("sampled_kmeans: bad arguments")
+    return dict(C=Cc, labels=labels, counts=counts, obj_hist=hist[:iters], obj_full=full.value)
 
 
 def _csr(rowptr, colidx):

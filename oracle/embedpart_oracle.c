@@ -10,6 +10,8 @@
  *   - Alg. 3, first step  P <- KMeans(E, k): cluster one dense embedding per
  *     vertex into exactly k groups; the clusters are the partitions
  *     (Sec. "Phase 2: Clustering and Balancing").
+ *   - Sec. "Implementation": the centroids are computed on a sample of the
+ *     embeddings (2^9 per cluster), then every vertex is assigned.
  *   - Sec. "Partitioning quality metrics": an edge (u,v) is cut iff
  *     pid(u) != pid(v); ECR = |C|/|E|; vertex balance = max|P_i| / mean|P_i|.
  *   - Sec. "Extension to Graph Reordering": gap xi_pi(u,v) = |pi(u)-pi(v)|,
@@ -27,7 +29,9 @@
  * hand-worked 1-D Lloyd run, k = 1 and k = N special cases, separated blobs,
  * translation / permutation equivariance, monotone objective, mean property,
  * closed-form cuts on paths / cycles / complete graphs / matchings,
- * adjacency-matrix brute force, balance extremes, permutation bijectivity.
+ * adjacency-matrix brute force, balance extremes, permutation bijectivity;
+ * sample-trained run: identity sample = Lloyd + one re-assignment, labels are
+ * the brute-force nearest centroid, rows outside the sample do not move C.
  * Numerical parity with figures printed in the paper is unpinned: every such
  * figure depends on datasets and trained weights that are not available.
  *
@@ -209,6 +213,48 @@ int or_lloyd(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
         if (obj_final) *obj_final = obj;
     }
     return 0;
+}
+
+/* ---- sample-trained K-Means ------------------------------------------------ */
+
+/*
+ * The clustering as the paper's Sec. "Implementation" runs it: the centroids
+ * are computed on a sample of the embeddings (2^9 per cluster there), and every
+ * vertex then gets the partition of its nearest centroid.
+ * Reading taken (the paper gives no further detail): the sample is the m rows
+ * rows[0..m) of X in that order; Lloyd runs `iters` rounds on it from its
+ * first k rows as initial centroids; then one assignment of all n rows
+ * against the trained centroids.
+ *   C        : k x d trained centroids (means over the SAMPLE)
+ *   counts   : sizes of the sample's clusters in the last round
+ *   obj_hist : the sample's objective per round (may be NULL)
+ *   labels   : n labels of the full assignment;  *obj_full its objective
+ * Returns 0, or -1 on bad arguments (m < k, m > n, a row out of range).
+ */
+int or_sampled_kmeans(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
+                      int64_t m, const int64_t *rows, int32_t iters, int flags,
+                      double *C, int32_t *labels, int64_t *counts,
+                      double *obj_hist, double *obj_full)
+{
+    if (n < 1 || d < 1 || k < 1 || m < (int64_t)k || m > n || ld < d || iters < 0) return -1;
+    for (int64_t i = 0; i < m; ++i)
+        if (rows[i] < 0 || rows[i] >= n) return -1;
+    float *S = (float *)malloc((size_t)m * (size_t)d * sizeof(float));
+    int32_t *sample_labels = (int32_t *)malloc((size_t)m * sizeof(int32_t));
+    int64_t *first = (int64_t *)malloc((size_t)k * sizeof(int64_t));
+    if (!S || !sample_labels || !first) { free(S); free(sample_labels); free(first); return -1; }
+    for (int64_t i = 0; i < m; ++i)
+        for (int32_t c = 0; c < d; ++c) S[i * d + c] = X[rows[i] * ld + c];
+    for (int32_t j = 0; j < k; ++j) first[j] = j;
+    int rc = or_lloyd(m, d, k, S, d, iters, first, flags & OR_FLAG_BF16_CENTROIDS,
+                      C, sample_labels, counts, obj_hist, NULL);
+    if (rc == 0) {
+        double obj = or_assign(n, d, k, X, ld, C, (flags & OR_FLAG_BF16_CENTROIDS) ? 1 : 0,
+                               labels, NULL, NULL);
+        if (obj_full) *obj_full = obj;
+    }
+    free(S); free(sample_labels); free(first);
+    return rc;
 }
 
 /* ---- partition quality over a CSR graph ---------------------------------- */

@@ -269,3 +269,56 @@ def test_exhaustive_optimum_is_never_beaten():
         best = min(best, s)
     r = oracle.lloyd(X, 2, 10, np.array([0, 1]), flags=oracle.FLAG_FINAL_REASSIGN)
     assert r["obj_final"] >= best - 1e-9
+
+
+# ---- sample-trained K-Means (paper, Sec. "Implementation") ---------------------------------------
+
+def _blobs(n, d, g, seed):
+    rng = np.random.default_rng(seed)
+    means = 3.0 * rng.standard_normal((g, d))
+    return (means[rng.integers(0, g, n)] + rng.standard_normal((n, d))).astype(np.float32)
+
+
+def test_sampled_identity_sample_is_lloyd_plus_one_assignment():
+    X = _blobs(400, 5, 4, 1)
+    rows = np.arange(400)
+    got = oracle.sampled_kmeans(X, 4, 6, rows)
+    ref = oracle.lloyd(X, 4, 6, np.arange(4), flags=oracle.FLAG_FINAL_REASSIGN)
+    np.testing.assert_array_equal(got["C"], ref["C"])
+    np.testing.assert_array_equal(got["labels"], ref["labels"])
+    np.testing.assert_array_equal(got["counts"], ref["counts"])
+    np.testing.assert_array_equal(got["obj_hist"], ref["obj_hist"])
+    assert got["obj_full"] == ref["obj_final"]
+
+
+def test_sampled_labels_are_brute_force_nearest_and_training_sees_only_the_sample():
+    X = _blobs(900, 3, 5, 2)
+    rows = oracle.init_indices(7, 900, 120)
+    got = oracle.sampled_kmeans(X, 5, 8, rows)
+    # training = Lloyd on the gathered rows, first k rows as the start
+    ref = oracle.lloyd(X[rows], 5, 8, np.arange(5))
+    np.testing.assert_array_equal(got["C"], ref["C"])
+    np.testing.assert_array_equal(got["counts"], ref["counts"])
+    assert got["counts"].sum() == 120
+    # labels of ALL rows: exhaustive nearest centroid in numpy fp64, lowest index on ties
+    d2 = ((X[:, None, :].astype(np.float64) - got["C"][None, :, :]) ** 2).sum(axis=2)
+    np.testing.assert_array_equal(got["labels"], d2.argmin(axis=1))
+    assert abs(got["obj_full"] - d2.min(axis=1).sum()) <= 1e-9 * got["obj_full"]
+    # rows outside the sample do not move the centroids
+    X2 = X.copy()
+    outside = np.setdiff1d(np.arange(900), rows)
+    X2[outside] += 100.0
+    again = oracle.sampled_kmeans(X2, 5, 8, rows)
+    np.testing.assert_array_equal(again["C"], got["C"])
+    np.testing.assert_array_equal(again["labels"][rows], got["labels"][rows])
+
+
+def test_sampled_order_of_the_sample_names_the_start_and_bad_arguments():
+    X = _blobs(300, 2, 3, 3)
+    rows = oracle.init_indices(11, 300, 60)
+    a = oracle.sampled_kmeans(X, 3, 0, rows)                       # no rounds: C = first k sample rows
+    np.testing.assert_array_equal(a["C"], X[rows[:3]].astype(np.float64))
+    with pytest.raises(ValueError):
+        oracle.sampled_kmeans(X, 3, 2, rows[:2])                   # fewer sample rows than clusters
+    with pytest.raises(ValueError):
+        oracle.sampled_kmeans(X, 3, 2, np.array([0, 1, 2, 300]))   # row out of range
