@@ -142,6 +142,26 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
                int32_t *labels, int64_t *counts, double *objective_hist, int flags,
                void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Sample-trained K-Means: the clustering as the paper's Sec. "Implementation" runs it. The
+ * centroids are computed on a sample of the embeddings (2^9 per cluster there) and every vertex
+ * then takes the partition of its nearest centroid.
+ *   m, sample_rows_host  the sample: m row indices of X (k <= m <= n, each in [0, n); they
+ *                        should be distinct, e.g. from kmeans_init_indices(seed, n, m)), HOST memory
+ *   iters                Lloyd rounds on the sample, starting from its first k rows
+ *   C                    k x d fp32, written: the trained centroids (means over the sample)
+ *   labels               n int32, 16-byte aligned, written: nearest trained centroid of every row of X
+ *   counts               k int64, written: the sample's cluster sizes in the last round
+ *   objective_hist       iters + 1 doubles or NULL: [t] = the sample's objective in round t,
+ *                        [iters] = the objective of the full assignment
+ *   ws                   kmeans_sampled_workspace_bytes(p, m) bytes; holds the dense copy of the sample
+ * Errors as kmeans_run; EP_EINVAL also for m outside [k, n] or a row index outside [0, n).
+ */
+int kmeans_sampled_workspace_bytes(const ep_problem *p, int64_t m, size_t *bytes_host);
+int kmeans_run_sampled(const ep_problem *p, const void *X, int64_t m, const int64_t *sample_rows_host,
+                       int32_t iters, float *C, int32_t *labels, int64_t *counts, double *objective_hist,
+                       void *ws, size_t ws_bytes, void *stream);
+
 /* Bytes of workspace that the graph calls below need. */
 int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host);
 

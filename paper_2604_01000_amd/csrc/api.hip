@@ -79,6 +79,52 @@ int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colid
     return EP_OK;
 }
 
+// `iters` Lloyd rounds from the centroids in C (see kmeans_run in the header).
+int run_rounds(const ep_problem &p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
+               double *objective_hist, int flags, const KmeansWs &w, hipStream_t s) {
+    int rc = EP_OK;
+    if (small_path_supported(p)) {  // fused rounds: X is read once per round
+        for (int32_t t = 0; t < iters; ++t)
+            if ((rc = launch_small_round(p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
+                                         t == 0, s)) != EP_OK)
+                return rc;
+        if (flags & EP_RUN_FINAL_REASSIGN)
+            rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+        return rc;
+    }
+    for (int32_t t = 0; t < iters; ++t) {
+        if ((rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + t : nullptr, s)) != EP_OK)
+            return rc;
+        if ((rc = do_update(p, X, labels, C, C, counts, w, s)) != EP_OK) return rc;
+    }
+    if (flags & EP_RUN_FINAL_REASSIGN)
+        rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+    return rc;
+}
+
+// Workspace of kmeans_run_sampled: the dense sample, its row indices, its labels, and one K-Means
+// workspace sized for the full problem (used for the sample's rounds, then for the full assignment).
+struct SampledWs {
+    void *S;
+    int64_t *rows;
+    int32_t *labels;
+    void *km;
+    int64_t ld_s;
+    size_t bytes;
+};
+SampledWs carve_sampled_ws(const ep_problem &p, int64_t m, void *ws) {
+    Carver c(ws);
+    SampledWs w{};
+    const int64_t unit = p.dtype == EP_BF16 ? 8 : 4;   // rows stay 16-byte aligned
+    w.ld_s = (p.d + unit - 1) / unit * unit;
+    w.S = c.take<unsigned char>((size_t)m * (size_t)w.ld_s * (p.dtype == EP_BF16 ? 2 : 4));
+    w.rows = c.take<int64_t>((size_t)m);
+    w.labels = c.take<int32_t>((size_t)m);
+    w.km = c.take<unsigned char>(carve_kmeans_ws(p, nullptr).bytes);
+    w.bytes = align_up(c.used, 256);
+    return w;
+}
+
 }  // namespace
 }  // namespace ep
 
@@ -184,23 +230,42 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
     if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (small_path_supported(*p)) {  // fused rounds: X is read once per round
-        for (int32_t t = 0; t < iters; ++t)
-            if ((rc = launch_small_round(*p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
-                                         t == 0, s)) != EP_OK)
-                return rc;
-        if (flags & EP_RUN_FINAL_REASSIGN)
-            rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+    return run_rounds(*p, X, iters, C, labels, counts, objective_hist, flags, w, s);
+}
+
+int kmeans_sampled_workspace_bytes(const ep_problem *p, int64_t m, size_t *bytes_host) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!bytes_host || m < p->k || m > p->n) return EP_EINVAL;
+    *bytes_host = carve_sampled_ws(*p, m, nullptr).bytes;
+    return EP_OK;
+}
+
+int kmeans_run_sampled(const ep_problem *p, const void *X, int64_t m, const int64_t *sample_rows_host, int32_t iters,
+                       float *C, int32_t *labels, int64_t *counts, double *objective_hist, void *ws,
+                       size_t ws_bytes, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!sample_rows_host || m < p->k || m > p->n || !C || !labels || !aligned(labels, 16) || !counts || iters < 0)
+        return EP_EINVAL;
+    for (int64_t i = 0; i < m; ++i)
+        if (sample_rows_host[i] < 0 || sample_rows_host[i] >= p->n) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_sampled_ws(*p, m, nullptr).bytes)) != EP_OK) return rc;
+    const SampledWs sw = carve_sampled_ws(*p, m, ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ep_problem ps = *p;   // the sample as a problem of its own: m dense rows
+    ps.n = m;
+    ps.ld = sw.ld_s;
+    EP_HIP_TRY(hipMemcpyAsync(sw.rows, sample_rows_host, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice, s));
+    if ((rc = launch_sample_rows(*p, X, m, sw.ld_s, sw.rows, sw.S, s)) != EP_OK) return rc;
+    // initial centroids: the first k rows of the sample (= rows sample_rows[0..k) of X)
+    if ((rc = launch_gather_rows(*p, X, sw.rows, C, s)) != EP_OK) return rc;
+    if ((rc = run_rounds(ps, sw.S, iters, C, sw.labels, counts, objective_hist, 0, carve_kmeans_ws(ps, sw.km), s)) !=
+        EP_OK)
         return rc;
-    }
-    for (int32_t t = 0; t < iters; ++t) {
-        if ((rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + t : nullptr, s)) != EP_OK)
-            return rc;
-        if ((rc = do_update(*p, X, labels, C, C, counts, w, s)) != EP_OK) return rc;
-    }
-    if (flags & EP_RUN_FINAL_REASSIGN)
-        rc = do_assign(*p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
-    return rc;
+    return do_assign(*p, X, C, carve_kmeans_ws(*p, sw.km), labels, nullptr,
+                     objective_hist ? objective_hist + iters : nullptr, s);
 }
 
 int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host) {

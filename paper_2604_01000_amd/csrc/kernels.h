@@ -29,6 +29,9 @@ struct KmeansWs {
 KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws);
 
 int launch_gather_rows(const ep_problem &p, const void *X, const int64_t *idx_dev, float *C, hipStream_t s);
+// S[i,:] = X[rows_dev[i],:] for i < m, element type of X, row stride ld_s.
+int launch_sample_rows(const ep_problem &p, const void *X, int64_t m, int64_t ld_s, const int64_t *rows_dev, void *S,
+                       hipStream_t s);
 int launch_prep_centroids(const ep_problem &p, const float *C, const KmeansWs &w, hipStream_t s);
 int launch_assign_generic(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                           float *min_d2, double *objective, hipStream_t s);

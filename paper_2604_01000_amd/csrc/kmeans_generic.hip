@@ -27,6 +27,17 @@ __global__ void gather_rows_kernel(int32_t d, int32_t k, int64_t ld, const XT *_
     C[t] = load_elem(X + idx[j] * ld + m);
 }
 
+// ---- sample: S[i,:] = X[rows[i],:] in the element type of X, row stride ld_s >= d -----------------
+// (the columns d .. ld_s - 1 of S are zeroed; no kernel reads them)
+template <typename XT>
+__global__ void sample_rows_kernel(int32_t d, int64_t m, int64_t ld, int64_t ld_s, const XT *__restrict__ X,
+                                   const int64_t *__restrict__ rows, XT *__restrict__ S) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= m * ld_s) return;
+    const int64_t i = t / ld_s, c = t % ld_s;
+    S[t] = c < d ? X[rows[i] * ld + c] : XT(0);
+}
+
 // ---- centroid preparation: squared norms (and bf16-rounded copies) -------------------------
 // One wave per centroid; the norm is accumulated in fp64 and rounded once.
 __global__ __launch_bounds__(kBlock) void prep_centroids_kernel(int32_t d, int32_t k, int round_bf16,
@@ -354,6 +365,18 @@ int launch_gather_rows(const ep_problem &p, const void *X, const int64_t *idx_de
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
         gather_rows_kernel<XT><<<(unsigned)ceil_div(total, kBlock), kBlock, 0, s>>>(
             p.d, p.k, p.ld, static_cast<const XT *>(X), idx_dev, C);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    });
+}
+
+int launch_sample_rows(const ep_problem &p, const void *X, int64_t m, int64_t ld_s, const int64_t *rows_dev, void *S,
+                       hipStream_t s) {
+    const int64_t total = m * ld_s;
+    return by_dtype(p, [&](auto *tag) {
+        using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;
+        sample_rows_kernel<XT><<<(unsigned)ceil_div(total, kBlock), kBlock, 0, s>>>(
+            p.d, m, p.ld, ld_s, static_cast<const XT *>(X), rows_dev, static_cast<XT *>(S));
         EP_LAUNCH_CHECK();
         return EP_OK;
     });

@@ -23,7 +23,8 @@ EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the hea
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
-    "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "graph_workspace_bytes",
+    "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_sampled_workspace_bytes",
+    "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
     "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
 )
@@ -62,6 +63,8 @@ def lib() -> C.CDLL:
         L.kmeans_assign.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.kmeans_update.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.kmeans_run.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+        L.kmeans_sampled_workspace_bytes.argtypes = [pp, i64, C.POINTER(sz)]
+        L.kmeans_run_sampled.argtypes = [pp, vp, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.graph_workspace_bytes.argtypes = [i64, i64, i32, C.POINTER(sz)]
         L.partition_quality.argtypes = [i64, i64, i32, vp, C.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.partition_permutation.argtypes = [i64, i32, vp, vp, vp, vp, sz, vp]
@@ -153,6 +156,20 @@ def kmeans_update(p, X, labels, C_prev, C_out, counts, ws):
 def kmeans_run(p, X, iters, Cc, labels, counts, objective_hist, flags, ws):
     _check(lib().kmeans_run(C.byref(p), _ptr(X), iters, _ptr(Cc), _ptr(labels), _ptr(counts), _ptr(objective_hist),
                             flags, _ptr(ws), ws.numel(), _stream()), "kmeans_run")
+
+
+def kmeans_sampled_workspace_bytes(p: ep_problem, m: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().kmeans_sampled_workspace_bytes(C.byref(p), m, C.byref(out)), "kmeans_sampled_workspace_bytes")
+    return out.value
+
+
+def kmeans_run_sampled(p, X, sample_rows_host, iters, Cc, labels, counts, objective_hist, ws):
+    rows = sample_rows_host.contiguous()
+    assert rows.device.type == "cpu" and rows.dtype == torch.int64
+    _check(lib().kmeans_run_sampled(C.byref(p), _ptr(X), rows.numel(), _ptr(rows), iters, _ptr(Cc), _ptr(labels),
+                                    _ptr(counts), _ptr(objective_hist), _ptr(ws), ws.numel(), _stream()),
+           "kmeans_run_sampled")
 
 
 def _is_i64(rowptr):

@@ -89,6 +89,33 @@ def test_null_pointers_workspace_and_flags():
     assert L.kmeans_init(C.byref(p), fake, idx, fake, ws, need, None) == ep.EP_EINVAL
 
 
+def test_sampled_run_rejects_bad_arguments():
+    L = ep.lib()
+    p = _prob()                                              # n = 1000, k = 8
+    out = C.c_size_t(0)
+    assert L.kmeans_sampled_workspace_bytes(C.byref(p), 7, C.byref(out)) == ep.EP_EINVAL      # m < k
+    assert L.kmeans_sampled_workspace_bytes(C.byref(p), 1001, C.byref(out)) == ep.EP_EINVAL   # m > n
+    assert L.kmeans_sampled_workspace_bytes(C.byref(p), 64, None) == ep.EP_EINVAL
+    need = ep.kmeans_sampled_workspace_bytes(p, 64)
+    assert need > ep.kmeans_workspace_bytes(p) + 64 * 128 * 4 and need % 256 == 0
+    fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)
+    rows = (C.c_int64 * 64)(*range(64))
+    args = lambda **kw: [kw.get("p", C.byref(p)), kw.get("X", fake), kw.get("m", 64), kw.get("rows", rows),
+                         kw.get("iters", 3), kw.get("C", fake), kw.get("labels", fake), kw.get("counts", fake), None,
+                         kw.get("ws", ws), kw.get("bytes", need), None]
+    assert L.kmeans_run_sampled(*args(rows=None)) == ep.EP_EINVAL
+    assert L.kmeans_run_sampled(*args(m=7)) == ep.EP_EINVAL
+    assert L.kmeans_run_sampled(*args(iters=-1)) == ep.EP_EINVAL
+    assert L.kmeans_run_sampled(*args(labels=None)) == ep.EP_EINVAL
+    assert L.kmeans_run_sampled(*args(counts=None)) == ep.EP_EINVAL
+    assert L.kmeans_run_sampled(*args(ws=None)) == ep.EP_EWORKSPACE
+    assert L.kmeans_run_sampled(*args(bytes=need - 1)) == ep.EP_EWORKSPACE
+    rows[5] = 1000                                           # row index out of range
+    assert L.kmeans_run_sampled(*args()) == ep.EP_EINVAL
+    rows[5] = -1
+    assert L.kmeans_run_sampled(*args()) == ep.EP_EINVAL
+
+
 def test_graph_calls_reject_bad_arguments():
     L = ep.lib()
     fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)

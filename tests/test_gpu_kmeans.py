@@ -209,3 +209,51 @@ def test_device_errors_are_reported_not_thrown():
     with pytest.raises(ep.EmbedPartError) as e:
         ep.kmeans_assign(km.p, km.X, km.C, km.labels, None, None, small)
     assert e.value.code == ep.EP_EWORKSPACE
+
+
+# ---- sample-trained K-Means ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,d,k,dtype,per_cluster,iters", [
+    (50_021, 128, 8, torch.float32, 512, 8),       # the paper's 2^9 rows per cluster
+    (30_011, 64, 40, torch.float32, 128, 5),
+    (20_007, 128, 300, torch.bfloat16, 32, 3),     # matrix-core path for the sample and the full assignment
+    (3_001, 20, 5, torch.float32, 600, 4),         # generic kernels, unpadded row stride, sample = everything
+])
+def test_sampled_run_matches_oracle(n, d, k, dtype, per_cluster, iters):
+    bf16 = dtype == torch.bfloat16
+    X = _mixture(n, d, min(k, 31), seed=3 * n + k, relu=True, dtype=dtype)
+    X32 = to_np32(X)
+    m = min(n, per_cluster * k)
+    rows = oracle.init_indices(n + 17, n, m)
+    p = ep.problem(X, k)
+    ws = ep.workspace(ep.kmeans_sampled_workspace_bytes(p, m), DEV)
+    Cd = torch.full((k, d), float("nan"), dtype=torch.float32, device=DEV)
+    labels = torch.full((n,), -7, dtype=torch.int32, device=DEV)
+    counts = torch.full((k,), -7, dtype=torch.int64, device=DEV)
+    hist = torch.full((iters + 1,), float("nan"), dtype=torch.float64, device=DEV)
+    ep.kmeans_run_sampled(p, X, torch.from_numpy(rows), iters, Cd, labels, counts, hist, ws)
+    torch.cuda.synchronize()
+    got_C, got_labels, got_hist = Cd.cpu().numpy(), labels.cpu().numpy(), hist.cpu().numpy()
+
+    # training: exactly what kmeans_run gives on the gathered rows (whose parity with the oracle's
+    # rounds check_free_running establishes), started from the sample's first k rows
+    S = X[torch.from_numpy(rows).to(DEV)].contiguous()
+    ref = Kmeans(S, k).init(np.arange(k)).run(iters)
+    np.testing.assert_array_equal(got_C, ref["C"])
+    np.testing.assert_array_equal(counts.cpu().numpy(), ref["counts"])
+    np.testing.assert_array_equal(got_hist[:iters], ref["obj_hist"][:iters])
+    check_free_running(S, k, iters, np.arange(k), bf16=bf16)
+
+    # full assignment: the oracle's search over all rows against the centroids the device trained
+    used = centroids_used(got_C, bf16)
+    want, best, _, obj_or = oracle.assign(X32, used)
+    differing, unexcused = label_mismatches(X32, used, got_labels, want, best)
+    assert unexcused == 0, f"{unexcused} of {differing} differing labels are not near-ties"
+    assert abs(got_hist[iters] - obj_or) <= 1e-5 * obj_or
+
+    # and the whole pipeline against the oracle's own: when the two trainings agree to the centroid
+    # tolerance, the two full assignments may differ only at points that sit on a boundary
+    orc = oracle.sampled_kmeans(X32, k, iters, rows, flags=oracle.FLAG_BF16_CENTROIDS if bf16 else 0)
+    if centroid_rel_err(got_C, orc["C"]) <= CENTROID_RTOL:
+        np.testing.assert_array_equal(counts.cpu().numpy(), orc["counts"])
+        assert np.count_nonzero(got_labels != orc["labels"]) <= max(3, n // 2000)
