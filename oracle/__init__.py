@@ -64,6 +64,8 @@ def lib():
         L.or_edge_cut_ratio.restype = C.c_double
         L.or_vertex_balance.argtypes = [C.c_int32, p]
         L.or_vertex_balance.restype = C.c_double
+        L.or_balance.argtypes = [C.c_int64, C.c_int32, p, p, C.c_int32, C.c_double, C.c_uint64, C.c_int32, p, p]
+        L.or_balance.restype = C.c_int
         L.or_permutation.argtypes = [C.c_int64, C.c_int32, p, p, p]
         L.or_permutation.restype = C.c_int
         L.or_edge_gap_sum.argtypes = [C.c_int64, p, p, p]
@@ -194,6 +196,22 @@ def edge_cut_ratio(cut: int, nnz: int) -> float:
 def vertex_balance(sizes) -> float:
     sizes = np.ascontiguousarray(sizes, dtype=np.int64)
     return lib().or_vertex_balance(sizes.shape[0], _ptr(sizes))
+
+
+def balance(rowptr, labels, k: int, beta: float, seed: int, max_rounds: int = 64, vclass=None, class_id: int = 0):
+    """Balancing of one vertex class (Alg. 3 loop + Alg. 4).  Returns (new labels int32[n], stats int64[3] =
+    rounds run, vertices moved, partitions still overloaded)."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    out = np.array(labels, dtype=np.int32, copy=True)
+    n = rowptr.shape[0] - 1
+    assert out.shape == (n,)
+    vc = None if vclass is None else np.ascontiguousarray(vclass, dtype=np.uint8)
+    stats = np.zeros(3, dtype=np.int64)
+    rc = lib().or_balance(n, k, _ptr(rowptr), None if vc is None else _ptr(vc), class_id, float(beta),
+                          seed & (2**64 - 1), max_rounds, _ptr(out), _ptr(stats))
+    if rc != 0:
+        raise ValueError("balance: bad arguments")
+    return out, stats
 
 
 def permutation(labels, k: int):

@@ -12,6 +12,9 @@
  *     (Sec. "Phase 2: Clustering and Balancing").
  *   - Sec. "Implementation": the centroids are computed on a sample of the
  *     embeddings (2^9 per cluster), then every vertex is assigned.
+ *   - Alg. 3 (the balancing loops) with the migration policy of Alg. 4:
+ *     vertices move from overloaded to underloaded partitions, smallest degree
+ *     first, destinations drawn in proportion to free capacity.
  *   - Sec. "Partitioning quality metrics": an edge (u,v) is cut iff
  *     pid(u) != pid(v); ECR = |C|/|E|; vertex balance = max|P_i| / mean|P_i|.
  *   - Sec. "Extension to Graph Reordering": gap xi_pi(u,v) = |pi(u)-pi(v)|,
@@ -31,7 +34,11 @@
  * closed-form cuts on paths / cycles / complete graphs / matchings,
  * adjacency-matrix brute force, balance extremes, permutation bijectivity;
  * sample-trained run: identity sample = Lloyd + one re-assignment, labels are
- * the brute-force nearest centroid, rows outside the sample do not move C.
+ * the brute-force nearest centroid, rows outside the sample do not move C;
+ * balancing: a hand-worked two-partition case, balanced input untouched, the
+ * movers are the smallest-degree members (independent argsort), loads within
+ * capacity afterwards, destinations in proportion to free capacity, the draw
+ * function restated with Python integers.
  * Numerical parity with figures printed in the paper is unpinned: every such
  * figure depends on datasets and trained weights that are not available.
  *
@@ -299,6 +306,106 @@ double or_vertex_balance(int32_t k, const int64_t *sizes)
         if (sizes[p] > mx) mx = sizes[p];
     }
     return (double)mx / ((double)total / (double)k);
+}
+
+/* ---- balancing (Alg. 3 loops, Alg. 4 migration policy) ---------------------- */
+
+/*
+ * One stateless draw: the destination of vertex v in migration round `round`
+ * is decided by a 64-bit mix of (seed, round, v), so the order in which the
+ * vertices are visited does not matter.  The mix is the splitmix64 output
+ * function applied to seed + (round * 2^32 + v + 1) * golden-ratio increment.
+ */
+static uint64_t draw64(uint64_t seed, uint32_t round, int64_t v)
+{
+    uint64_t z = seed + (((uint64_t)round << 32) + (uint64_t)v + 1ULL) * 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+typedef struct { int64_t degree; int64_t v; } or_cand;
+static int cand_less(const void *a, const void *b)
+{
+    const or_cand *x = (const or_cand *)a, *y = (const or_cand *)b;
+    if (x->degree != y->degree) return x->degree < y->degree ? -1 : 1;
+    return x->v < y->v ? -1 : (x->v > y->v ? 1 : 0);
+}
+
+/*
+ * Balancing of one vertex class (one of the three while-loops of Alg. 3) with
+ * the migration policy of Alg. 4.
+ *   S          = {v : vclass == NULL or vclass[v] == class_id}, the candidate set
+ *   capacity   C = max(floor(beta * |S| / k), ceil(|S| / k)) for every partition
+ *                (Alg. 3: a partition is overloaded iff its load exceeds
+ *                beta * |S| / k; the second term only keeps the target reachable
+ *                when beta is so close to 1 that k * floor(..) < |S|)
+ *   per round  loads L_i over S; O = {L_i > C}, U = {L_i < C}; f_i = C - L_i on U,
+ *              F = sum f_i; from every i in O the m_i = L_i - C members of S with
+ *              the smallest degree move (reading: ties by smaller vertex id; the
+ *              degree is the stored row length rowptr[v+1] - rowptr[v]); each
+ *              goes to j in U with probability f_j / F: r = draw64 mod F, j = the
+ *              partition whose interval of the running sum of f (partitions in
+ *              index order) holds r.  All draws of a round use that round's L.
+ *   rounds     repeat while some partition is overloaded, at most max_rounds.
+ * stats[0] = rounds run, stats[1] = vertices moved in total, stats[2] = partitions
+ * still overloaded at the end.  Returns 0, or -1 on bad arguments.
+ */
+int or_balance(int64_t n, int32_t k, const int64_t *rowptr, const uint8_t *vclass,
+               int32_t class_id, double beta, uint64_t seed, int32_t max_rounds,
+               int32_t *labels, int64_t *stats)
+{
+    if (n < 1 || k < 1 || k > 255 || !rowptr || !labels || !stats || max_rounds < 0 || !(beta >= 1.0)) return -1;
+    for (int64_t v = 0; v < n; ++v)
+        if (labels[v] < 0 || labels[v] >= k) return -1;
+    int64_t *L = (int64_t *)calloc((size_t)k, sizeof(int64_t));
+    int64_t *cumf = (int64_t *)calloc((size_t)k, sizeof(int64_t));
+    or_cand *cand = (or_cand *)malloc((size_t)n * sizeof(or_cand));
+    int32_t *dest = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    if (!L || !cumf || !cand || !dest) { free(L); free(cumf); free(cand); free(dest); return -1; }
+    stats[0] = stats[1] = stats[2] = 0;
+    for (int32_t round = 0;; ++round) {
+        int64_t total = 0;
+        for (int32_t i = 0; i < k; ++i) L[i] = 0;
+        for (int64_t v = 0; v < n; ++v)
+            if (!vclass || vclass[v] == class_id) { L[labels[v]]++; total++; }
+        int64_t C = (int64_t)floor(beta * (double)total / (double)k);
+        const int64_t reach = (total + k - 1) / k;
+        if (C < reach) C = reach;
+        int64_t F = 0, over = 0;
+        for (int32_t i = 0; i < k; ++i) {
+            if (L[i] < C) F += C - L[i];
+            cumf[i] = F;                       /* running sum of the free capacities */
+            if (L[i] > C) over++;
+        }
+        stats[2] = over;
+        if (over == 0 || round >= max_rounds) break;
+        stats[0] = round + 1;
+        for (int64_t v = 0; v < n; ++v) dest[v] = -1;
+        for (int32_t i = 0; i < k; ++i) {
+            if (L[i] <= C) continue;
+            int64_t cnt = 0;
+            for (int64_t v = 0; v < n; ++v)
+                if ((!vclass || vclass[v] == class_id) && labels[v] == i) {
+                    cand[cnt].degree = rowptr[v + 1] - rowptr[v];
+                    cand[cnt].v = v;
+                    cnt++;
+                }
+            qsort(cand, (size_t)cnt, sizeof(or_cand), cand_less);
+            const int64_t m = L[i] - C;
+            for (int64_t q = 0; q < m; ++q) {
+                const int64_t v = cand[q].v;
+                const uint64_t r = draw64(seed, (uint32_t)round, v) % (uint64_t)F;
+                int32_t j = 0;
+                while ((uint64_t)cumf[j] <= r) ++j;   /* first partition whose running sum exceeds r */
+                dest[v] = j;
+            }
+        }
+        for (int64_t v = 0; v < n; ++v)
+            if (dest[v] >= 0) { labels[v] = dest[v]; stats[1]++; }
+    }
+    free(L); free(cumf); free(cand); free(dest);
+    return 0;
 }
 
 /* ---- reordering ------------------------------------------------------------ */
