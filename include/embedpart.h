@@ -55,6 +55,8 @@ extern "C" {
 #define EP_MAX_D          1024
 #define EP_MAX_K          65536
 #define EP_MAX_N          ((int64_t)1 << 31)   /* vertex ids and labels are int32; n < 2^31 */
+#define EP_BALANCE_MAX_K      255              /* partition_balance: partition-scale k only */
+#define EP_BALANCE_MAX_ROUNDS 1024
 
 /* The clustering problem: n embeddings of dimension d, row-major with row
  * stride ld (elements, ld >= d), to be grouped into k clusters.
@@ -196,6 +198,34 @@ int partition_permutation(int64_t n, int32_t k, const int32_t *labels,
 int edge_gap_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
                  const int32_t *colidx, const int32_t *new_id,
                  uint64_t *gap_sum, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Balancing of a partition for ONE vertex class: one of the three loops of the paper's Alg. 3
+ * (training, validation, remaining vertices) with the migration policy of Alg. 4. While some
+ * partition holds more than C = max(floor(beta |S| / k), ceil(|S| / k)) members of the class S,
+ * every overloaded partition gives up its L_i - C members of smallest degree (equal degrees:
+ * smaller vertex id first; degree = rowptr[v+1] - rowptr[v], degrees of 2^24 and more count as
+ * equal), and each of them goes to an underloaded partition drawn with probability proportional
+ * to its free capacity: r = mix64(seed, round, v) mod F over the running sum of the free
+ * capacities in partition order (mix64 = the splitmix64 output function applied to
+ * seed + (round * 2^32 + v + 1) * 0x9E3779B97F4A7C15).  All draws of a round use the loads at its
+ * start.  At most max_rounds rounds are enqueued; rounds after the last needed one do nothing.
+ *   rowptr     n + 1 offsets, int32 or int64 (rowptr_is_i64); only the row lengths are used
+ *   vclass     n bytes, class of every vertex, or NULL: all vertices form the class
+ *   class_id   the class to balance (0..255)
+ *   beta       imbalance factor, >= 1
+ *   labels     n int32 in [0, k), updated in place
+ *   stats      3 int64, written: rounds that moved vertices, vertices moved, partitions still
+ *              overloaded after the last round (0 = balanced)
+ *   ws         balance_workspace_bytes(n) bytes
+ * k <= EP_BALANCE_MAX_K (else EP_EUNSUPPORTED); 0 <= max_rounds <= EP_BALANCE_MAX_ROUNDS.
+ * Integer arithmetic and a counter-based draw: the result is bit-reproducible.
+ */
+int balance_workspace_bytes(int64_t n, size_t *bytes_host);
+int partition_balance(int64_t n, int32_t k, const void *rowptr, int rowptr_is_i64,
+                      const uint8_t *vclass, int32_t class_id, double beta, uint64_t seed,
+                      int32_t max_rounds, int32_t *labels, int64_t *stats,
+                      void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Sum over vertices of the vertex bandwidth max_{u in N(v)} |pi(v) - pi(u)|

@@ -297,6 +297,27 @@ int partition_permutation(int64_t n, int32_t k, const int32_t *labels, int32_t *
                                 static_cast<hipStream_t>(stream));
 }
 
+int balance_workspace_bytes(int64_t n, size_t *bytes_host) {
+    if (n < 1 || n >= EP_MAX_N || !bytes_host) return EP_EINVAL;
+    *bytes_host = carve_balance_ws(n, nullptr).bytes;
+    return EP_OK;
+}
+
+int partition_balance(int64_t n, int32_t k, const void *rowptr, int rowptr_is_i64, const uint8_t *vclass,
+                      int32_t class_id, double beta, uint64_t seed, int32_t max_rounds, int32_t *labels,
+                      int64_t *stats, void *ws, size_t ws_bytes, void *stream) {
+    if (n < 1 || n >= EP_MAX_N || k < 1 || !rowptr || !aligned(rowptr, 8) || !labels || !stats || !aligned(stats, 8))
+        return EP_EINVAL;
+    if (!(beta >= 1.0) || !(beta < 1.0e6) || max_rounds < 0 || max_rounds > EP_BALANCE_MAX_ROUNDS || class_id < 0 ||
+        class_id > 255)
+        return EP_EINVAL;
+    if (k > EP_BALANCE_MAX_K) return EP_EUNSUPPORTED;
+    int rc = check_ws(ws, ws_bytes, carve_balance_ws(n, nullptr).bytes);
+    if (rc != EP_OK) return rc;
+    return launch_balance(n, k, rowptr, rowptr_is_i64 != 0, vclass, class_id, beta, seed, max_rounds, labels, stats,
+                          carve_balance_ws(n, ws), static_cast<hipStream_t>(stream));
+}
+
 static int gap_call(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
                     const int32_t *new_id, uint64_t *out, EdgeReduce what, void *ws, size_t ws_bytes, void *stream) {
     int rc = check_graph(n, nnz, rowptr, colidx);

@@ -450,9 +450,8 @@ int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const 
                : launch_sweep_rows<int32_t, kBandwidth>(n, nnz, 0, rowptr, i64, colidx, new_id, out, s);
 }
 
-int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
-                         int32_t *tmp, int32_t *hist, hipStream_t s) {
-    const int passes = k <= kRadix ? 1 : 2;          // k <= 65536
+int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
+                       int32_t *hist, hipStream_t s) {
     int64_t rows_per_block = std::max<int64_t>(ceil_div(n, kSortBlocksMax), 2048);
     rows_per_block = ceil_div(rows_per_block, kBlock) * kBlock;
     const int blocks = (int)ceil_div(n, rows_per_block);
@@ -461,17 +460,22 @@ int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *n
     for (int pass = 0; pass < passes; ++pass) {
         int32_t *dst = (passes - pass) % 2 == 1 ? order : tmp;
         const bool last = pass == passes - 1;
-        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, labels, src, 8 * pass, hist);
+        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist);
         EP_LAUNCH_CHECK();
         sort_scan_kernel<<<kRadix, kRadix, 0, s>>>(hist, blocks, hist + (size_t)kSortBlocksMax * kRadix);
         EP_LAUNCH_CHECK();
-        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, labels, src, 8 * pass, hist,
+        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist,
                                                       hist + (size_t)kSortBlocksMax * kRadix, dst,
                                                       last ? new_id : nullptr);
         EP_LAUNCH_CHECK();
         src = dst;
     }
     return EP_OK;
+}
+
+int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
+                         int32_t *tmp, int32_t *hist, hipStream_t s) {
+    return launch_sort_by_key(n, k <= kRadix ? 1 : 2, labels, new_id, order, tmp, hist, s);   // k <= 65536
 }
 
 }  // namespace ep

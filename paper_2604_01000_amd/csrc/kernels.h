@@ -80,9 +80,27 @@ int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowp
 // Stable sort of vertex ids by label: order (sorted position -> vertex) and, if non-null, new_id (its inverse).
 int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
                          int32_t *tmp, int32_t *hist, hipStream_t s);
+// Stable LSD radix sort of vertex ids by the low 8 * passes bits of keys[v].
+int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
+                       int32_t *hist, hipStream_t s);
 int launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 enum class EdgeReduce { GapSum, BandwidthSum };
 int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const int32_t *colidx,
                     const int32_t *new_id, uint64_t *out, EdgeReduce what, const GraphWs &w, hipStream_t s);
+
+// ---- balancing (balance.hip) -------------------------------------------------------
+struct BalanceWs {
+    unsigned char *plan;  // per-round plan (loads, moves, free capacities, segment starts)
+    int32_t *keys;        // [n]
+    int32_t *order;       // [n]
+    int32_t *tmp;         // [n]
+    int32_t *sort_hist;
+    size_t bytes;
+};
+BalanceWs carve_balance_ws(int64_t n, void *ws);
+// Up to max_rounds migration rounds of one vertex class; k <= 255.
+int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uint8_t *vclass, int32_t class_id,
+                   double beta, uint64_t seed, int32_t max_rounds, int32_t *labels, int64_t *stats,
+                   const BalanceWs &w, hipStream_t s);
 
 }  // namespace ep

@@ -20,12 +20,14 @@ EP_F32, EP_BF16 = 0, 1
 EP_RUN_FINAL_REASSIGN = 1
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
 EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the header
+EP_BALANCE_MAX_K, EP_BALANCE_MAX_ROUNDS = 255, 1024
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
     "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_sampled_workspace_bytes",
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
+    "balance_workspace_bytes", "partition_balance",
     "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
@@ -68,6 +70,8 @@ def lib() -> C.CDLL:
         L.graph_workspace_bytes.argtypes = [i64, i64, i32, C.POINTER(sz)]
         L.partition_quality.argtypes = [i64, i64, i32, vp, C.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.partition_permutation.argtypes = [i64, i32, vp, vp, vp, vp, sz, vp]
+        L.balance_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
+        L.partition_balance.argtypes = [i64, i32, vp, C.c_int, vp, i32, C.c_double, C.c_uint64, i32, vp, vp, vp, sz, vp]
         L.edge_gap_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.vertex_bandwidth_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
@@ -170,6 +174,18 @@ def kmeans_run_sampled(p, X, sample_rows_host, iters, Cc, labels, counts, object
     _check(lib().kmeans_run_sampled(C.byref(p), _ptr(X), rows.numel(), _ptr(rows), iters, _ptr(Cc), _ptr(labels),
                                     _ptr(counts), _ptr(objective_hist), _ptr(ws), ws.numel(), _stream()),
            "kmeans_run_sampled")
+
+
+def balance_workspace_bytes(n: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().balance_workspace_bytes(n, C.byref(out)), "balance_workspace_bytes")
+    return out.value
+
+
+def partition_balance(n, k, rowptr, vclass, class_id, beta, seed, max_rounds, labels, stats, ws):
+    _check(lib().partition_balance(n, k, _ptr(rowptr), _is_i64(rowptr), _ptr(vclass), class_id, float(beta),
+                                   seed & (2**64 - 1), max_rounds, _ptr(labels), _ptr(stats), _ptr(ws), ws.numel(),
+                                   _stream()), "partition_balance")
 
 
 def _is_i64(rowptr):

@@ -35,7 +35,7 @@ def test_binding_constants_equal_the_header():
     text = HEADER.read_text()
     defines = dict(re.findall(r"#define\s+(EP_\w+)\s+\(?(-?\d+)\)?\s", text))
     for name in ("EP_OK", "EP_EINVAL", "EP_EUNSUPPORTED", "EP_EWORKSPACE", "EP_EHIP", "EP_F32", "EP_BF16",
-                 "EP_RUN_FINAL_REASSIGN", "EP_MAX_D", "EP_MAX_K", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
+                 "EP_RUN_FINAL_REASSIGN", "EP_MAX_D", "EP_MAX_K", "EP_BALANCE_MAX_K", "EP_BALANCE_MAX_ROUNDS", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
                  "EP_PROF_EDGE_SWEEP"):
         assert int(defines[name]) == getattr(ep, name), name
     assert "((int64_t)1 << 31)" in text and ep.EP_MAX_N == 1 << 31
@@ -114,6 +114,31 @@ def test_sampled_run_rejects_bad_arguments():
     assert L.kmeans_run_sampled(*args()) == ep.EP_EINVAL
     rows[5] = -1
     assert L.kmeans_run_sampled(*args()) == ep.EP_EINVAL
+
+
+def test_balance_rejects_bad_arguments():
+    L = ep.lib()
+    fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)
+    out = C.c_size_t(0)
+    assert L.balance_workspace_bytes(0, C.byref(out)) == ep.EP_EINVAL
+    assert L.balance_workspace_bytes(10, None) == ep.EP_EINVAL
+    need = ep.balance_workspace_bytes(1000)
+    assert need >= 3 * 4 * 1000 and need % 256 == 0
+    call = lambda **kw: L.partition_balance(kw.get("n", 1000), kw.get("k", 8), kw.get("rowptr", fake), 0, None, 0,
+                                            kw.get("beta", 1.05), 7, kw.get("rounds", 8), kw.get("labels", fake),
+                                            kw.get("stats", fake), kw.get("ws", ws), kw.get("bytes", need), None)
+    assert call(n=0) == ep.EP_EINVAL
+    assert call(k=0) == ep.EP_EINVAL
+    assert call(k=256) == ep.EP_EUNSUPPORTED
+    assert call(rowptr=None) == ep.EP_EINVAL
+    assert call(labels=None) == ep.EP_EINVAL
+    assert call(stats=None) == ep.EP_EINVAL
+    assert call(beta=0.99) == ep.EP_EINVAL
+    assert call(beta=float("nan")) == ep.EP_EINVAL
+    assert call(rounds=-1) == ep.EP_EINVAL
+    assert call(rounds=ep.EP_BALANCE_MAX_ROUNDS + 1) == ep.EP_EINVAL
+    assert call(ws=None) == ep.EP_EWORKSPACE
+    assert call(bytes=need - 1) == ep.EP_EWORKSPACE
 
 
 def test_graph_calls_reject_bad_arguments():
