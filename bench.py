@@ -149,6 +149,41 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict
         step()
         torch.cuda.synchronize()
 
+    # ---- the balancing loops of the paper's Alg. 3 on the K-Means partition (partition-scale k only):
+    # ---- three vertex classes (seeded: 55% / 15% / 30%), beta = 1.05, timed beside the headline ----
+    balance = None
+    if w.k <= ep.EP_BALANCE_MAX_K:
+        g = torch.Generator(device="cpu").manual_seed(w.seed + 7)
+        vclass = torch.bucketize(torch.rand(w.n, generator=g), torch.tensor([0.55, 0.70])).to(torch.uint8).to(dev)
+        bws = ep.workspace(ep.balance_workspace_bytes(w.n), dev)
+        stats = torch.zeros((3, 3), dtype=torch.int64, device=dev)
+        blabels = labels.clone()
+        cut_b = torch.zeros(1, dtype=torch.int64, device=dev)
+        sizes_b = torch.zeros(w.k, dtype=torch.int64, device=dev)
+
+        def balance_all():
+            blabels.copy_(labels)
+            for cls in range(3):
+                ep.partition_balance(w.n, w.k, rowptr, vclass, cls, 1.05, w.seed + cls, 16, blabels, stats[cls], bws)
+
+        balance_all()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            balance_all()
+        b.record()
+        torch.cuda.synchronize()
+        ep.partition_quality(w.n, nnz, w.k, rowptr, colidx, blabels, cut_b, sizes_b, gws)
+        torch.cuda.synchronize()
+        st = stats.cpu().numpy()
+        balance = dict(ms=a.elapsed_time(b) / steps, beta=1.05, max_rounds=16, rounds=st[:, 0].tolist(),
+                       moved=st[:, 1].tolist(), still_overloaded=st[:, 2].tolist(),
+                       vertex_balance_before=int(sizes.max().item()) * w.k / w.n,
+                       vertex_balance_after=int(sizes_b.max().item()) * w.k / w.n,
+                       edge_cut_ratio_before=int(cut.item()) / max(nnz, 1),
+                       edge_cut_ratio_after=int(cut_b.item()) / max(nnz, 1))
+        del bws, blabels, vclass
+
     # ---- copy bandwidth of this machine, for context: a plain 16-byte-per-lane copy of X ----
     Y = torch.empty_like(X)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -206,7 +241,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict
                 config=dict(workload=w.name, n=w.n, d=w.d, k=w.k, iters=w.iters, nnz=nnz,
                             step="kmeans_init + kmeans_run + partition_quality" +
                                  (" + partition_permutation + edge_gap_sum" if reorder else "")),
-                roofline=roofline, cpu_baseline=cpu, reference=reference, quality=quality, sampled_variant=sampled,
+                roofline=roofline, cpu_baseline=cpu, reference=reference, quality=quality, sampled_variant=sampled, balance_variant=balance,
                 labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
 
 

@@ -14,8 +14,9 @@
 //   5. the first m_i vertices of partition i's run move; the destination of vertex v is the
 //      partition whose interval of the running sum holds (mix(seed, round, v) mod F).
 // The draw is a function of (seed, round, v) only, so the result does not depend on the order in
-// which threads get to the vertices.  Rounds whose plan finds nothing overloaded do nothing: the
-// host enqueues max_rounds rounds without ever reading anything back.
+// which threads get to the vertices.  Rounds whose plan finds nothing overloaded do nothing (every
+// kernel after the plan reads its `active` flag and returns): the host enqueues max_rounds rounds
+// without ever reading anything back.
 #include <algorithm>
 
 #include "kernels.h"
@@ -92,9 +93,9 @@ __global__ __launch_bounds__(kBlock) void bal_keys_kernel(int64_t n, int32_t k, 
                                                            const BalPlan *__restrict__ plan,
                                                            int32_t *__restrict__ keys) {
     const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v >= n) return;
+    if (v >= n || !plan->active) return;
     uint32_t key = kStay;
-    if (plan->active && (!vclass || vclass[v] == class_id)) {
+    if (!vclass || vclass[v] == class_id) {
         const int32_t l = labels[v];
         if (l >= 0 && l < k && plan->m[l] > 0) {
             const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void bal_keys_kernel(int64_t n, int32_t k, 
 __global__ void bal_segments_kernel(int64_t n, const int32_t *__restrict__ keys, const int32_t *__restrict__ order,
                                     BalPlan *plan) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n) return;
+    if (i > n || !plan->active) return;
     const int prev = i == 0 ? -1 : (int)((uint32_t)keys[order[i - 1]] >> 24);
     const int cur = i == n ? 256 : (int)((uint32_t)keys[order[i]] >> 24);
     for (int j = prev + 1; j <= cur; ++j) plan->seg[j] = i;
@@ -186,7 +187,7 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
             bal_keys_kernel<int32_t><<<per_vertex, kBlock, 0, s>>>(n, k, static_cast<const int32_t *>(rowptr), vclass,
                                                                    class_id, labels, plan, w.keys);
         EP_LAUNCH_CHECK();
-        int rc = launch_sort_by_key(n, 4, w.keys, nullptr, w.order, w.tmp, w.sort_hist, s);
+        int rc = launch_sort_by_key(n, 4, w.keys, nullptr, w.order, w.tmp, w.sort_hist, &plan->active, s);
         if (rc != EP_OK) return rc;
         bal_segments_kernel<<<(unsigned)ceil_div(n + 1, kBlock), kBlock, 0, s>>>(n, w.keys, w.order, plan);
         EP_LAUNCH_CHECK();

@@ -300,7 +300,8 @@ __device__ __forceinline__ int32_t sort_key(const int32_t *__restrict__ labels, 
 __global__ __launch_bounds__(kBlock) void sort_hist_kernel(int64_t n, int64_t rows_per_block,
                                                             const int32_t *__restrict__ labels,
                                                             const int32_t *__restrict__ order_in, int shift,
-                                                            int32_t *__restrict__ hist) {
+                                                            int32_t *__restrict__ hist, const int *__restrict__ enable) {
+    if (enable && !*enable) return;   // uniform over the grid: a sort whose result nobody will use
     __shared__ int32_t h[kRadix];
     h[threadIdx.x] = 0;
     __syncthreads();
@@ -316,7 +317,9 @@ __global__ __launch_bounds__(kBlock) void sort_hist_kernel(int64_t n, int64_t ro
 // hist is [256][blocks] (digit-major).  Workgroup d scans row d in place (exclusive) and writes the
 // row total; the scatter kernel adds the totals of the lower digits itself.
 __global__ __launch_bounds__(kRadix) void sort_scan_kernel(int32_t *__restrict__ hist, int blocks,
-                                                            int32_t *__restrict__ digit_total) {
+                                                            int32_t *__restrict__ digit_total,
+                                                            const int *__restrict__ enable) {
+    if (enable && !*enable) return;
     __shared__ int32_t part[kRadix];
     const int t = threadIdx.x;
     int32_t *row = hist + (int64_t)blockIdx.x * blocks;
@@ -347,7 +350,9 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(int64_t n, int64_t
                                                                const int32_t *__restrict__ offsets,
                                                                const int32_t *__restrict__ digit_total,
                                                                int32_t *__restrict__ order_out,
-                                                               int32_t *__restrict__ new_id) {
+                                                               int32_t *__restrict__ new_id,
+                                                               const int *__restrict__ enable) {
+    if (enable && !*enable) return;
     __shared__ int32_t running[kRadix];
     __shared__ int32_t wcnt[kSortWaves][kRadix];
     const int t = threadIdx.x, wave = t >> 6;
@@ -451,7 +456,7 @@ int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const 
 }
 
 int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
-                       int32_t *hist, hipStream_t s) {
+                       int32_t *hist, const int *enable, hipStream_t s) {
     int64_t rows_per_block = std::max<int64_t>(ceil_div(n, kSortBlocksMax), 2048);
     rows_per_block = ceil_div(rows_per_block, kBlock) * kBlock;
     const int blocks = (int)ceil_div(n, rows_per_block);
@@ -460,13 +465,13 @@ int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_
     for (int pass = 0; pass < passes; ++pass) {
         int32_t *dst = (passes - pass) % 2 == 1 ? order : tmp;
         const bool last = pass == passes - 1;
-        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist);
+        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist, enable);
         EP_LAUNCH_CHECK();
-        sort_scan_kernel<<<kRadix, kRadix, 0, s>>>(hist, blocks, hist + (size_t)kSortBlocksMax * kRadix);
+        sort_scan_kernel<<<kRadix, kRadix, 0, s>>>(hist, blocks, hist + (size_t)kSortBlocksMax * kRadix, enable);
         EP_LAUNCH_CHECK();
         sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist,
                                                       hist + (size_t)kSortBlocksMax * kRadix, dst,
-                                                      last ? new_id : nullptr);
+                                                      last ? new_id : nullptr, enable);
         EP_LAUNCH_CHECK();
         src = dst;
     }
@@ -475,7 +480,7 @@ int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_
 
 int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
                          int32_t *tmp, int32_t *hist, hipStream_t s) {
-    return launch_sort_by_key(n, k <= kRadix ? 1 : 2, labels, new_id, order, tmp, hist, s);   // k <= 65536
+    return launch_sort_by_key(n, k <= kRadix ? 1 : 2, labels, new_id, order, tmp, hist, nullptr, s);   // k <= 65536
 }
 
 }  // namespace ep

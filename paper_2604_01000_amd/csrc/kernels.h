@@ -80,9 +80,10 @@ int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowp
 // Stable sort of vertex ids by label: order (sorted position -> vertex) and, if non-null, new_id (its inverse).
 int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
                          int32_t *tmp, int32_t *hist, hipStream_t s);
-// Stable LSD radix sort of vertex ids by the low 8 * passes bits of keys[v].
+// Stable LSD radix sort of vertex ids by the low 8 * passes bits of keys[v].  enable: nullptr, or a
+// device flag read by every kernel of the sort; 0 turns the whole sort into a no-op.
 int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
-                       int32_t *hist, hipStream_t s);
+                       int32_t *hist, const int *enable, hipStream_t s);
 int launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 enum class EdgeReduce { GapSum, BandwidthSum };
 int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const int32_t *colidx,
