@@ -1,6 +1,7 @@
 // Balancing of a partition: one of the three while-loops of the EmbedPart paper's Alg. 3 with the
-// migration policy of Alg. 4 ("random migration proportional to free capacity", smallest degree
-// first), for one vertex class, entirely on the device and in integers.
+// migration policy of Alg. 4 (movers leave overloaded partitions smallest degree first and land in
+// underloaded ones in proportion to free capacity), for one vertex class, entirely on the device
+// and in integers.
 //
 // A migration round:
 //   1. loads L_i of the class per partition (LDS histogram, integer atomics);
