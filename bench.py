@@ -8,8 +8,9 @@ workload, the partition-sorted relabelling and its edge-gap sum.  The headline v
 point-iterations per second over whole steps (n * iters / step time).
 
 Prints ONE JSON line.  `roofline` describes the kernel that reads X in every Lloyd round, timed
-with HIP events recorded around each of its launches (ep_profile_arm) in a second pass of the
-same steps, so that the events do not perturb the headline timing.  `cpu_baseline` is the fp64
+with HIP events that the library hands to each of its launches (ep_profile_arm; the launch stamps
+them with the kernel's own begin and end) in a second pass of the same steps, so that the events
+do not perturb the headline timing.  `cpu_baseline` is the fp64
 oracle timed on this machine's host cores.
 """
 from __future__ import annotations

@@ -238,9 +238,11 @@ int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_
 
 /*
  * Benchmark aid, not part of the method: per-kernel timing with HIP events the caller owns.
- * While armed, each launch of a kernel of class `kernel_class` made by any call records
- * events_host[2*i] just before and events_host[2*i+1] just after launch number i (counted from
- * arming) on that call's stream, for i < capacity / 2; later launches are not recorded.
+ * While armed, launch number i (counted from arming) of a kernel of class `kernel_class` made by
+ * any call is bracketed by events_host[2*i] and events_host[2*i+1] on that call's stream, for
+ * i < capacity / 2; later launches are not timed.  The tuned Lloyd kernels hand the pair to the
+ * launch itself, which stamps them with the kernel's own begin and end; the other kernels record
+ * them on the stream just before and just after the launch.
  * events_host: host array of hipEvent_t handles created with timing enabled; it must stay
  * valid until disarmed.  ep_profile_arm(NULL, 0, 0) disarms.  This and the HIP error code are
  * the library's only process-global state; arming is not thread-safe.

@@ -12,15 +12,17 @@ void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 static void **g_prof_events = nullptr;
 static int g_prof_capacity = 0, g_prof_class = 0, g_prof_count = 0;
 
-ProfScope::ProfScope(int kernel_class, hipStream_t s) : stop_(nullptr), s_(s) {
+ProfScope::ProfScope(int kernel_class, hipStream_t s, bool kernel_events)
+    : start_(nullptr), stop_(nullptr), s_(s), kernel_events_(kernel_events) {
     if (!g_prof_events || kernel_class != g_prof_class) return;
     const int i = g_prof_count++;
     if (2 * i + 1 >= g_prof_capacity) return;
-    (void)hipEventRecord(static_cast<hipEvent_t>(g_prof_events[2 * i]), s);
+    start_ = static_cast<hipEvent_t>(g_prof_events[2 * i]);
     stop_ = static_cast<hipEvent_t>(g_prof_events[2 * i + 1]);
+    if (!kernel_events_) (void)hipEventRecord(start_, s);
 }
 ProfScope::~ProfScope() {
-    if (stop_) (void)hipEventRecord(stop_, s_);
+    if (stop_ && !kernel_events_) (void)hipEventRecord(stop_, s_);
 }
 
 namespace {

@@ -22,12 +22,17 @@ void note_hip_error(hipError_t e);
 
 #define EP_LAUNCH_CHECK() EP_HIP_TRY(hipGetLastError())
 
-// Records the caller's events around one kernel launch while ep_profile_arm() is in force.
+// Times one kernel launch with the caller's events while ep_profile_arm() is in force.
+// Default: the two events are recorded on the stream before and after the launch (the interval
+// then includes the launch overhead of the bracketing events, a few microseconds).
+// kernel_events: nothing is recorded; the launch site passes start_ / stop_ to
+// hipExtLaunchKernelGGL, which stamps them with the kernel's own begin and end.
 struct ProfScope {
-    ProfScope(int kernel_class, hipStream_t s);
+    ProfScope(int kernel_class, hipStream_t s, bool kernel_events = false);
     ~ProfScope();
-    hipEvent_t stop_;
+    hipEvent_t start_, stop_;
     hipStream_t s_;
+    bool kernel_events_;
 };
 
 constexpr int kWave = 64;

@@ -23,6 +23,8 @@
 //     winner; they are evaluated again on the vector unit (v_dot2_f32_bf16) to name the winner
 //     itself (lowest index on ties) and to produce ||x - c||^2 for the objective: 1/4096 of the
 //     work of step 2, and 1 KB of centroid data per point instead of the whole tile.
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 #include "kernels.h"
@@ -388,8 +390,12 @@ int launch_large(const ep_problem &p, const bf16_t *X, const float *C, const Kme
         // last round drains.)
         const int64_t wg_blocks = ceil_div(ceil_div(p.n, (int64_t)kTile * kMainPointTiles), kWaves);
         const int grid = (int)std::min<int64_t>(wg_blocks, 256 * EP_LARGE_OCC);
-        ProfScope prof(EP_PROF_LLOYD_MAIN, s);
-        large_assign_kernel<D, kMainPointTiles><<<grid, kBlock, 0, s>>>(0, p.n, p.ld, tiles, X, w.records, w.best_tile);
+        ProfScope prof(EP_PROF_LLOYD_MAIN, s, true);
+        if (prof.start_)   // timed launch: the events get the kernel's own begin and end
+            hipExtLaunchKernelGGL((large_assign_kernel<D, kMainPointTiles>), dim3(grid), dim3(kBlock), 0, s, prof.start_,
+                                  prof.stop_, 0, (int64_t)0, p.n, p.ld, tiles, X, w.records, w.best_tile);
+        else
+            large_assign_kernel<D, kMainPointTiles><<<grid, kBlock, 0, s>>>(0, p.n, p.ld, tiles, X, w.records, w.best_tile);
         EP_LAUNCH_CHECK();
     }
     const int blocks = (int)std::min<int64_t>(kObjBlocksMax, ceil_div(p.n, kBlock / 32));

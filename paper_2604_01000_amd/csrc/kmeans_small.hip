@@ -20,6 +20,8 @@
 //     registers for the whole life of the wave, so there are no atomics and no LDS traffic.
 //   * At the end the four waves of a workgroup add their accumulators in wave order through LDS
 //     and store one partial per workgroup; update_finalize_kernel reduces those in fp64.
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 #include <type_traits>
 
@@ -841,7 +843,7 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
     const bool stream_x = (double)p.n * (double)p.ld * 4.0 > kLastLevelCacheBytes;
     double *sp = want_obj ? s_part_of(w) : nullptr;
-    ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s);
+    ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s, true);
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
         constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
@@ -850,8 +852,14 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
         if (lds_bytes > 64 * 1024)                                                                            \
             EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
-        kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, labels_out,  \
-                                                   labels_in, min_d2, w.psum, w.pcnt, sp, xsq_part_of(w));    \
+        if (prof.start_)   /* timed launch: the events get the kernel's own begin and end */                \
+            hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
+                                  p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, labels_out, labels_in, min_d2,  \
+                                  w.psum, w.pcnt, sp, xsq_part_of(w));                                        \
+        else                                                                                                  \
+            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C,          \
+                                                       labels_out, labels_in, min_d2, w.psum, w.pcnt, sp,    \
+                                                       xsq_part_of(w));                                       \
     } while (0)
     if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
