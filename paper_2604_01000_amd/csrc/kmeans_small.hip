@@ -149,7 +149,7 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 
 // XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
 template <int D, int KT, int MODE, bool XSQ, bool STREAM>
-__global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) void lloyd_small_kernel(
+__global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
     int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const float *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
@@ -482,8 +482,12 @@ __global__ __launch_bounds__(kBlock, (KT == 1 || (KT == 2 && D == 64)) ? 2 : 1) 
         }
     };
 
-    if constexpr (kLdsSums && MODE == kFused) {
-        // k > 16, fused round, one wave per SIMD: everything that is not part of the score product
+    if constexpr (kLdsSums && MODE == kFused && KT >= 4) {
+        // k > 32, fused round.  With four centroid tiles the split centroid operand (192 registers) and
+        // the sum tables (137 KB) leave room for one wave per SIMD only, so nothing else hides a wave's
+        // latencies.  (Two tiles fit two waves per SIMD and run the plain loop below: measured
+        // 304 us against 385 us for this pipeline at one wave, n = 2.45 M, k = 32.)
+        // Everything that is not part of the score product
         // (arg-max, labels, ranks, the row adds into the LDS sums) is done one sub-tile late, in the
         // issue slots between the matrix instructions of the next sub-tile.  The deferred work of the
         // previous sub-tile is a list of items (4 arg-max, label store, 2 rank halves, one per 16-byte
