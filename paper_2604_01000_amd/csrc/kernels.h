@@ -12,7 +12,7 @@ constexpr int kSmallKElems = 8192;    // k*d at or below this: per-workgroup LDS
 
 struct KmeansWs {
     double *obj_part;     // [kObjBlocksMax]
-    float *cnorm;         // [k]   ||c_j||^2 of the centroids the distances use
+    float *cnorm;         // [k]   generic path: ||c_j||^2; bf16 matrix-core path: -||c_j||^2 / 2 (of the rounded centroids)
     float *cq;            // [k*d] bf16-rounded centroids as fp32 (EP_BF16 only, else unused)
     bf16_t *cq16;         // [k*d] the same as bf16 (EP_BF16 only)
     float *psum;          // [kUpdBlocksMax * k * d]   (small k)

@@ -6,20 +6,31 @@
 // sums and counts from which the second pass forms the means.
 //
 // Mapping to the hardware (one wave = 64 lanes, lane = 16 * g + c):
-//   * A wave owns a 16-point sub-tile.  Its rows are loaded from HBM with 16-byte loads that are
-//     contiguous across the 16 lanes of a group (group g, step r reads point 4g + r), which is
-//     also the operand layout of the update product.
-//   * x.c runs on the fp32 matrix cores: v_mfma_f32_16x16x4_f32 with the points as the M
-//     dimension and 16 centroids as the N dimension.  That operand needs lane c to hold point c,
-//     so the sub-tile is transposed through a wave-private, padded LDS tile.
-//   * The result holds, in lane (g, c), the scores of points 4g..4g+3 against centroid c; the
-//     argmax is a 16-lane butterfly on (score, index).
-//   * Sums: sums[centroid][column] += onehot[centroid][point] * x[point][column], again on the
-//     matrix cores, contracted over the 16 points of the sub-tile.  Multiplying by exact 0/1
-//     keeps every addition an ordinary fp32 addition in a fixed order; accumulators live in
-//     registers for the whole life of the wave, so there are no atomics and no LDS traffic.
-//   * At the end the four waves of a workgroup add their accumulators in wave order through LDS
-//     and store one partial per workgroup; update_finalize_kernel reduces those in fp64.
+//   * A wave owns a contiguous range of 16-point sub-tiles.  A sub-tile is read with buffer loads
+//     in the layout the score product wants (lane (g, c): point c, columns 16 j + 4 g .. + 3),
+//     one or two sub-tiles ahead of the arithmetic.
+//   * Scores on the matrix cores, points as rows and 16 centroids per tile as columns, the
+//     accumulators preset to -||c||^2 / 2 (formed by the wave itself in its prologue):
+//       k <= 16: v_mfma_f32_16x16x4_f32;
+//       k >  16: six bf16 products of an exact three-way bf16 split of x and c
+//                (v_mfma_f32_16x16x32_bf16), as accurate as the fp32 instruction at a third of
+//                its time.
+//   * The result holds, in lane (g, c), the scores of points 4g .. 4g + 3 against centroid c; the
+//     arg-max is a 16-lane DPP butterfly on an order-preserving integer key (maximum first, then
+//     the lowest index among the lanes that hold it).  Labels are buffered in LDS and written
+//     out in bursts.
+//   * Sums without atomics and in a fixed order:
+//       k <= 16: sums[centroid][column] += onehot[centroid][point] * x[point][column] on the fp32
+//                matrix cores (multiplying by exact 0/1 keeps every addition an ordinary fp32
+//                addition), accumulators in registers for the whole life of the wave; the operand
+//                needs the transposed layout, which costs one trip through a padded LDS tile;
+//       k >  16: a k x d table of sums per wave in LDS; the points of a sub-tile are ranked among
+//                the earlier points with the same label, and round r adds the rows of rank r.
+//   * k <= 32 runs two waves per SIMD; 32 < k <= 64 leaves room for one, and its fused loop is
+//     software-pipelined by hand (the previous sub-tile's vector work sits between the matrix
+//     instructions of the current one).
+//   * At the end the four waves of a workgroup add their sums in wave order through LDS and store
+//     one partial per workgroup; lloyd_small_finalize_kernel reduces those in fp64.
 #include <hip/hip_ext.h>
 
 #include <algorithm>
