@@ -14,11 +14,13 @@
 //     reads are conflict-free) followed by the 32 biases.
 //  2. large_assign_kernel: a wave keeps 128 points (4 operand tiles of 32) in registers and walks
 //     all centroid tiles; records are staged through a 3-deep LDS ring shared by the 4 waves of a
-//     workgroup.  v_mfma_f32_32x32x16_bf16 with centroids as rows and points as columns leaves
-//     16 centroids of one point in each lane, as 4 groups of 4 consecutive rows.  Per tile and
-//     point the epilogue takes the 4 group maxima and their maximum, and keeps (best score, tile,
-//     group maxima) with one compare and selects: about one VALU operation per score, no
-//     per-score index bookkeeping.  The accumulators are preset to the bias from LDS.
+//     workgroup, with LDS-direct loads (no staging registers).  v_mfma_f32_32x32x16_bf16 with
+//     centroids as rows and points as columns leaves 16 centroids of one point in each lane, as
+//     4 groups of 4 consecutive rows.  Per tile and point the fold takes the 4 group maxima and
+//     their maximum and keeps (best score, 8 tile + 2 group) with one compare and two selects:
+//     under one VALU operation per score, no per-score index bookkeeping.  One accumulation
+//     chain per point tile, preset with the bias from LDS; the fold of the previous chain's
+//     result is issued between the matrix instructions of the running chain.
 //  3. large_refine_kernel: the sweep names, per point, 4 consecutive centroid rows that hold the
 //     winner; they are evaluated again on the vector unit (v_dot2_f32_bf16) to name the winner
 //     itself (lowest index on ties) and to produce ||x - c||^2 for the objective: 1/4096 of the
