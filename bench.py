@@ -29,10 +29,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/), scaled by the copy-kernel calibration; None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "arxiv_like": 89_705_751,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
-    "products_like": 1_281_901_216,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
-    "products_reorder": 1_159_370_670,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
-    "papers_like": 57_369_040_283,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
+    "arxiv_like": 89_720_233,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
+    "products_like": 1_281_838_677,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
+    "products_reorder": 1_149_254_277,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
+    "papers_like": 57_357_561_944,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
 }
 
 
@@ -59,7 +59,7 @@ class HipEvents:
             self.hip.hipEventDestroy(C.c_void_p(ev))
 
 
-def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict:
+def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variants: bool = True) -> dict:
     import numpy as np
     import torch
 
@@ -132,7 +132,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict
     # ---- every row (kmeans_run_sampled); timed beside the headline, not part of it ----
     sampled = None
     m = min(w.n, 512 * w.k)
-    if m < w.n:
+    if variants and m < w.n:
         rows = ep.kmeans_init_indices(w.seed + 1, w.n, m)
         sws = ep.workspace(ep.kmeans_sampled_workspace_bytes(p, m), dev)
         ep.kmeans_run_sampled(p, X, rows, w.iters, Cc, labels, counts, hist, sws)
@@ -153,7 +153,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict
     # ---- the balancing loops of the paper's Alg. 3 on the K-Means partition (partition-scale k only):
     # ---- three vertex classes (seeded: 55% / 15% / 30%), beta = 1.05, timed beside the headline ----
     balance = None
-    if w.k <= ep.EP_BALANCE_MAX_K:
+    if variants and w.k <= ep.EP_BALANCE_MAX_K:
         g = torch.Generator(device="cpu").manual_seed(w.seed + 7)
         vclass = torch.bucketize(torch.rand(w.n, generator=g), torch.tensor([0.55, 0.70])).to(torch.uint8).to(dev)
         bws = ep.workspace(ep.balance_workspace_bytes(w.n), dev)
@@ -256,6 +256,8 @@ def main() -> int:
     ap.add_argument("--also", default="products_like",
                     help="comma-separated further workloads reported under 'more' (fewer steps); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the sample-trained and the balancing legs (for profiles of the headline kernels alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -263,11 +265,11 @@ def main() -> int:
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    out = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    out = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, not args.no_variants)
     more = []
     for name in [v for v in args.also.split(",") if v and v != args.workload]:
         torch.cuda.empty_cache()
-        more.append(run_workload(name, max(3, args.steps // 4), 1, False))
+        more.append(run_workload(name, max(3, args.steps // 4), 1, False, not args.no_variants))
     if more:
         out["more"] = more
     print(json.dumps(out))
