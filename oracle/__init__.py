@@ -72,6 +72,8 @@ def lib():
         L.or_edge_gap_sum.restype = C.c_uint64
         L.or_vertex_bandwidth_sum.argtypes = [C.c_int64, p, p, p]
         L.or_vertex_bandwidth_sum.restype = C.c_uint64
+        L.or_reorder_csr.argtypes = [C.c_int64, p, p, p, p, p]
+        L.or_reorder_csr.restype = C.c_int
         _lib = L
     return _lib
 
@@ -237,3 +239,17 @@ def vertex_bandwidth_sum(rowptr, colidx, new_id=None) -> int:
     if new_id is not None:
         new_id = np.ascontiguousarray(new_id, dtype=np.int32)
     return lib().or_vertex_bandwidth_sum(rowptr.shape[0] - 1, _ptr(rowptr), _ptr(colidx), _ptr(new_id))
+
+
+def reorder_csr(rowptr, colidx, new_id):
+    """The graph rewritten under the new ids: returns (new_rowptr int64[n+1], new_colidx int32[nnz]); row
+    new_id[v] holds the neighbours of v under their new ids, ascending."""
+    rowptr, colidx = _csr(rowptr, colidx)
+    new_id = np.ascontiguousarray(new_id, dtype=np.int32)
+    n = rowptr.shape[0] - 1
+    assert new_id.shape == (n,)
+    new_rowptr = np.empty(n + 1, dtype=np.int64)
+    new_colidx = np.empty(colidx.shape[0], dtype=np.int32)
+    if lib().or_reorder_csr(n, _ptr(rowptr), _ptr(colidx), _ptr(new_id), _ptr(new_rowptr), _ptr(new_colidx)) != 0:
+        raise ValueError("reorder_csr: new_id is not a permutation, or a column index is out of range")
+    return new_rowptr, new_colidx

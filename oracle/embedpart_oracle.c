@@ -20,7 +20,8 @@
  *   - Sec. "Extension to Graph Reordering": gap xi_pi(u,v) = |pi(u)-pi(v)|,
  *     vertex bandwidth = max gap over a vertex's neighbours, average graph
  *     bandwidth = its mean over vertices; the reordering gives vertices of
- *     one partition consecutive ids.
+ *     one partition consecutive ids, and the ids are the positions in memory:
+ *     the graph is rewritten under the new ids.
  *
  * The paper names K-Means but none of its details.  The readings taken here
  * (squared Euclidean distance in its direct form, lowest index wins ties, an
@@ -38,7 +39,9 @@
  * balancing: a hand-worked two-partition case, balanced input untouched, the
  * movers are the smallest-degree members (independent argsort), loads within
  * capacity afterwards, destinations in proportion to free capacity, the draw
- * function restated with Python integers.
+ * function restated with Python integers; rewriting the graph under pi: the
+ * permuted sparse matrix of a library routine, gap / bandwidth / cut carried
+ * over unchanged, identity and inverse permutations, a hand-worked graph.
  * Numerical parity with figures printed in the paper is unpinned: every such
  * figure depends on datasets and trained weights that are not available.
  *
@@ -468,4 +471,42 @@ uint64_t or_vertex_bandwidth_sum(int64_t n, const int64_t *rowptr, const int32_t
         total += (uint64_t)widest;
     }
     return total;
+}
+
+/*
+ * The graph rewritten under the new ids (Sec. "Extension to Graph
+ * Reordering": the id of a vertex is its position in memory, so relabelling
+ * means moving the rows).  Row pi(v) of the result holds the neighbours of v
+ * under their new ids.  Reading that makes the result unique: the entries of a
+ * row come in ascending new id (parallel edges stay, side by side).
+ * new_rowptr has n + 1 entries, new_colidx as many as colidx.
+ */
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+int or_reorder_csr(int64_t n, const int64_t *rowptr, const int32_t *colidx,
+                   const int32_t *new_id, int64_t *new_rowptr, int32_t *new_colidx)
+{
+    int32_t *order = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+    for (int64_t r = 0; r < n; ++r) order[r] = -1;
+    for (int64_t v = 0; v < n; ++v) {
+        if (new_id[v] < 0 || new_id[v] >= n || order[new_id[v]] != -1) { free(order); return -1; }
+        order[new_id[v]] = (int32_t)v;
+    }
+    new_rowptr[0] = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        int64_t v = order[r], len = rowptr[v + 1] - rowptr[v], at = new_rowptr[r];
+        for (int64_t j = 0; j < len; ++j) {
+            int32_t u = colidx[rowptr[v] + j];
+            if (u < 0 || u >= n) { free(order); return -1; }
+            new_colidx[at + j] = new_id[u];
+        }
+        qsort(new_colidx + at, (size_t)len, sizeof(int32_t), cmp_i32);
+        new_rowptr[r + 1] = at + len;
+    }
+    free(order);
+    return 0;
 }

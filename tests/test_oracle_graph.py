@@ -150,3 +150,83 @@ def test_clustered_ids_shrink_gaps_on_a_block_graph():
     pi, _ = oracle.permutation(labels, 2)
     assert oracle.edge_gap_sum(rp, ci, pi) < oracle.edge_gap_sum(rp, ci)
     assert oracle.partition_quality(rp, ci, labels, 2)[0] == 0
+
+
+# ---- the graph rewritten under the new ids ---------------------------------------------------
+
+
+def _random_graph(rng, n, m, hub=None):
+    """Random undirected multigraph-free edge list, optionally with one vertex joined to many."""
+    e = set()
+    while len(e) < m:
+        u, v = (int(t) for t in rng.integers(0, n, 2))
+        if u != v:
+            e.add((min(u, v), max(u, v)))
+    if hub is not None:
+        e |= {(min(hub, v), max(hub, v)) for v in range(n) if v != hub and v % 3}
+    return csr_from_undirected(n, sorted(e))
+
+
+def test_reorder_worked_example(golden_dir):
+    g = _golden_rows(golden_dir / "reorder_worked.txt")
+    rp, ci = csr_from_undirected(5, [(0, 1), (0, 2), (0, 4), (1, 3), (2, 4)])
+    new_id, _ = oracle.permutation(np.array(g["labels"], dtype=np.int32), 2)
+    assert new_id.tolist() == [int(t) for t in g["new_id"]]
+    nrp, nci = oracle.reorder_csr(rp, ci, new_id)
+    assert nrp.tolist() == [int(t) for t in g["new_rowptr"]]
+    assert nci.tolist() == [int(t) for t in g["new_colidx"]]
+
+
+def test_reorder_is_the_permuted_matrix():
+    """Rewriting under pi is P A P^T: a library's sparse fancy indexing, never the oracle's own loop."""
+    sp = pytest.importorskip("scipy.sparse")
+    rng = np.random.default_rng(3)
+    for n, m, hub in [(40, 90, None), (300, 1500, 7), (1000, 400, 999)]:   # the last: many empty rows
+        rp, ci = _random_graph(rng, n, m, hub)
+        new_id = rng.permutation(n).astype(np.int32)
+        order = np.argsort(new_id)
+        A = sp.csr_matrix((np.ones(len(ci), dtype=np.int8), ci, rp), shape=(n, n))
+        B = A[order][:, order].tocsr()
+        B.sort_indices()
+        nrp, nci = oracle.reorder_csr(rp, ci, new_id)
+        np.testing.assert_array_equal(nrp, B.indptr)
+        np.testing.assert_array_equal(nci, B.indices)
+
+
+def test_reorder_carries_the_metrics_over():
+    """Gap sum, bandwidth sum and cut of (G, pi) are those of the rewritten graph under the identity."""
+    rng = np.random.default_rng(4)
+    n, k = 500, 6
+    rp, ci = _random_graph(rng, n, 2500, hub=11)
+    labels = rng.integers(0, k, n).astype(np.int32)
+    new_id, order = oracle.permutation(labels, k)
+    nrp, nci = oracle.reorder_csr(rp, ci, new_id)
+    assert oracle.edge_gap_sum(nrp, nci) == oracle.edge_gap_sum(rp, ci, new_id)
+    assert oracle.vertex_bandwidth_sum(nrp, nci) == oracle.vertex_bandwidth_sum(rp, ci, new_id)
+    cut, sizes = oracle.partition_quality(rp, ci, labels, k)
+    cut2, sizes2 = oracle.partition_quality(nrp, nci, labels[order], k)
+    assert cut2 == cut and sizes2.tolist() == sizes.tolist()
+    assert (np.diff(labels[order]) >= 0).all()                     # partitions are contiguous id ranges
+    np.testing.assert_array_equal(np.diff(nrp), np.diff(rp)[order])  # degrees travel with the vertices
+
+
+def test_reorder_identity_inverse_and_multiplicity():
+    rng = np.random.default_rng(5)
+    n = 200
+    rp, ci = _random_graph(rng, n, 700)
+    ident = np.arange(n, dtype=np.int32)
+    nrp, nci = oracle.reorder_csr(rp, ci, ident)          # rows already sorted: unchanged
+    np.testing.assert_array_equal(nrp, rp)
+    np.testing.assert_array_equal(nci, ci)
+    pi = rng.permutation(n).astype(np.int32)
+    inv = np.argsort(pi).astype(np.int32)
+    brp, bci = oracle.reorder_csr(*oracle.reorder_csr(rp, ci, pi), inv)
+    np.testing.assert_array_equal(brp, rp)
+    np.testing.assert_array_equal(bci, ci)
+    # unsorted rows, a parallel edge and a self-loop: sorted, multiplicity kept
+    rp2 = np.array([0, 4, 5, 6], dtype=np.int64)
+    ci2 = np.array([2, 1, 2, 0, 0, 0], dtype=np.int32)
+    nrp, nci = oracle.reorder_csr(rp2, ci2, np.array([2, 0, 1], dtype=np.int32))
+    assert nrp.tolist() == [0, 1, 2, 6] and nci.tolist() == [2, 2, 0, 1, 1, 2]
+    with pytest.raises(ValueError):
+        oracle.reorder_csr(rp2, ci2, np.array([0, 0, 1], dtype=np.int32))     # not a bijection
