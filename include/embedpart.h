@@ -237,6 +237,28 @@ int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_
                          uint64_t *bw_sum, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The graph rewritten under new vertex ids (Sec. "Extension to Graph Reordering": the id of a
+ * vertex is its position in memory, and vertices of one partition get consecutive ids): row
+ * new_id[v] of the result holds the neighbours of v under their new ids, in ascending order
+ * (parallel edges stay, side by side).  Metrics of (graph, pi) equal those of the result under
+ * the identity.
+ *   rowptr, colidx   the graph as for partition_quality
+ *   new_id, order    n int32 each, inverse permutations of [0, n) as partition_permutation
+ *                    writes them: new_id[v] = pi(v), order[pi(v)] = v
+ *   new_rowptr       n + 1 offsets, written, same width as rowptr (8-byte aligned)
+ *   new_colidx       nnz int32, written; must not overlap colidx
+ *   ws               graph_reorder_workspace_bytes(n, nnz) bytes
+ * If `order` is not a permutation (an entry out of range, or the degrees met through it do not
+ * add up to nnz) new_colidx is left unwritten; column indices outside [0, n) are carried over as
+ * they are.  No access leaves the buffers in either case.  EP_EINVAL also for nnz >= 2^31 with
+ * 32-bit offsets.  Integer work only: the result is bit-reproducible.
+ */
+int graph_reorder_workspace_bytes(int64_t n, int64_t nnz, size_t *bytes_host);
+int graph_reorder(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
+                  const int32_t *colidx, const int32_t *new_id, const int32_t *order,
+                  void *new_rowptr, int32_t *new_colidx, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Benchmark aid, not part of the method: per-kernel timing with HIP events the caller owns.
  * While armed, launch number i (counted from arming) of a kernel of class `kernel_class` made by
  * any call is bracketed by events_host[2*i] and events_host[2*i+1] on that call's stream, for

@@ -341,4 +341,23 @@ int vertex_bandwidth_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_
                     stream);
 }
 
+int graph_reorder_workspace_bytes(int64_t n, int64_t nnz, size_t *bytes_host) {
+    if (n < 1 || n >= EP_MAX_N || nnz < 0 || !bytes_host) return EP_EINVAL;
+    *bytes_host = carve_reorder_ws(n, nnz, nullptr).bytes;
+    return EP_OK;
+}
+
+int graph_reorder(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64, const int32_t *colidx,
+                  const int32_t *new_id, const int32_t *order, void *new_rowptr, int32_t *new_colidx, void *ws,
+                  size_t ws_bytes, void *stream) {
+    int rc = check_graph(n, nnz, rowptr, colidx);
+    if (rc != EP_OK) return rc;
+    if (!new_id || !order || !new_rowptr || !aligned(new_rowptr, 8) || (nnz > 0 && !new_colidx)) return EP_EINVAL;
+    if (!rowptr_is_i64 && nnz >= ((int64_t)1 << 31)) return EP_EINVAL;
+    if (new_rowptr == rowptr || (nnz > 0 && new_colidx == colidx)) return EP_EINVAL;
+    if ((rc = check_ws(ws, ws_bytes, carve_reorder_ws(n, nnz, nullptr).bytes)) != EP_OK) return rc;
+    return launch_reorder(n, nnz, rowptr, rowptr_is_i64 != 0, colidx, new_id, order, new_rowptr, new_colidx,
+                          carve_reorder_ws(n, nnz, ws), static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, 
                                                            int64_t *__restrict__ stats) {
     if (!plan->active) return;   // uniform over the grid
     __shared__ long long cumf[256];
-    cumf[threadIdx.x] = threadIdx.x < k ? plan->cumf[threadIdx.x] : plan->F;
+    cumf[threadIdx.x] = (int)threadIdx.x < k ? plan->cumf[threadIdx.x] : plan->F;
     __syncthreads();
     const int64_t pos = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     int moved = 0;

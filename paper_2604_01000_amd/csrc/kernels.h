@@ -104,4 +104,16 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
                    double beta, uint64_t seed, int32_t max_rounds, int32_t *labels, int64_t *stats,
                    const BalanceWs &w, hipStream_t s);
 
+// ---- the graph under new vertex ids (reorder.hip) ----------------------------------------
+struct ReorderWs {
+    int64_t *block_sums;   // [ceil(n / 2048)] degree sums per workgroup, then their exclusive scan
+    int64_t *total;        // [1] sum of the degrees met through `order` (== nnz for a permutation)
+    int64_t *window_rows;  // [ceil(nnz / 4096) + 1] first row starting at or after every window boundary
+    size_t bytes;
+};
+ReorderWs carve_reorder_ws(int64_t n, int64_t nnz, void *ws);
+// new_rowptr / new_colidx: the CSR with row new_id[v] = neighbours of v under their new ids, ascending.
+int launch_reorder(int64_t n, int64_t nnz, const void *rowptr, bool i64, const int32_t *colidx, const int32_t *new_id,
+                   const int32_t *order, void *new_rowptr, int32_t *new_colidx, const ReorderWs &w, hipStream_t s);
+
 }  // namespace ep

@@ -27,7 +27,7 @@ SYMBOLS = (
     "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_sampled_workspace_bytes",
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
-    "balance_workspace_bytes", "partition_balance",
+    "balance_workspace_bytes", "partition_balance", "graph_reorder_workspace_bytes", "graph_reorder",
     "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.partition_balance.argtypes = [i64, i32, vp, C.c_int, vp, i32, C.c_double, C.c_uint64, i32, vp, vp, vp, sz, vp]
         L.edge_gap_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.vertex_bandwidth_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
+        L.graph_reorder_workspace_bytes.argtypes = [i64, i64, C.POINTER(sz)]
+        L.graph_reorder.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
         L.ep_bench_copy.argtypes = [vp, vp, sz, vp]
         for name in SYMBOLS:
@@ -214,6 +216,18 @@ def edge_gap_sum(n, nnz, rowptr, colidx, new_id, gap_sum, ws):
 def vertex_bandwidth_sum(n, nnz, rowptr, colidx, new_id, bw_sum, ws):
     _check(lib().vertex_bandwidth_sum(n, nnz, _ptr(rowptr), _is_i64(rowptr), _ptr(colidx), _ptr(new_id),
                                       _ptr(bw_sum), _ptr(ws), ws.numel(), _stream()), "vertex_bandwidth_sum")
+
+
+def graph_reorder_workspace_bytes(n: int, nnz: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().graph_reorder_workspace_bytes(n, nnz, C.byref(out)), "graph_reorder_workspace_bytes")
+    return out.value
+
+
+def graph_reorder(n, nnz, rowptr, colidx, new_id, order, new_rowptr, new_colidx, ws):
+    assert new_rowptr.dtype == rowptr.dtype
+    _check(lib().graph_reorder(n, nnz, _ptr(rowptr), _is_i64(rowptr), _ptr(colidx), _ptr(new_id), _ptr(order),
+                               _ptr(new_rowptr), _ptr(new_colidx), _ptr(ws), ws.numel(), _stream()), "graph_reorder")
 
 
 def ep_bench_copy(dst, src):

@@ -175,3 +175,12 @@ class Graph:
         ep.vertex_bandwidth_sum(self.n, self.nnz, self.rowptr, self.colidx, new_id, out, self.ws)
         torch.cuda.synchronize()
         return int(out.item()) & (2**64 - 1)
+
+    def reorder(self, new_id, order):
+        """(new_rowptr, new_colidx) as numpy; outputs are pre-filled so that unwritten entries show."""
+        new_rowptr = torch.full_like(self.rowptr, -7)
+        new_colidx = torch.full_like(self.colidx, -7)
+        ws = ep.workspace(ep.graph_reorder_workspace_bytes(self.n, self.nnz), DEV)
+        ep.graph_reorder(self.n, self.nnz, self.rowptr, self.colidx, new_id, order, new_rowptr, new_colidx, ws)
+        torch.cuda.synchronize()
+        return new_rowptr.cpu().numpy(), new_colidx.cpu().numpy()

@@ -176,3 +176,32 @@ def test_seeded_rows_match_the_oracle(seed, n, k):
 def test_seeded_rows_reject_k_above_n():
     with pytest.raises(ep.EmbedPartError):
         ep.kmeans_init_indices(0, 3, 4)
+
+
+def test_graph_reorder_rejects_bad_arguments():
+    L = ep.lib()
+    fake, fake2, ws = C.c_void_p(0x1000), C.c_void_p(0x2000), C.c_void_p(0x100000)
+    out = C.c_size_t(0)
+    assert L.graph_reorder_workspace_bytes(0, 10, C.byref(out)) == ep.EP_EINVAL
+    assert L.graph_reorder_workspace_bytes(10, -1, C.byref(out)) == ep.EP_EINVAL
+    assert L.graph_reorder_workspace_bytes(10, 10, None) == ep.EP_EINVAL
+    need = ep.graph_reorder_workspace_bytes(100_000, 5_000_000)
+    assert need >= 8 * (5_000_000 // 4096 + 100_000 // 2048) and need % 256 == 0
+    call = lambda **kw: L.graph_reorder(kw.get("n", 100_000), kw.get("nnz", 5_000_000), kw.get("rowptr", fake),
+                                        kw.get("i64", 0), kw.get("colidx", fake), kw.get("new_id", fake),
+                                        kw.get("order", fake), kw.get("new_rowptr", fake2),
+                                        kw.get("new_colidx", fake2), kw.get("ws", ws), kw.get("bytes", need), None)
+    assert call(n=0) == ep.EP_EINVAL
+    assert call(nnz=-1) == ep.EP_EINVAL
+    assert call(rowptr=None) == ep.EP_EINVAL
+    assert call(colidx=None) == ep.EP_EINVAL
+    assert call(colidx=C.c_void_p(0x1004)) == ep.EP_EINVAL              # 16-byte alignment of the column array
+    assert call(new_id=None) == ep.EP_EINVAL
+    assert call(order=None) == ep.EP_EINVAL
+    assert call(new_rowptr=None) == ep.EP_EINVAL
+    assert call(new_colidx=None) == ep.EP_EINVAL
+    assert call(new_rowptr=fake) == ep.EP_EINVAL                        # in place is not supported
+    assert call(new_colidx=fake) == ep.EP_EINVAL
+    assert call(nnz=1 << 31, bytes=1 << 40) == ep.EP_EINVAL             # 32-bit offsets cannot hold it
+    assert call(ws=None) == ep.EP_EWORKSPACE
+    assert call(bytes=need - 1) == ep.EP_EWORKSPACE
