@@ -10,10 +10,11 @@
 //      parallel).  A workgroup owns the rows that START in its window.  Every non-empty owned row
 //      marks its first position in LDS, a propagation of the marks (wave scans, no search) tells
 //      every position its row, and the entries are gathered position by position (reads of an old
-//      row stay coalesced), relabelled through new_id, as 64-bit keys (row in the window, new
-//      column).  A bitonic network sorts the keys, the low halves go back coalesced.  Rows of at
-//      most 4,096 entries end at most 4,096 positions past the window, so 8,192 keys (64 KB)
-//      always hold them.
+//      row stay coalesced) and relabelled through new_id.  Every row is then sorted by a bitonic
+//      network of its own in a padded power-of-two region of LDS, all rows of the window in the
+//      same sequence of steps (see "all short rows of a window sorted at once" below), and the
+//      columns go back coalesced.  Rows of at most 4,096 entries end at most 4,096 positions past
+//      the window, so 8,192 positions and fewer than 16,384 padded slots (64 KB) always hold them.
 //   3. A row longer than a window is necessarily the last row starting in its window (the next row
 //      starts past the window's end).  Its workgroup sorts it afterwards in place in global
 //      memory: tiles of 16,384 entries are sorted in LDS, merge steps whose partners are 16,384 or
@@ -35,8 +36,8 @@ constexpr int kScanPer = 8;                     // consecutive rows per thread i
 constexpr int kScanTile = kBlock * kScanPer;    // rows per workgroup
 constexpr int kScanTop = 1024;                  // threads of the kernel that scans the workgroup sums
 constexpr int kWin = 4096;                      // positions of new_colidx per window
-constexpr int kCap = 2 * kWin;                  // 64-bit keys in LDS
-constexpr int kTile32 = 2 * kCap;               // 32-bit keys in the same LDS (long rows)
+constexpr int kCap = 2 * kWin;                  // positions held in LDS
+constexpr int kTile32 = 2 * kCap;               // entries of a long row sorted in the same LDS at once
 
 template <typename RowT>
 __device__ __forceinline__ int64_t new_row_degree(int64_t n, const RowT *__restrict__ rowptr,
@@ -232,6 +233,99 @@ __device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v) {
     return v;
 }
 
+// ---- all short rows of a window sorted at once -------------------------------------------------
+// Every row gets a region of 2^p slots, p = ceil(log2(length)), filled up with +infinity.  The
+// regions are laid out by descending p, so every region is aligned to its own size and the slots
+// that still take part in the merges of 2^(lg+1) entries are a prefix: bound = first slot of the
+// classes p <= lg.  The network is then purely positional (no test per entry, no idle thread but in
+// the last iteration), LDS traffic follows sum 2^p p^2 over the rows, and the last three steps of
+// every merge (partners 4, 2, 1 apart) run in registers on 8 consecutive slots per thread.
+constexpr int kClasses = 13;                    // p = 0 .. 12 (rows of up to kWin = 2^12 entries)
+constexpr uint32_t kPadding = 0xFFFFFFFFu;
+
+__device__ __forceinline__ void order_if(bool on, uint32_t &a, uint32_t &b) {
+    const uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
+    a = on ? lo : a;
+    b = on ? hi : b;
+}
+
+// Merges of 2, 4 and 8 entries, whole, on 8 consecutive slots per thread.  end0 / end1 / end2: first
+// slot that takes no part in the merges of 2 / 4 / 8 (multiples of 2 / 4 / 8).
+__device__ __forceinline__ void sort_groups_of_8(uint32_t *pad, int end0, int end1, int end2) {
+    for (int g = threadIdx.x; 8 * g < end0; g += kBlock) {
+        uint4 a = reinterpret_cast<uint4 *>(pad)[2 * g], b = reinterpret_cast<uint4 *>(pad)[2 * g + 1];
+        const int at = 8 * g;
+        order_if(at + 2 <= end0, a.x, a.y); order_if(at + 4 <= end0, a.z, a.w);
+        order_if(at + 6 <= end0, b.x, b.y); order_if(at + 8 <= end0, b.z, b.w);
+        const bool a1 = at + 4 <= end1, b1 = at + 8 <= end1;
+        order_if(a1, a.x, a.w); order_if(a1, a.y, a.z); order_if(b1, b.x, b.w); order_if(b1, b.y, b.z);
+        order_if(a1, a.x, a.y); order_if(a1, a.z, a.w); order_if(b1, b.x, b.y); order_if(b1, b.z, b.w);
+        const bool c2 = at + 8 <= end2;
+        order_if(c2, a.x, b.w); order_if(c2, a.y, b.z); order_if(c2, a.z, b.y); order_if(c2, a.w, b.x);
+        order_if(c2, a.x, a.z); order_if(c2, a.y, a.w); order_if(c2, b.x, b.z); order_if(c2, b.y, b.w);
+        order_if(c2, a.x, a.y); order_if(c2, a.z, a.w); order_if(c2, b.x, b.y); order_if(c2, b.z, b.w);
+        reinterpret_cast<uint4 *>(pad)[2 * g] = a;
+        reinterpret_cast<uint4 *>(pad)[2 * g + 1] = b;
+    }
+    __syncthreads();
+}
+
+// Partners 4, 2 and 1 apart over the slots below `bound` (a multiple of 8).
+__device__ __forceinline__ void merge_tail_of_8(uint32_t *pad, int bound) {
+    for (int g = threadIdx.x; 8 * g < bound; g += kBlock) {
+        uint4 a = reinterpret_cast<uint4 *>(pad)[2 * g], b = reinterpret_cast<uint4 *>(pad)[2 * g + 1];
+        order_if(true, a.x, b.x); order_if(true, a.y, b.y); order_if(true, a.z, b.z); order_if(true, a.w, b.w);
+        order_if(true, a.x, a.z); order_if(true, a.y, a.w); order_if(true, b.x, b.z); order_if(true, b.y, b.w);
+        order_if(true, a.x, a.y); order_if(true, a.z, a.w); order_if(true, b.x, b.y); order_if(true, b.z, b.w);
+        reinterpret_cast<uint4 *>(pad)[2 * g] = a;
+        reinterpret_cast<uint4 *>(pad)[2 * g + 1] = b;
+    }
+    __syncthreads();
+}
+
+// One positional step over the pairs below bound / 2; four pairs of a thread are read before the
+// first is written.  mirror: the step that opens a merge of 2 * half entries (partner = mirror
+// image); otherwise partners are `stride` apart.
+template <bool MIRROR>
+__device__ __forceinline__ void positional_step(uint32_t *pad, int bound, int lg, int stride) {
+    constexpr int kAtOnce = 4;
+    const int pairs = bound >> 1;
+    for (int t0 = threadIdx.x; t0 < pairs; t0 += kAtOnce * kBlock) {
+        int lo[kAtOnce], hi[kAtOnce];
+        uint32_t x[kAtOnce], y[kAtOnce];
+#pragma unroll
+        for (int e = 0; e < kAtOnce; ++e) {
+            const int t = min(t0 + e * kBlock, pairs - 1);          // a repeated pair is harmless: same values
+            if (MIRROR) {
+                const int half = 1 << lg, blk = t >> lg, off = t & (half - 1);
+                lo[e] = (blk << (lg + 1)) + off;
+                hi[e] = (blk << (lg + 1)) + 2 * half - 1 - off;
+            } else {
+                lo[e] = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                hi[e] = lo[e] + stride;
+            }
+            x[e] = pad[lo[e]];
+            y[e] = pad[hi[e]];
+        }
+#pragma unroll
+        for (int e = 0; e < kAtOnce; ++e)
+            if (y[e] < x[e]) { pad[lo[e]] = y[e]; pad[hi[e]] = x[e]; }
+    }
+    __syncthreads();
+}
+
+// class_base[p]: first slot of the rows of class p (classes laid out from kClasses - 1 down to 0);
+// classes: the number of classes in use (largest p + 1).
+__device__ __forceinline__ void sort_regions(uint32_t *pad, const int *class_base, int classes) {
+    sort_groups_of_8(pad, class_base[0], classes > 1 ? class_base[1] : 0, classes > 2 ? class_base[2] : 0);
+    for (int lg = 3; lg < classes - 1; ++lg) {          // merges of 2^(lg+1) entries: classes above lg
+        const int bound = class_base[lg];
+        positional_step<true>(pad, bound, lg, 0);
+        for (int stride = (1 << lg) >> 1; stride >= 8; stride >>= 1) positional_step<false>(pad, bound, lg, stride);
+        merge_tail_of_8(pad, bound);
+    }
+}
+
 template <typename RowT>
 __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t nnz, const RowT *__restrict__ rowptr,
                                                                const int32_t *__restrict__ colidx,
@@ -241,13 +335,14 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
                                                                const int64_t *__restrict__ total,
                                                                const int64_t *__restrict__ window_rows,
                                                                int32_t *__restrict__ new_colidx) {
-    constexpr int kChunks = kCap / kWave;
-    __shared__ uint64_t keys[kCap];
+    constexpr int kChunks = kCap / kWave, kPer = kCap / kBlock, kWaves = kBlock / kWave, kGroup = 16;
+    __shared__ __attribute__((aligned(16))) uint32_t lds[2 * kCap];   // marks | regions of the rows, then the padded slots
     __shared__ uint32_t chunk_mark[kChunks];       // largest mark of a chunk of 64 positions, then the carry into it
     __shared__ int64_t plan[2];
+    __shared__ int class_count[kClasses], class_base[kClasses + 1];
     // `order` was not a permutation of the rows: the row starts do not add up, nothing is written.
     if (*total != nnz) return;
-    uint32_t *mark = reinterpret_cast<uint32_t *>(keys) + 1;     // high word of key i: mark[2 * i]
+    uint32_t *mark = lds, *region = lds + kCap;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t r0 = window_rows[blockIdx.x], r1 = window_rows[blockIdx.x + 1];
     const int64_t s0 = (int64_t)new_rowptr[r0], s1 = (int64_t)new_rowptr[r1];
@@ -256,16 +351,22 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
         return (uint32_t)col < (uint64_t)n ? (uint32_t)new_id[col] : (uint32_t)col;
     };
 
-    // Marks: the first position of every owned row of at most kWin entries gets (row - r0 + 1).
-    // A longer row can only be the last owned one; it is set aside.
+    // Marks: the first position of every owned row of at most kWin entries gets (row - r0 + 1), and
+    // the row takes the next region of its class.  A longer row can only be the last owned one; it
+    // is set aside.
     const int span = (int)std::min<int64_t>(kCap, s1 - s0);
-    for (int i = threadIdx.x; i < span; i += kBlock) mark[2 * i] = 0;
+    for (int i = threadIdx.x; i < span; i += kBlock) mark[i] = 0;
+    if (threadIdx.x < kClasses) class_count[threadIdx.x] = 0;
     if (threadIdx.x == 0) { plan[0] = s1; plan[1] = -1; }
     __syncthreads();
     for (int64_t r = r0 + threadIdx.x; r < r1; r += kBlock) {
         const int64_t st = (int64_t)new_rowptr[r], en = (int64_t)new_rowptr[r + 1];
         if (en - st > kWin) { plan[0] = st; plan[1] = r; }
-        else if (en > st && st - s0 < span) mark[2 * (st - s0)] = (uint32_t)(r - r0 + 1);
+        else if (en > st && st - s0 < span) {
+            const int len = (int)(en - st), p = len <= 1 ? 0 : 32 - __builtin_clz(len - 1);
+            mark[st - s0] = (uint32_t)(r - r0 + 1);
+            region[st - s0] = (uint32_t)p << 16 | (uint32_t)atomicAdd(&class_count[p], 1);
+        }
     }
     __syncthreads();
     const int64_t short_end = plan[0], long_row = plan[1];
@@ -273,10 +374,16 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
     if (cnt64 > span) return;                       // cannot happen with monotone row starts
     const int cnt = (int)cnt64;
     if (cnt > 0) {
+        if (threadIdx.x == 0) {
+            int at = 0;
+            for (int p = kClasses - 1; p >= 0; --p) { class_base[p] = at; at += class_count[p] << p; }
+            class_base[kClasses] = at;               // slots in use: less than 2 * cnt
+        }
+        // Every position learns its row: the marks are propagated forward (they grow with the position).
         const int chunks = (cnt + kWave - 1) / kWave;
-        for (int c = wave; c < chunks; c += kBlock / kWave) {
+        for (int c = wave; c < chunks; c += kWaves) {
             const int i = c * kWave + lane;
-            const uint32_t m = wave_inclusive_max(i < cnt ? mark[2 * i] : 0u);
+            const uint32_t m = wave_inclusive_max(i < cnt ? mark[i] : 0u);
             if (lane == kWave - 1) chunk_mark[c] = m;
         }
         __syncthreads();
@@ -294,20 +401,67 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
             }
         }
         __syncthreads();
-        for (int c = wave; c < chunks; c += kBlock / kWave) {
-            const int i = c * kWave + lane;
-            uint32_t m = wave_inclusive_max(i < cnt ? mark[2 * i] : 0u);
-            m = m > chunk_mark[c] ? m : chunk_mark[c];
-            if (i < cnt && m > 0) {                  // m > 0 always: position 0 is the start of a row
-                const int64_t r = r0 + (int64_t)m - 1;
-                const int32_t v = order[r];
-                const int64_t j = s0 + i - (int64_t)new_rowptr[r];
-                keys[i] = ((uint64_t)(m - 1) << 32) | relabel(colidx[(int64_t)rowptr[v] + j]);
+        // Gather.  The chain position -> row -> old row -> old entry -> new id is four dependent loads;
+        // each link is issued for kGroup positions of the thread at once so that their latencies overlap.
+        uint32_t renamed[kPer];
+        int slot[kPer];                              // where the entry waits in the padded layout, -1: none
+#pragma unroll
+        for (int g = 0; g < kPer; g += kGroup) {
+            uint32_t m[kGroup];
+#pragma unroll
+            for (int e = 0; e < kGroup; ++e) {       // position i = threadIdx.x + kBlock * j lies in chunk wave + kWaves * j
+                const int c = wave + kWaves * (g + e), i = c * kWave + lane;
+                m[e] = 0;
+                if (c < chunks) {                    // uniform over the wave
+                    const uint32_t own = wave_inclusive_max(i < cnt ? mark[i] : 0u);
+                    m[e] = i < cnt ? (own > chunk_mark[c] ? own : chunk_mark[c]) : 0u;
+                }
+            }
+            int32_t v[kGroup];
+            int64_t first[kGroup];
+#pragma unroll
+            for (int e = 0; e < kGroup; ++e) {       // m > 0 wherever i < cnt: position 0 is the start of a row
+                const int64_t r = r0 + (m[e] > 0 ? (int64_t)m[e] - 1 : 0);
+                v[e] = order[r];
+                first[e] = (int64_t)new_rowptr[r];
+            }
+            int64_t from[kGroup];
+#pragma unroll
+            for (int e = 0; e < kGroup; ++e) {
+                const int i = threadIdx.x + kBlock * (g + e);
+                from[e] = m[e] > 0 ? (int64_t)rowptr[v[e]] + (s0 + i - first[e]) : 0;
+            }
+            int32_t col[kGroup];
+#pragma unroll
+            for (int e = 0; e < kGroup; ++e) col[e] = colidx[from[e]];
+#pragma unroll
+            for (int e = 0; e < kGroup; ++e) {
+                const int i = threadIdx.x + kBlock * (g + e);
+                renamed[g + e] = relabel(col[e]);
+                slot[g + e] = -1;
+                if (m[e] > 0) {
+                    const int start = (int)(first[e] - s0);
+                    const uint32_t reg = region[start];
+                    const int p = (int)(reg >> 16);
+                    slot[g + e] = class_base[p] + ((int)(reg & 0xFFFF) << p) + (i - start);
+                }
             }
         }
+        __syncthreads();                             // marks and regions are not read any more
+        uint32_t *pad = lds;
+        const int slots = class_base[kClasses];
+        int classes = kClasses;
+        while (classes > 1 && class_count[classes - 1] == 0) --classes;   // uniform
+        for (int i = threadIdx.x; i < (slots + 7) / 8 * 8; i += kBlock) pad[i] = kPadding;
         __syncthreads();
-        lds_bitonic_sort(keys, cnt);
-        for (int i = threadIdx.x; i < cnt; i += kBlock) new_colidx[s0 + i] = (int32_t)(uint32_t)keys[i];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (slot[j] >= 0) pad[slot[j]] = renamed[j];
+        __syncthreads();
+        sort_regions(pad, class_base, classes);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (slot[j] >= 0) new_colidx[s0 + threadIdx.x + kBlock * j] = (int32_t)pad[slot[j]];
     }
     if (long_row >= 0) {                             // uniform over the workgroup
         __syncthreads();
@@ -317,7 +471,7 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
         uint32_t *dst = reinterpret_cast<uint32_t *>(new_colidx + short_end);
         for (int64_t j = threadIdx.x; j < len; j += kBlock) dst[j] = relabel(src[j]);
         __syncthreads();
-        sort_long_row(dst, len, reinterpret_cast<uint32_t *>(keys));
+        sort_long_row(dst, len, lds);
     }
 }
 
