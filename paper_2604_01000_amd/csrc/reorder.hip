@@ -223,13 +223,17 @@ __global__ __launch_bounds__(kBlock) void reorder_window_rows_kernel(int64_t n, 
     window_rows[b] = pos >= nnz ? n : first_row_at_or_after(new_rowptr, n, pos);
 }
 
+// Inclusive running maximum over the 64 lanes, on the data-parallel-primitive paths (no LDS):
+// shifts by 1, 2, 4, 8 inside rows of 16 lanes, then the last lane of row 0 / 2 into rows 1 / 3 and
+// the last lane of row 1 into rows 2 and 3.  Lanes without a source see 0 (the values are unsigned).
 __device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int step = 1; step < kWave; step <<= 1) {
-        const uint32_t other = (uint32_t)__shfl_up((int)v, step, kWave);
-        if (lane >= step) v = other > v ? other : v;
-    }
+    auto fold = [&](uint32_t other) { v = other > v ? other : v; };
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true));    // row_shr:1
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true));    // row_shr:2
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true));    // row_shr:4
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true));    // row_shr:8
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false));   // row_bcast:15 into rows 1, 3
+    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false));   // row_bcast:31 into rows 2, 3
     return v;
 }
 
@@ -335,7 +339,7 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
                                                                const int64_t *__restrict__ total,
                                                                const int64_t *__restrict__ window_rows,
                                                                int32_t *__restrict__ new_colidx) {
-    constexpr int kChunks = kCap / kWave, kPer = kCap / kBlock, kWaves = kBlock / kWave, kGroup = 16;
+    constexpr int kChunks = kCap / kWave, kPer = kCap / kBlock, kWaves = kBlock / kWave, kGroup = 32;
     __shared__ __attribute__((aligned(16))) uint32_t lds[2 * kCap];   // marks | regions of the rows, then the padded slots
     __shared__ uint32_t chunk_mark[kChunks];       // largest mark of a chunk of 64 positions, then the carry into it
     __shared__ int64_t plan[2];
@@ -380,11 +384,17 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
             class_base[kClasses] = at;               // slots in use: less than 2 * cnt
         }
         // Every position learns its row: the marks are propagated forward (they grow with the position).
+        // Position i = threadIdx.x + kBlock * j lies in chunk wave + kWaves * j of 64 positions.
         const int chunks = (cnt + kWave - 1) / kWave;
-        for (int c = wave; c < chunks; c += kWaves) {
-            const int i = c * kWave + lane;
-            const uint32_t m = wave_inclusive_max(i < cnt ? mark[i] : 0u);
-            if (lane == kWave - 1) chunk_mark[c] = m;
+        uint32_t own[kPer];                          // running maximum inside the chunk
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int c = wave + kWaves * j, i = c * kWave + lane;
+            own[j] = 0;
+            if (c < chunks) {                        // uniform over the wave
+                own[j] = wave_inclusive_max(i < cnt ? mark[i] : 0u);
+                if (lane == kWave - 1) chunk_mark[c] = own[j];
+            }
         }
         __syncthreads();
         if (wave == 0) {                            // carry into chunk c = the largest mark before it
@@ -409,13 +419,10 @@ __global__ __launch_bounds__(kBlock) void reorder_rows_kernel(int64_t n, int64_t
         for (int g = 0; g < kPer; g += kGroup) {
             uint32_t m[kGroup];
 #pragma unroll
-            for (int e = 0; e < kGroup; ++e) {       // position i = threadIdx.x + kBlock * j lies in chunk wave + kWaves * j
+            for (int e = 0; e < kGroup; ++e) {
                 const int c = wave + kWaves * (g + e), i = c * kWave + lane;
                 m[e] = 0;
-                if (c < chunks) {                    // uniform over the wave
-                    const uint32_t own = wave_inclusive_max(i < cnt ? mark[i] : 0u);
-                    m[e] = i < cnt ? (own > chunk_mark[c] ? own : chunk_mark[c]) : 0u;
-                }
+                if (i < cnt) m[e] = own[g + e] > chunk_mark[c] ? own[g + e] : chunk_mark[c];
             }
             int32_t v[kGroup];
             int64_t first[kGroup];
