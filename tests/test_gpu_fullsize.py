@@ -64,7 +64,45 @@ def _graph_check(w, labels_np, k, reorder=False):
         np.testing.assert_array_equal(order.cpu().numpy(), order_or)
         assert gr.gap_sum(new_id) == oracle.edge_gap_sum(gr.rp_np, gr.ci_np, new_or)
         assert gr.gap_sum(None) == oracle.edge_gap_sum(gr.rp_np, gr.ci_np)
+        nrp, nci = gr.reorder(new_id, order)                 # the graph rewritten under pi, in full
+        nrp_or, nci_or = oracle.reorder_csr(gr.rp_np, gr.ci_np, new_or)
+        np.testing.assert_array_equal(nrp, nrp_or)
+        np.testing.assert_array_equal(nci, nci_or)
     return cut_or / max(gr.nnz, 1)
+
+
+def _entry_hash(rows, cols):
+    """Order-free 64-bit fingerprint of a multiset of (row, column) pairs (int64 arithmetic wraps)."""
+    h = (rows.to(torch.int64) * 1_000_003 + cols.to(torch.int64)) * -7046029254386353131
+    return int((h ^ (h >> 29)).sum().item())
+
+
+def _reorder_property_check(w, labels_np, k):
+    """graph_reorder where the oracle cannot follow (1.6e9 entries): row starts against a prefix sum by
+    the tensor library, every row ascending, the multiset of (row, column) pairs equal to the relabelled
+    input, and the gap / bandwidth sums carried over."""
+    rowptr, colidx, _ = synth.sbm_graph(w, DEV)
+    gr = Graph(rowptr, colidx, k_max=k)
+    new_id, order = gr.permutation(torch.from_numpy(labels_np).to(DEV), k)
+    new_rowptr, new_colidx = torch.full_like(rowptr, -7), torch.full_like(colidx, -7)
+    ws = ep.workspace(ep.graph_reorder_workspace_bytes(gr.n, gr.nnz), DEV)
+    ep.graph_reorder(gr.n, gr.nnz, gr.rowptr, gr.colidx, new_id, order, new_rowptr, new_colidx, ws)
+    torch.cuda.synchronize()
+    deg = rowptr[1:] - rowptr[:-1]
+    deg_new = deg[order.long()]
+    assert new_rowptr[0].item() == 0
+    assert torch.equal(new_rowptr[1:], torch.cumsum(deg_new, 0).to(rowptr.dtype))
+    starts = torch.zeros(gr.nnz + 1, dtype=torch.bool, device=DEV)
+    starts[new_rowptr[:-1][deg_new > 0].long()] = True
+    assert bool(((new_colidx[1:] >= new_colidx[:-1]) | starts[1:-1]).all())
+    del starts
+    ids = torch.arange(gr.n, dtype=torch.int32, device=DEV)
+    want = _entry_hash(torch.repeat_interleave(new_id, deg), new_id[colidx.long()])
+    got = _entry_hash(torch.repeat_interleave(ids, deg_new), new_colidx)
+    assert got == want
+    g2 = Graph(new_rowptr, new_colidx, k_max=k)
+    assert g2.gap_sum(None) == gr.gap_sum(new_id)
+    assert g2.bandwidth_sum(None) == gr.bandwidth_sum(new_id)
 
 
 def test_products_like_full():
@@ -128,6 +166,7 @@ def test_papers_like_full():
     torch.cuda.empty_cache()
     ecr = _graph_check(w, labels_np, w.k)
     print(f"papers_like: edge-cut ratio {ecr:.4f}")
+    _reorder_property_check(w, labels_np, w.k)
 
 
 def test_maximum_k_and_maximum_d():
