@@ -44,6 +44,7 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;
@@ -159,9 +160,12 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 }
 
 // XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
-template <int D, int KT, int MODE, bool XSQ, bool STREAM>
+// XT: element type of X.  bfloat16 rows are widened to fp32 as they arrive (exact) and the centroids
+// are rounded to bfloat16 for the scores (the reading taken for bfloat16 embeddings: see
+// large_assign_kernel); sums and means use the data in full precision.
+template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT>
 __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
-    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const float *__restrict__ X,
+    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
     int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part) {
@@ -172,6 +176,8 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
     // spend k/16 times the work of the scores on mostly-zero one-hot products, so every wave keeps
     // its own padded k x d table of sums in LDS and adds rows to it (see add_rows_to_lds_sums).
     constexpr bool kLdsSums = KT >= 2;
+    constexpr bool kBf16 = !std::is_same<XT, float>::value;
+    constexpr int kElem = (int)sizeof(XT);
     constexpr int kFlush = SmallLds<D, KT>::kFlush;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
     float *lds = reinterpret_cast<float *>(dyn_lds);                       // transposition tiles | per-wave sums
@@ -217,6 +223,10 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
                 for (int j = 0; j < NJ; ++j) {
                     f32x4 v = {0.f, 0.f, 0.f, 0.f};
                     if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
+                    if constexpr (kBf16) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = bf16_to_f32(f32_to_bf16_rne(v[e]));
+                    }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) nacc = fma((double)v[e], (double)v[e], nacc);
                     if constexpr (kSplit) {
@@ -277,8 +287,8 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
     constexpr bool kPointPerLane = MODE != kUpdateOnly || KT >= 2;
     int voff[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) voff[r] = (int)(((4 * g + r) * ld + 4 * c) * 4);
-    const int voff_a = (int)((c * ld + 4 * g) * 4);
+    for (int r = 0; r < 4; ++r) voff[r] = (int)(((4 * g + r) * ld + 4 * c) * kElem);
+    const int voff_a = (int)((c * ld + 4 * g) * kElem);
 
     auto load_subtile = [&](int64_t st, f32x4(&dst)[NX]) {
         // A sub-tile past this workgroup's range gets an empty descriptor: the loads are still
@@ -287,19 +297,27 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
         const bool live = st < last;
         const int64_t row0 = live ? st * kSub : 0;
         const int rows_here = (int)min((int64_t)kSub, n - row0);
-        const int bytes = live ? (int)(((rows_here - 1) * ld + D) * 4) : 0;
+        const int bytes = live ? (int)(((rows_here - 1) * ld + D) * kElem) : 0;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(X + row0 * ld), 0, bytes, 0x00020000);
+            const_cast<XT *>(X + row0 * ld), 0, bytes, 0x00020000);
         // STREAM: a matrix larger than the last-level cache is read with the non-temporal hint (it
         // cannot be there again next round, and the hint buys ~2% of stream rate); a smaller one is
         // left to the caches, which serve it in the later rounds.
         constexpr int kAux = STREAM ? 2 : 0;
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
-            const u32x4 raw = kPointPerLane
-                                  ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, kAux)
-                                  : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), kAux);
-            dst[q] = __builtin_bit_cast(f32x4, raw);
+            if constexpr (kBf16) {   // the same four columns per piece, 8 bytes of them
+                const u32x2 raw = kPointPerLane
+                                      ? __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff_a, 32 * q, kAux)
+                                      : __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff[q / NH], 128 * (q % NH), kAux);
+                dst[q] = f32x4{__uint_as_float(raw[0] << 16), __uint_as_float(raw[0] & 0xffff0000u),
+                               __uint_as_float(raw[1] << 16), __uint_as_float(raw[1] & 0xffff0000u)};
+            } else {
+                const u32x4 raw = kPointPerLane
+                                      ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, kAux)
+                                      : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), kAux);
+                dst[q] = __builtin_bit_cast(f32x4, raw);
+            }
         }
     };
 
@@ -852,35 +870,42 @@ double *xsq_part_of(const KmeansWs &w) { return w.obj_part + kSmallMaxBlocks; }
 double *xsq_total_of(const KmeansWs &w) { return w.obj_part + 2 * kSmallMaxBlocks; }
 
 template <int MODE, bool XSQ>
-int launch_mode(const ep_problem &p, const float *X, const float *C, const KmeansWs &w, int32_t *labels_out,
+int launch_mode(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels_out,
                 const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
-    const bool stream_x = (double)p.n * (double)p.ld * 4.0 > kLastLevelCacheBytes;
+    const bool bf16 = p.dtype == EP_BF16;
+    const bool stream_x = (double)p.n * (double)p.ld * (bf16 ? 2.0 : 4.0) > kLastLevelCacheBytes;
     double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s, true);
-#define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
+#define EP_SMALL_LAUNCH_T(D_, KT_, XT_)                                                                       \
     do {                                                                                                      \
         constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
-        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true>                                   \
-                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false>;                                 \
+        const XT_ *Xt = static_cast<const XT_ *>(X);                                                          \
+        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_>                              \
+                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_>;                            \
         if (lds_bytes > 64 * 1024)                                                                            \
             EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
         if (prof.start_)   /* timed launch: the events get the kernel's own begin and end */                \
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
-                                  p.n, p.ld, p.k, geo.subtiles_per_wave, X, C, labels_out, labels_in, min_d2,  \
+                                  p.n, p.ld, p.k, geo.subtiles_per_wave, Xt, C, labels_out, labels_in, min_d2, \
                                   w.psum, w.pcnt, sp, xsq_part_of(w));                                        \
         else                                                                                                  \
-            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, X, C,          \
+            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, Xt, C,         \
                                                        labels_out, labels_in, min_d2, w.psum, w.pcnt, sp,    \
                                                        xsq_part_of(w));                                       \
+    } while (0)
+#define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
+    do {                                                                                                      \
+        if (bf16) EP_SMALL_LAUNCH_T(D_, KT_, bf16_t); else EP_SMALL_LAUNCH_T(D_, KT_, float);                 \
     } while (0)
     if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
     } else {
         if (kt == 1) EP_SMALL_LAUNCH(64, 1); else if (kt == 2) EP_SMALL_LAUNCH(64, 2); else EP_SMALL_LAUNCH(64, 4);
     }
+#undef EP_SMALL_LAUNCH_T
 #undef EP_SMALL_LAUNCH
     EP_LAUNCH_CHECK();
     return EP_OK;
@@ -889,16 +914,16 @@ int launch_mode(const ep_problem &p, const float *X, const float *C, const Kmean
 }  // namespace
 
 bool small_path_supported(const ep_problem &p) {
-    return p.dtype == EP_F32 && (p.d == 64 || p.d == 128) && p.k <= 64 && p.ld < ((int64_t)1 << 24);
+    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && (p.d == 64 || p.d == 128) && p.k <= 64 &&
+           p.ld < ((int64_t)1 << 24);
 }
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }
 
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s) {
-    const float *Xf = static_cast<const float *>(X);
-    int rc = objective ? launch_mode<kAssignOnly, true>(p, Xf, C, w, labels, nullptr, min_d2, true, s)
-                       : launch_mode<kAssignOnly, false>(p, Xf, C, w, labels, nullptr, min_d2, false, s);
+    int rc = objective ? launch_mode<kAssignOnly, true>(p, X, C, w, labels, nullptr, min_d2, true, s)
+                       : launch_mode<kAssignOnly, false>(p, X, C, w, labels, nullptr, min_d2, false, s);
     if (rc != EP_OK) return rc;
     if (objective) {
         sum_obj_kernel<<<1, 64, 0, s>>>(s_part_of(w), xsq_part_of(w), small_blocks(p), xsq_total_of(w), objective);
@@ -919,18 +944,16 @@ static int launch_small_finalize(const ep_problem &p, const float *C_prev, float
 
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
-    int rc = launch_mode<kUpdateOnly, false>(p, static_cast<const float *>(X), nullptr, w, nullptr, labels, nullptr,
-                                             false, s);
+    int rc = launch_mode<kUpdateOnly, false>(p, X, nullptr, w, nullptr, labels, nullptr, false, s);
     if (rc != EP_OK) return rc;
     return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, s);
 }
 
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
                        int64_t *counts, double *objective, bool first_round, hipStream_t s) {
-    const float *Xf = static_cast<const float *>(X);
     const bool fresh = objective && first_round;  // sum ||x||^2 is computed in the first round and kept
-    int rc = fresh ? launch_mode<kFused, true>(p, Xf, C, w, labels, nullptr, nullptr, true, s)
-                   : launch_mode<kFused, false>(p, Xf, C, w, labels, nullptr, nullptr, objective != nullptr, s);
+    int rc = fresh ? launch_mode<kFused, true>(p, X, C, w, labels, nullptr, nullptr, true, s)
+                   : launch_mode<kFused, false>(p, X, C, w, labels, nullptr, nullptr, objective != nullptr, s);
     if (rc != EP_OK) return rc;
     return launch_small_finalize(p, C, C, counts, w, objective, fresh, s);
 }

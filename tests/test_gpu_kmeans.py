@@ -65,6 +65,11 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (2049, 64, 33, True, torch.bfloat16, 72),
     (6000, 128, 1024, True, torch.bfloat16, None),
     (5000, 64, 200, True, torch.bfloat16, None),     # matrix-core path at d = 64
+    (1037, 64, 4, False, torch.bfloat16, None),      # bfloat16 rows on the small-k kernels: one centroid tile,
+    (7777, 128, 16, True, torch.bfloat16, 136),      # padded rows,
+    (3001, 128, 30, True, torch.bfloat16, None),     # two tiles,
+    (2999, 64, 24, True, torch.bfloat16, None),
+    (4099, 128, 64, True, torch.bfloat16, None),     # four tiles (pipelined fused round)
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -140,6 +145,8 @@ def test_run_matches_oracle_full_size(name):
                                                (12_345, 128, 700, torch.bfloat16, 4),
                                                (6_007, 128, 24, torch.float32, 6), (6_011, 64, 40, torch.float32, 6),
                                                (8_009, 64, 300, torch.bfloat16, 4),
+                                               (20_011, 128, 16, torch.bfloat16, 8), (9_000, 128, 64, torch.bfloat16, 6),
+                                               (6_011, 64, 40, torch.bfloat16, 6), (6_007, 128, 24, torch.bfloat16, 6),
                                                (5_000, 48, 6, torch.float32, 10)])
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
