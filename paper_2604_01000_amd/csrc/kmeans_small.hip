@@ -209,7 +209,11 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
     constexpr bool kSplit = KT >= 2;
     constexpr int KS = D / 32;       // K-steps of the bf16 instruction
     f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
-    u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kSplit ? KT : 1][kSplit ? KS : 1], cl[kSplit ? KT : 1][kSplit ? KS : 1];
+    // bfloat16 data: x is its own high term and the rounded centroid has no lower terms either, so of
+    // the six products only xh.ch is left and cm, cl are not kept.
+    constexpr bool kThreeTerms = kSplit && !kBf16;
+    u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kThreeTerms ? KT : 1][kThreeTerms ? KS : 1],
+        cl[kThreeTerms ? KT : 1][kThreeTerms ? KS : 1];
     float hn[KT];   // -||c||^2 / 2 of centroid 16*mt + c: the value the score accumulators start from
     // Called after the first sub-tile's loads have been issued, so that the two latencies overlap.
     auto load_centroids = [&]() {
@@ -232,8 +236,11 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
                     if constexpr (kSplit) {
                         const int s = j >> 1, w = 2 * (j & 1);
                         const Split3 lo = split3_pair(v[0], v[1]), hi = split3_pair(v[2], v[3]);
-                        ch[mt][s][w] = lo.h, cm[mt][s][w] = lo.m, cl[mt][s][w] = lo.l;
-                        ch[mt][s][w + 1] = hi.h, cm[mt][s][w + 1] = hi.m, cl[mt][s][w + 1] = hi.l;
+                        ch[mt][s][w] = lo.h, ch[mt][s][w + 1] = hi.h;
+                        if constexpr (kThreeTerms) {
+                            cm[mt][s][w] = lo.m, cl[mt][s][w] = lo.l;
+                            cm[mt][s][w + 1] = hi.m, cl[mt][s][w + 1] = hi.l;
+                        }
                     } else {
                         creg[mt][j] = v;
                     }
@@ -254,8 +261,10 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
 #pragma unroll
                     for (int s = 0; s < KS; ++s) {
                         asm volatile("" : "+a"(ch[mt][s]));
-                        asm volatile("" : "+a"(cm[mt][s]));
-                        asm volatile("" : "+a"(cl[mt][s]));
+                        if constexpr (kThreeTerms) {
+                            asm volatile("" : "+a"(cm[mt][s]));
+                            asm volatile("" : "+a"(cl[mt][s]));
+                        }
                     }
             }
         }
@@ -354,7 +363,23 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
         const Split3 t = split3_pair(v[2 * (pr & 1)], v[2 * (pr & 1) + 1]);
         xh[s & 1][pr] = t.h, xm[s & 1][pr] = t.m, xl[s & 1][pr] = t.l;
     };
+    constexpr int kScoreGroups = kThreeTerms ? 6 * KS : KS;   // groups of KT matrix instructions per sub-tile
     auto split_scores = [&](const f32x4(&x)[NX], f32x4(&acc)[KT], auto &&after_group) {
+        if constexpr (!kThreeTerms) {   // widened bfloat16: the operand is the upper halves, packed again
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u32x4 a;
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    const f32x4 &v = x[2 * s + (pr >> 1)];
+                    a[pr] = (__float_as_uint(v[2 * (pr & 1) + 1]) & 0xffff0000u) | (__float_as_uint(v[2 * (pr & 1)]) >> 16);
+                }
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) acc[mt] = mfma_bf16_k32(a, ch[mt][s], acc[mt]);
+                after_group(s);
+            }
+            return;
+        }
 #pragma unroll
         for (int pr = 0; pr < 4; ++pr) split_x(x, 0, pr);
 #pragma unroll
@@ -526,7 +551,7 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
         constexpr int kFixedRounds = D >= 128 ? 3 : 2;   // these ranks without branches; higher ranks (rare) in a loop
         constexpr int kFirstAdd = 7;                       // items 0 .. 6: arg-max (4), labels, rank (2)
         constexpr int kItems = kFirstAdd + kFixedRounds * NJ;
-        constexpr int kGroups = 6 * KS;
+        constexpr int kGroups = kScoreGroups;
         __shared__ __attribute__((aligned(16))) int32_t scrap[4 * kBlock];   // 16 bytes per lane, written by idle lanes, never read
         float *dummy = wsums + 16 * KT * STRIDE + 4 * g;   // the extra row idle lanes add to; never read
         f32x4 scp[KT];         // previous sub-tile: scores
