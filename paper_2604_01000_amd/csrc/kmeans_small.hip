@@ -165,7 +165,8 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 // large_assign_kernel); sums and means use the data in full precision.
 template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT>
 __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
-    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, const XT *__restrict__ X,
+    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, int64_t waves_with_one_more,
+    const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
     int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part) {
@@ -282,8 +283,10 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
 
     // Every wave owns a contiguous range of sub-tiles (a fixed function of n and the grid).
     const int64_t total_sub = (n + kSub - 1) / kSub;
-    const int64_t first = ((int64_t)blockIdx.x * kWaves + wave) * subtiles_per_wave;
-    const int64_t last = min(total_sub, first + subtiles_per_wave);
+    // (the first waves_with_one_more waves of the grid take one sub-tile more than the others)
+    const int64_t wave_id = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t first = wave_id * subtiles_per_wave + min(wave_id, waves_with_one_more);
+    const int64_t last = min(total_sub, first + subtiles_per_wave + (wave_id < waves_with_one_more ? 1 : 0));
 
     // Rows are read with buffer loads: the descriptor is rebuilt per sub-tile from a scalar base
     // and covers exactly the sub-tile's valid bytes, so lanes that would read past the last row
@@ -879,14 +882,15 @@ __global__ __launch_bounds__(64) void sum_obj_kernel(const double *__restrict__ 
 
 struct Geometry {
     int blocks;
-    int64_t subtiles_per_wave;
+    int64_t subtiles_per_wave;      // every wave takes this many sub-tiles,
+    int64_t waves_with_one_more;    // and the first so many waves one more
 };
 
 Geometry geometry(int64_t n) {
     const int64_t total_sub = ceil_div(n, kSub);
     const int64_t wgs = std::min<int64_t>(kSmallMaxBlocks, ceil_div(total_sub, kWaves));
-    const int64_t per_wave = ceil_div(total_sub, wgs * kWaves);
-    return Geometry{(int)ceil_div(total_sub, per_wave * kWaves), per_wave};
+    const int64_t waves = wgs * kWaves;
+    return Geometry{(int)wgs, total_sub / waves, total_sub % waves};
 }
 
 // Workspace slots inside KmeansWs::obj_part (kObjBlocksMax doubles).
@@ -914,12 +918,13 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
         if (prof.start_)   /* timed launch: the events get the kernel's own begin and end */                \
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
-                                  p.n, p.ld, p.k, geo.subtiles_per_wave, Xt, C, labels_out, labels_in, min_d2, \
+                                  p.n, p.ld, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,       \
+                                  labels_out, labels_in, min_d2,                                              \
                                   w.psum, w.pcnt, sp, xsq_part_of(w));                                        \
         else                                                                                                  \
-            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave, Xt, C,         \
-                                                       labels_out, labels_in, min_d2, w.psum, w.pcnt, sp,    \
-                                                       xsq_part_of(w));                                       \
+            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave,                 \
+                                                       geo.waves_with_one_more, Xt, C, labels_out, labels_in, \
+                                                       min_d2, w.psum, w.pcnt, sp, xsq_part_of(w));           \
     } while (0)
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
