@@ -164,7 +164,7 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 // are rounded to bfloat16 for the scores (the reading taken for bfloat16 embeddings: see
 // large_assign_kernel); sums and means use the data in full precision.
 template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT>
-__global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void lloyd_small_kernel(
+__global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_small_kernel(
     int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, int64_t waves_with_one_more,
     const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
@@ -930,7 +930,9 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
     do {                                                                                                      \
         if (bf16) EP_SMALL_LAUNCH_T(D_, KT_, bf16_t); else EP_SMALL_LAUNCH_T(D_, KT_, float);                 \
     } while (0)
-    if (p.d == 128) {
+    if (p.d == 256) {
+        EP_SMALL_LAUNCH(256, 1);
+    } else if (p.d == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
     } else {
         if (kt == 1) EP_SMALL_LAUNCH(64, 1); else if (kt == 2) EP_SMALL_LAUNCH(64, 2); else EP_SMALL_LAUNCH(64, 4);
@@ -944,8 +946,8 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
 }  // namespace
 
 bool small_path_supported(const ep_problem &p) {
-    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && (p.d == 64 || p.d == 128) && p.k <= 64 &&
-           p.ld < ((int64_t)1 << 24);
+    const bool shape = ((p.d == 64 || p.d == 128) && p.k <= 64) || (p.d == 256 && p.k <= 16);
+    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && shape && p.ld < ((int64_t)1 << 24);
 }
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }

@@ -70,6 +70,10 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (3001, 128, 30, True, torch.bfloat16, None),     # two tiles,
     (2999, 64, 24, True, torch.bfloat16, None),
     (4099, 128, 64, True, torch.bfloat16, None),     # four tiles (pipelined fused round)
+    (5003, 256, 11, True, torch.float32, None),      # d = 256 on the small-k kernel (one centroid tile only)
+    (3001, 256, 16, False, torch.float32, 260),
+    (2999, 256, 7, True, torch.bfloat16, None),
+    (3000, 256, 20, True, torch.float32, None),      # d = 256, k > 16: generic kernels
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -147,6 +151,7 @@ def test_run_matches_oracle_full_size(name):
                                                (8_009, 64, 300, torch.bfloat16, 4),
                                                (20_011, 128, 16, torch.bfloat16, 8), (9_000, 128, 64, torch.bfloat16, 6),
                                                (6_011, 64, 40, torch.bfloat16, 6), (6_007, 128, 24, torch.bfloat16, 6),
+                                               (9_001, 256, 12, torch.float32, 6), (9_003, 256, 16, torch.bfloat16, 6),
                                                (5_000, 48, 6, torch.float32, 10)])
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
