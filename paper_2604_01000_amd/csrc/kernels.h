@@ -9,6 +9,7 @@ namespace ep {
 constexpr int kObjBlocksMax = 2048;   // partial objectives per assignment launch
 constexpr int kUpdBlocksMax = 1024;   // partial sums per small-k update launch
 constexpr int kSmallKElems = 8192;    // k*d at or below this: per-workgroup LDS partial sums
+constexpr int kSegWavesTarget = 4096; // sorted update: waves to spread k segments over when k is small
 
 struct KmeansWs {
     double *obj_part;     // [kObjBlocksMax]
@@ -21,6 +22,7 @@ struct KmeansWs {
     int32_t *order;       // [n]  rows sorted by label           (large k)
     int32_t *order_tmp;   // [n]
     int64_t *seg;         // [k+1] segment offsets               (large k)
+    double *seg_part;     // [kSegWavesTarget * d] sums of the parts of long segments (large k, d = 64 or 128)
     int32_t *sort_hist;   // radix-sort block histograms
     unsigned char *records;  // centroid tile records of the large-k matrix-core path
     int32_t *best_tile;   // [n] code of the 4 candidate centroid rows per point (large-k path)

@@ -258,6 +258,75 @@ __device__ __forceinline__ void load8<bf16_t>(const bf16_t *p, float (&v)[8]) {
     v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xFFFF0000u);
 }
 
+// Sum of the rows order[b .. e) in fp64 by one wave, for d = 8 * kLanes: lane = (sub, chunk) adds the
+// rows b + sub, b + sub + 64 / kLanes, ... in 8 columns, then the sub-lanes are added in a fixed
+// butterfly.  Every lane ends with the totals of its 8 columns.
+template <typename XT, int kLanes>
+__device__ __forceinline__ void sum_sorted_rows(const XT *__restrict__ X, int64_t ld, const int32_t *__restrict__ order,
+                                                int64_t b, int64_t e, int lane, double (&acc)[8]) {
+    constexpr int kL = kLanes > 0 ? kLanes : 1, kRows = 64 / kL;
+    const int chunk = lane % kL, sub = lane / kL;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.0;
+    int64_t t = b + sub;
+    for (; t + kRows < e; t += 2 * kRows) {   // two rows in flight per lane
+        float v0[8], v1[8];
+        load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
+        load8(X + (int64_t)order[t + kRows] * ld + 8 * chunk, v1);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] += (double)v1[q];
+    }
+    if (t < e) {
+        float v0[8];
+        load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
+    }
+#pragma unroll
+    for (int off = kL; off < 64; off <<= 1)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] += __shfl_xor(acc[q], off, 64);
+}
+
+// Few, long segments (k well below the number of waves the chip runs): every segment is cut into
+// `pieces` contiguous parts, one wave each; the parts' sums go to the workspace in fp64 and
+// segment_combine_kernel adds them in order.  The cut depends on (n, k) only: reproducible.
+template <typename XT, int kLanes>
+__global__ __launch_bounds__(kBlock) void segment_partial_kernel(int32_t d, int32_t k, int32_t pieces, int64_t ld,
+                                                                  const XT *__restrict__ X,
+                                                                  const int32_t *__restrict__ order,
+                                                                  const int64_t *__restrict__ seg,
+                                                                  double *__restrict__ part) {
+    const int64_t w = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (w >= (int64_t)k * pieces) return;
+    const int j = (int)(w / pieces), piece = (int)(w % pieces), lane = threadIdx.x & 63;
+    const int64_t b = seg[j], cnt = seg[j + 1] - b;
+    double acc[8];
+    sum_sorted_rows<XT, kLanes>(X, ld, order, b + cnt * piece / pieces, b + cnt * (piece + 1) / pieces, lane, acc);
+    if (lane < kLanes) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) part[w * d + 8 * lane + q] = acc[q];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void segment_combine_kernel(int32_t d, int32_t k, int32_t pieces,
+                                                                  const int64_t *__restrict__ seg,
+                                                                  const double *__restrict__ part,
+                                                                  const float *__restrict__ C_prev,
+                                                                  float *__restrict__ C_out,
+                                                                  int64_t *__restrict__ counts) {
+    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= (int64_t)k * d) return;
+    const int j = (int)(t / d), col = (int)(t % d);
+    const int64_t cnt = seg[j + 1] - seg[j];
+    double tot = 0.0;
+    for (int piece = 0; piece < pieces; ++piece) tot += part[((int64_t)j * pieces + piece) * d + col];
+    C_out[t] = cnt > 0 ? (float)(tot / (double)cnt) : C_prev[t];
+    if (col == 0) counts[j] = cnt;
+}
+
 template <typename XT, int kLanes>
 __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t k, int64_t ld,
                                                                const XT *__restrict__ X,
@@ -273,31 +342,9 @@ __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t
     const int64_t cnt = e - b;
     if (lane == 0) counts[j] = cnt;
     if (kLanes > 0) {
-        constexpr int kRows = kLanes > 0 ? 64 / (kLanes > 0 ? kLanes : 1) : 1;
         const int chunk = lane % (kLanes > 0 ? kLanes : 1), sub = lane / (kLanes > 0 ? kLanes : 1);
         double acc[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[q] = 0.0;
-        int64_t t = b + sub;
-        for (; t + kRows < e; t += 2 * kRows) {   // two rows in flight per lane
-            float v0[8], v1[8];
-            load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
-            load8(X + (int64_t)order[t + kRows] * ld + 8 * chunk, v1);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += (double)v1[q];
-        }
-        if (t < e) {
-            float v0[8];
-            load8(X + (int64_t)order[t] * ld + 8 * chunk, v0);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += (double)v0[q];
-        }
-#pragma unroll
-        for (int off = (kLanes > 0 ? kLanes : 64); off < 64; off <<= 1)
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += __shfl_xor(acc[q], off, 64);
+        sum_sorted_rows<XT, kLanes>(X, ld, order, b, e, lane, acc);
         if (sub == 0) {
             float *co = C_out + (int64_t)j * d + 8 * chunk;
             const float *cp = C_prev + (int64_t)j * d + 8 * chunk;
@@ -349,6 +396,7 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
         w.order = c.take<int32_t>((size_t)p.n);
         w.order_tmp = c.take<int32_t>((size_t)p.n);
         w.seg = c.take<int64_t>((size_t)p.k + 1);
+        if (p.d == 64 || p.d == 128) w.seg_part = c.take<double>((size_t)kSegWavesTarget * p.d);
         w.sort_hist = c.take<int32_t>(sort_hist_elems());
     }
     if (large_path_supported(p)) {
@@ -446,6 +494,19 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
         ProfScope prof(EP_PROF_UPDATE_SUMS, s);
         const unsigned grid = (unsigned)ceil_div(p.k, kBlock / 64);
         const XT *Xt = static_cast<const XT *>(X);
+        const int pieces = kSegWavesTarget / p.k;   // waves per segment; k * pieces <= kSegWavesTarget
+        if (pieces >= 2 && w.seg_part) {
+            const unsigned pgrid = (unsigned)ceil_div((int64_t)p.k * pieces, kBlock / 64);
+            if (p.d == 128)
+                segment_partial_kernel<XT, 16><<<pgrid, kBlock, 0, s>>>(p.d, p.k, pieces, p.ld, Xt, w.order, w.seg, w.seg_part);
+            else
+                segment_partial_kernel<XT, 8><<<pgrid, kBlock, 0, s>>>(p.d, p.k, pieces, p.ld, Xt, w.order, w.seg, w.seg_part);
+            EP_LAUNCH_CHECK();
+            segment_combine_kernel<<<(unsigned)ceil_div((int64_t)p.k * p.d, kBlock), kBlock, 0, s>>>(
+                p.d, p.k, pieces, w.seg, w.seg_part, C_prev, C_out, counts);
+            EP_LAUNCH_CHECK();
+            return EP_OK;
+        }
         if (p.d == 128)
             segment_mean_kernel<XT, 16><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
         else if (p.d == 64)

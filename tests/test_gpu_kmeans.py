@@ -74,6 +74,8 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (3001, 256, 16, False, torch.float32, 260),
     (2999, 256, 7, True, torch.bfloat16, None),
     (3000, 256, 20, True, torch.float32, None),      # d = 256, k > 16: generic kernels
+    (6000, 128, 100, True, torch.float32, None),     # fp32 with k > 64: generic assignment, segments cut in parts
+    (5000, 64, 200, False, torch.float32, 68),
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -152,6 +154,7 @@ def test_run_matches_oracle_full_size(name):
                                                (20_011, 128, 16, torch.bfloat16, 8), (9_000, 128, 64, torch.bfloat16, 6),
                                                (6_011, 64, 40, torch.bfloat16, 6), (6_007, 128, 24, torch.bfloat16, 6),
                                                (9_001, 256, 12, torch.float32, 6), (9_003, 256, 16, torch.bfloat16, 6),
+                                               (12_345, 128, 150, torch.float32, 4), (30_011, 64, 70, torch.bfloat16, 4),
                                                (5_000, 48, 6, torch.float32, 10)])
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
