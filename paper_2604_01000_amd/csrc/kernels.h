@@ -9,7 +9,7 @@ namespace ep {
 constexpr int kObjBlocksMax = 2048;   // partial objectives per assignment launch
 constexpr int kUpdBlocksMax = 1024;   // partial sums per small-k update launch
 constexpr int kSmallKElems = 8192;    // k*d at or below this: per-workgroup LDS partial sums
-constexpr int kSegWavesTarget = 4096; // sorted update: waves to spread k segments over when k is small
+constexpr int kSegWavesTarget = 16384; // sorted update: waves to spread k segments over when k is small
 
 struct KmeansWs {
     double *obj_part;     // [kObjBlocksMax]
