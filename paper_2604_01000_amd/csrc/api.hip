@@ -62,6 +62,7 @@ bool small_k(const ep_problem &p) { return (int64_t)p.k * p.d <= kSmallKElems; }
 int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
               float *min_d2, double *objective, hipStream_t s) {
     if (small_path_supported(p)) return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
+    if (small_sliced_supported(p)) return launch_small_assign_sliced(p, X, C, w, labels, min_d2, objective, s);
     if (large_path_supported(p)) return launch_large_assign(p, X, C, w, labels, min_d2, objective, s);
     int rc = launch_prep_centroids(p, C, w, s);
     if (rc != EP_OK) return rc;

@@ -19,6 +19,7 @@ struct KmeansWs {
     float *psum;          // [kUpdBlocksMax * k * d]   (small k)
     int32_t *pcnt;        // [kUpdBlocksMax * k]       (small k)
     int64_t *idx;         // [k] init row indices
+    float *best_score;    // [n] best score over the centroid slices seen so far (fp32, d in {64,128}, k > 64)
     int32_t *order;       // [n]  rows sorted by label           (large k)
     int32_t *order_tmp;   // [n]
     int64_t *seg;         // [k+1] segment offsets               (large k)
@@ -49,6 +50,10 @@ int launch_small_assign(const ep_problem &p, const void *X, const float *C, cons
                         float *min_d2, double *objective, hipStream_t s);
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+// fp32, d in {64,128}, k > 64: the same assignment kernel over slices of 64 centroids (k / 64 passes).
+bool small_sliced_supported(const ep_problem &p);
+int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                               float *min_d2, double *objective, hipStream_t s);
 // One fused round: assign against C, sums, then C <- means (in place), *objective <- this
 // round's objective.
 // first_round: the data-only term of the objective (sum ||x||^2) is computed and kept in the

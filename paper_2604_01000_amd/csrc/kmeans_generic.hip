@@ -389,6 +389,7 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
         w.cq = c.take<float>(kd);
         w.cq16 = c.take<bf16_t>(kd);
     }
+    if (small_sliced_supported(p)) w.best_score = c.take<float>((size_t)p.n);
     if (kd <= (size_t)kSmallKElems) {
         w.psum = c.take<float>((size_t)kUpdBlocksMax * kd);
         w.pcnt = c.take<int32_t>((size_t)kUpdBlocksMax * p.k);

@@ -169,7 +169,8 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
-    int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part) {
+    int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part,
+    int32_t label_base, float *__restrict__ best_score) {
     constexpr int NJ = D / 16;       // 16-byte pieces per lane in the transposed layout; also column tiles
     constexpr int NH = D / 64;       // 16-byte pieces per lane and point in the load layout
     constexpr int STRIDE = D + 4;    // padded LDS row: consecutive rows start 4 banks apart
@@ -405,6 +406,11 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         const int rows_here = (int)min((int64_t)kSub, n - row0);  // uniform
         int32_t lab[4];
         f32x4 bt[NX];  // sum operand: piece r * NH + h
+        // Assignment over a slice of the centroids (best_score != nullptr, assignment mode only): the
+        // best score of the earlier slices is fetched now and met at the end of the sub-tile.
+        float earlier_best = -3.4e38f;
+        if (MODE == kAssignOnly && best_score && label_base > 0 && c < 4 && 4 * g + c < rows_here)
+            earlier_best = best_score[row0 + 4 * g + c];
         if (MODE != kUpdateOnly) {
             // The sum product needs the other layout: the sub-tile goes through the wave's LDS tile
             // (written point-per-lane, read row-per-group) in the shadow of the score product.
@@ -482,13 +488,25 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
             const float my_s = key_float(sel == 0 ? bkey[0] : sel == 1 ? bkey[1] : sel == 2 ? bkey[2] : bkey[3]);
             const int32_t my_l = sel == 0 ? lab[0] : sel == 1 ? lab[1] : sel == 2 ? lab[2] : lab[3];
             const bool owner = c < 4 && 4 * g + c < rows_here;
-            if (c < 4) lbuf[buffered * kSub + 4 * g + c] = my_l;
-            ++buffered;
-            if (kLdsSums) {   // every lane of a 16-lane row keeps the row's sum; lane c == 0's is used
+            bool sliced = false;
+            if constexpr (MODE == kAssignOnly) sliced = best_score != nullptr;   // uniform
+            float fin_s = my_s;   // the point's best score over this and the earlier slices
+            if (sliced) {   // strict >: on equal scores the earlier slice (lower index) keeps the point
+                const bool better = my_s > earlier_best;
+                fin_s = better ? my_s : earlier_best;
+                if (owner) {
+                    if (better) labels_out[row0 + 4 * g + c] = my_l + label_base;
+                    best_score[row0 + 4 * g + c] = fin_s;
+                }
+            } else {
+                if (c < 4) lbuf[buffered * kSub + 4 * g + c] = my_l;
+                ++buffered;
+            }
+            if (kLdsSums && !sliced) {   // every lane of a 16-lane row keeps the row's sum; lane c == 0's is used
 #pragma unroll
                 for (int v = 0; v < 4; ++v) obj_s += (double)(4 * g + v < rows_here ? key_float(bkey[v]) : 0.f);
             } else if (owner) {
-                obj_s += (double)my_s;
+                obj_s += (double)fin_s;
             }
             if (XSQ && c < rows_here) obj_x += (double)xpart;
             if (min_d2) {  // uniform branch
@@ -497,7 +515,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
                 xn += __shfl_xor(xn, 32, 64);
                 if (g == 0) xn_lds[wave][c] = xn;
                 wave_lds_fence();
-                if (owner) min_d2[row0 + 4 * g + c] = fmaxf(xn_lds[wave][4 * g + c] - 2.f * my_s, 0.f);
+                if (owner) min_d2[row0 + 4 * g + c] = fmaxf(xn_lds[wave][4 * g + c] - 2.f * fin_s, 0.f);
                 wave_lds_fence();
             }
         } else if (!kLdsSums) {
@@ -719,7 +737,9 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     // ---- objective partials of this workgroup (fixed order) ----
     if (MODE != kUpdateOnly && s_part) {
         double os = obj_s, ox = obj_x;
-        if (kLdsSums && c != 0) os = 0.0;   // k > 16: all 16 lanes of a row hold the same sum
+        bool per_row = kLdsSums;            // k > 16: all 16 lanes of a row hold the same sum,
+        if constexpr (MODE == kAssignOnly) per_row = per_row && best_score == nullptr;   // except over slices
+        if (per_row && c != 0) os = 0.0;
         for (int off = 32; off > 0; off >>= 1) {
             os += __shfl_down(os, off, 64);
             if (XSQ) ox += __shfl_down(ox, off, 64);
@@ -898,9 +918,12 @@ double *s_part_of(const KmeansWs &w) { return w.obj_part; }
 double *xsq_part_of(const KmeansWs &w) { return w.obj_part + kSmallMaxBlocks; }
 double *xsq_total_of(const KmeansWs &w) { return w.obj_part + 2 * kSmallMaxBlocks; }
 
+// label_base / best_score: assignment over one 64-centroid slice of a larger k (see
+// launch_small_assign_sliced); 0 / nullptr otherwise.
 template <int MODE, bool XSQ>
 int launch_mode(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels_out,
-                const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s) {
+                const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s, int32_t label_base = 0,
+                float *best_score = nullptr) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
     const bool bf16 = p.dtype == EP_BF16;
@@ -920,11 +943,12 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
                                   p.n, p.ld, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,       \
                                   labels_out, labels_in, min_d2,                                              \
-                                  w.psum, w.pcnt, sp, xsq_part_of(w));                                        \
+                                  w.psum, w.pcnt, sp, xsq_part_of(w), label_base, best_score);                \
         else                                                                                                  \
             kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave,                 \
                                                        geo.waves_with_one_more, Xt, C, labels_out, labels_in, \
-                                                       min_d2, w.psum, w.pcnt, sp, xsq_part_of(w));           \
+                                                       min_d2, w.psum, w.pcnt, sp, xsq_part_of(w),            \
+                                                       label_base, best_score);                               \
     } while (0)
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
@@ -957,6 +981,32 @@ int launch_small_assign(const ep_problem &p, const void *X, const float *C, cons
     int rc = objective ? launch_mode<kAssignOnly, true>(p, X, C, w, labels, nullptr, min_d2, true, s)
                        : launch_mode<kAssignOnly, false>(p, X, C, w, labels, nullptr, min_d2, false, s);
     if (rc != EP_OK) return rc;
+    if (objective) {
+        sum_obj_kernel<<<1, 64, 0, s>>>(s_part_of(w), xsq_part_of(w), small_blocks(p), xsq_total_of(w), objective);
+        EP_LAUNCH_CHECK();
+    }
+    return EP_OK;
+}
+
+// fp32 rows, d in {64, 128}, k > 64: the assignment kernel runs once per slice of 64 centroids and
+// keeps, per point, the best score so far (in the workspace) and its label: k / 64 passes over X
+// with the exact arithmetic of the k <= 64 kernel.  Ties go to the lower index: a later slice must
+// beat the earlier ones strictly.
+bool small_sliced_supported(const ep_problem &p) {
+    return p.dtype == EP_F32 && (p.d == 64 || p.d == 128) && p.k > 64 && p.ld < ((int64_t)1 << 24);
+}
+
+int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
+                               float *min_d2, double *objective, hipStream_t s) {
+    float *best = w.best_score;
+    for (int32_t base = 0; base < p.k; base += 64) {
+        ep_problem slice = p;
+        slice.k = std::min<int32_t>(64, p.k - base);
+        const float *Cs = C + (int64_t)base * p.d;
+        int rc = objective ? launch_mode<kAssignOnly, true>(slice, X, Cs, w, labels, nullptr, min_d2, true, s, base, best)
+                           : launch_mode<kAssignOnly, false>(slice, X, Cs, w, labels, nullptr, min_d2, false, s, base, best);
+        if (rc != EP_OK) return rc;
+    }
     if (objective) {
         sum_obj_kernel<<<1, 64, 0, s>>>(s_part_of(w), xsq_part_of(w), small_blocks(p), xsq_total_of(w), objective);
         EP_LAUNCH_CHECK();

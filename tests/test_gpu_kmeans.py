@@ -74,7 +74,10 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (3001, 256, 16, False, torch.float32, 260),
     (2999, 256, 7, True, torch.bfloat16, None),
     (3000, 256, 20, True, torch.float32, None),      # d = 256, k > 16: generic kernels
-    (6000, 128, 100, True, torch.float32, None),     # fp32 with k > 64: generic assignment, segments cut in parts
+    (6000, 128, 100, True, torch.float32, None),     # fp32 with k > 64: assignment in slices of 64 centroids,
+    (4097, 128, 65, True, torch.float32, 132),       # one full slice and a slice of one centroid,
+    (3000, 64, 129, False, torch.float32, None),     # two full slices and one more centroid,
+    (5001, 128, 1000, True, torch.float32, None),    # 16 slices; update: segments cut in parts
     (5000, 64, 200, False, torch.float32, 68),
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
@@ -103,6 +106,23 @@ def test_assign_ties_take_the_lowest_index():
     want, _, _, _ = oracle.assign(X32, C)
     assert not np.any(got >= 6)
     np.testing.assert_array_equal(got, want)
+
+
+def test_assign_ties_across_centroid_slices():
+    """fp32 with k > 64 is assigned in slices of 64 centroids: a duplicate in a later slice must not take
+    the point from the earlier one, and the returned distances and objective are those of the winner."""
+    X = _mixture(4000, 128, 6, seed=8)
+    X32 = to_np32(X)
+    base = X32[oracle.init_indices(11, 4000, 70)].astype(np.float64)
+    C = np.concatenate([base, base[[3, 69, 0, 64]], base[:60] + 5.0])      # 134 centroids; 70..73 duplicate 3, 69, 0, 64
+    C = C.astype(np.float32).astype(np.float64)                            # what the device is given
+    km = Kmeans(X, C.shape[0]).set_centroids(C)
+    got, d2, obj = km.assign()
+    want, best, _, obj_or = oracle.assign(X32, C)
+    np.testing.assert_array_equal(got, want)
+    assert not np.any((got >= 70) & (got <= 73))
+    assert np.all(np.abs(d2 - best) <= 1e-5 * ((X32.astype(np.float64) ** 2).sum(1) + (C[want] ** 2).sum(1)))
+    assert abs(obj - obj_or) <= 1e-5 * obj_or
 
 
 @pytest.mark.parametrize("n,d,k,relu,dtype,ld", SHAPES)
