@@ -57,8 +57,6 @@ uint64_t splitmix64(uint64_t &state) {
     return z ^ (z >> 31);
 }
 
-bool small_k(const ep_problem &p) { return (int64_t)p.k * p.d <= kSmallKElems; }
-
 int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
               float *min_d2, double *objective, hipStream_t s) {
     if (small_path_supported(p)) return launch_small_assign(p, X, C, w, labels, min_d2, objective, s);
@@ -72,8 +70,8 @@ int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs
 int do_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
               int64_t *counts, const KmeansWs &w, hipStream_t s) {
     if (small_path_supported(p)) return launch_small_update(p, X, labels, C_prev, C_out, counts, w, s);
-    return small_k(p) ? launch_update_small(p, X, labels, C_prev, C_out, counts, w, s)
-                      : launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, s);
+    return update_by_sorted_rows(p) ? launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, s)
+                                    : launch_update_small(p, X, labels, C_prev, C_out, counts, w, s);
 }
 
 int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colidx) {

@@ -11,6 +11,13 @@ constexpr int kUpdBlocksMax = 1024;   // partial sums per small-k update launch
 constexpr int kSmallKElems = 8192;    // k*d at or below this: per-workgroup LDS partial sums
 constexpr int kSegWavesTarget = 16384; // sorted update: waves to spread k segments over when k is small
 
+// Which centroid update a problem outside the fused small-k kernels takes: per-workgroup partial sums
+// for small k * d, otherwise (and for k > 64 at d = 64 or 128, where it is several times faster)
+// rows sorted by label + segment means.  The workspace is carved accordingly.
+inline bool update_by_sorted_rows(const ep_problem &p) {
+    return (int64_t)p.k * p.d > kSmallKElems || (p.k > 64 && (p.d == 64 || p.d == 128));
+}
+
 struct KmeansWs {
     double *obj_part;     // [kObjBlocksMax]
     float *cnorm;         // [k]   generic path: ||c_j||^2; bf16 matrix-core path: -||c_j||^2 / 2 (of the rounded centroids)

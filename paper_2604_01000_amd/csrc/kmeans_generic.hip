@@ -390,7 +390,7 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
         w.cq16 = c.take<bf16_t>(kd);
     }
     if (small_sliced_supported(p)) w.best_score = c.take<float>((size_t)p.n);
-    if (kd <= (size_t)kSmallKElems) {
+    if (!update_by_sorted_rows(p)) {
         w.psum = c.take<float>((size_t)kUpdBlocksMax * kd);
         w.pcnt = c.take<int32_t>((size_t)kUpdBlocksMax * p.k);
     } else {
