@@ -29,10 +29,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/), scaled by the copy-kernel calibration; None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "arxiv_like": 89_720_233,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
-    "products_like": 1_281_838_677,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
+    "arxiv_like": 90_006_646,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
+    "products_like": 1_285_319_468,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
     "products_reorder": 1_149_254_277,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
-    "papers_like": 57_357_561_944,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
+    "papers_like": 57_349_581_665,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
 }
 
 
