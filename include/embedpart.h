@@ -228,6 +228,37 @@ int partition_balance(int64_t n, int32_t k, const void *rowptr, int rowptr_is_i6
                       void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Phase 2 of the method in one call (the paper's Alg. 3, ClusterAndBalance): P <- KMeans(E, k),
+ * then the three balancing loops over the training, validation and remaining vertices, each
+ * with its own imbalance factor.  It enqueues exactly what kmeans_init + kmeans_run (or
+ * kmeans_run_sampled) + three partition_balance calls would, in that order, and returns the
+ * same results bit for bit.
+ *   rows_host  sample_rows == 0: k distinct row indices, the initial centroids (kmeans_init);
+ *              sample_rows == m > 0: the m sample rows of kmeans_run_sampled
+ *   vclass     n bytes: 0 training, 1 validation, 2 remaining vertex; NULL: every vertex counts
+ *              as remaining (one loop, beta[2])
+ *   C          k * d fp32, written: the centroids K-Means ended with
+ *   labels     n int32, 16-byte aligned, written: the partition of every vertex after balancing
+ *   counts     k int64, written: the cluster sizes K-Means ended with (before balancing)
+ *   stats      9 int64, written: the three partition_balance statistics of class 0, 1, 2 (with
+ *              vclass == NULL only the last three)
+ *   ws         cluster_and_balance_workspace_bytes(p, sample_rows) bytes
+ * Errors: as the calls it is made of; k > EP_BALANCE_MAX_K gives EP_EUNSUPPORTED.
+ */
+typedef struct ep_phase2 {
+    double beta[3];      /* imbalance factors beta_train, beta_val, beta_rest (>= 1) */
+    uint64_t seed;       /* class c draws its destinations with seed + c */
+    int32_t iters;       /* Lloyd rounds */
+    int32_t max_rounds;  /* migration rounds per class, at most EP_BALANCE_MAX_ROUNDS */
+    int64_t sample_rows; /* 0: Lloyd over all rows; m: centroids trained on m sample rows */
+} ep_phase2;
+int cluster_and_balance_workspace_bytes(const ep_problem *p, int64_t sample_rows, size_t *bytes_host);
+int cluster_and_balance(const ep_problem *p, const void *X, const void *rowptr, int rowptr_is_i64,
+                        const uint8_t *vclass, const ep_phase2 *opt, const int64_t *rows_host,
+                        float *C, int32_t *labels, int64_t *counts, int64_t *stats,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Sum over vertices of the vertex bandwidth max_{u in N(v)} |pi(v) - pi(u)|
  * (0 for a vertex without neighbours); divided by n it is the average graph
  * bandwidth of the paper's reordering evaluation.  bw_sum: 1 uint64, written.

@@ -359,4 +359,50 @@ int graph_reorder(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
                           carve_reorder_ws(n, nnz, ws), static_cast<hipStream_t>(stream));
 }
 
+static size_t phase2_kmeans_bytes(const ep_problem &p, int64_t m) {
+    return align_up(m > 0 ? carve_sampled_ws(p, m, nullptr).bytes : carve_kmeans_ws(p, nullptr).bytes, 256);
+}
+
+int cluster_and_balance_workspace_bytes(const ep_problem *p, int64_t sample_rows, size_t *bytes_host) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!bytes_host || sample_rows < 0 || (sample_rows > 0 && (sample_rows < p->k || sample_rows > p->n)))
+        return EP_EINVAL;
+    *bytes_host = phase2_kmeans_bytes(*p, sample_rows) + carve_balance_ws(p->n, nullptr).bytes;
+    return EP_OK;
+}
+
+int cluster_and_balance(const ep_problem *p, const void *X, const void *rowptr, int rowptr_is_i64,
+                        const uint8_t *vclass, const ep_phase2 *opt, const int64_t *rows_host, float *C,
+                        int32_t *labels, int64_t *counts, int64_t *stats, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!opt || !stats || !aligned(stats, 8) || opt->sample_rows < 0) return EP_EINVAL;
+    if (p->k > EP_BALANCE_MAX_K) return EP_EUNSUPPORTED;
+    const int64_t m = opt->sample_rows;
+    if (m > 0 && (m < p->k || m > p->n)) return EP_EINVAL;
+    const size_t km_bytes = phase2_kmeans_bytes(*p, m), bal_bytes = carve_balance_ws(p->n, nullptr).bytes;
+    if ((rc = check_ws(ws, ws_bytes, km_bytes + bal_bytes)) != EP_OK) return rc;
+    void *bal_ws = static_cast<char *>(ws) + km_bytes;
+    // every argument is validated by the calls themselves before anything is enqueued; the balancing
+    // arguments are checked first so that a bad one does not leave a finished clustering behind
+    for (int c = 0; c < 3; ++c)
+        if (!(opt->beta[c] >= 1.0) || !(opt->beta[c] < 1.0e6)) return EP_EINVAL;
+    if (opt->max_rounds < 0 || opt->max_rounds > EP_BALANCE_MAX_ROUNDS || !rowptr || !aligned(rowptr, 8))
+        return EP_EINVAL;
+    if (m > 0) {
+        rc = kmeans_run_sampled(p, X, m, rows_host, opt->iters, C, labels, counts, nullptr, ws, km_bytes, stream);
+    } else {
+        if ((rc = kmeans_init(p, X, rows_host, C, ws, km_bytes, stream)) != EP_OK) return rc;
+        rc = kmeans_run(p, X, opt->iters, C, labels, counts, nullptr, 0, ws, km_bytes, stream);
+    }
+    if (rc != EP_OK) return rc;
+    for (int c = vclass ? 0 : 2; c < 3; ++c) {
+        rc = partition_balance(p->n, p->k, rowptr, rowptr_is_i64, vclass, c, opt->beta[c], opt->seed + (uint64_t)c,
+                               opt->max_rounds, labels, stats + 3 * c, bal_ws, bal_bytes, stream);
+        if (rc != EP_OK) return rc;
+    }
+    return EP_OK;
+}
+
 }  // extern "C"

@@ -28,6 +28,7 @@ SYMBOLS = (
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
     "balance_workspace_bytes", "partition_balance", "graph_reorder_workspace_bytes", "graph_reorder",
+    "cluster_and_balance_workspace_bytes", "cluster_and_balance",
     "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
@@ -36,6 +37,11 @@ EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
 class ep_problem(C.Structure):
     _fields_ = [("n", C.c_int64), ("ld", C.c_int64), ("d", C.c_int32), ("k", C.c_int32),
                 ("dtype", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ep_phase2(C.Structure):
+    _fields_ = [("beta", C.c_double * 3), ("seed", C.c_uint64), ("iters", C.c_int32), ("max_rounds", C.c_int32),
+                ("sample_rows", C.c_int64)]
 
 
 class EmbedPartError(RuntimeError):
@@ -75,6 +81,9 @@ def lib() -> C.CDLL:
         L.edge_gap_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.vertex_bandwidth_sum.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, sz, vp]
         L.graph_reorder_workspace_bytes.argtypes = [i64, i64, C.POINTER(sz)]
+        L.cluster_and_balance_workspace_bytes.argtypes = [C.POINTER(ep_problem), i64, C.POINTER(sz)]
+        L.cluster_and_balance.argtypes = [C.POINTER(ep_problem), vp, vp, C.c_int, vp, C.POINTER(ep_phase2), vp, vp, vp,
+                                          vp, vp, vp, sz, vp]
         L.graph_reorder.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
         L.ep_bench_copy.argtypes = [vp, vp, sz, vp]
@@ -216,6 +225,25 @@ def edge_gap_sum(n, nnz, rowptr, colidx, new_id, gap_sum, ws):
 def vertex_bandwidth_sum(n, nnz, rowptr, colidx, new_id, bw_sum, ws):
     _check(lib().vertex_bandwidth_sum(n, nnz, _ptr(rowptr), _is_i64(rowptr), _ptr(colidx), _ptr(new_id),
                                       _ptr(bw_sum), _ptr(ws), ws.numel(), _stream()), "vertex_bandwidth_sum")
+
+
+def phase2_options(beta, seed: int, iters: int, max_rounds: int, sample_rows: int = 0) -> ep_phase2:
+    return ep_phase2((C.c_double * 3)(*[float(b) for b in beta]), seed & (2**64 - 1), iters, max_rounds, sample_rows)
+
+
+def cluster_and_balance_workspace_bytes(p: ep_problem, sample_rows: int = 0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().cluster_and_balance_workspace_bytes(C.byref(p), sample_rows, C.byref(out)),
+           "cluster_and_balance_workspace_bytes")
+    return out.value
+
+
+def cluster_and_balance(p, X, rowptr, vclass, opt, rows_host, Cc, labels, counts, stats, ws):
+    rows_host = rows_host.contiguous()
+    assert rows_host.device.type == "cpu" and rows_host.dtype == torch.int64
+    _check(lib().cluster_and_balance(C.byref(p), _ptr(X), _ptr(rowptr), _is_i64(rowptr), _ptr(vclass), C.byref(opt),
+                                     _ptr(rows_host), _ptr(Cc), _ptr(labels), _ptr(counts), _ptr(stats), _ptr(ws),
+                                     ws.numel(), _stream()), "cluster_and_balance")
 
 
 def graph_reorder_workspace_bytes(n: int, nnz: int) -> int:

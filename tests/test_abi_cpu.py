@@ -205,3 +205,40 @@ def test_graph_reorder_rejects_bad_arguments():
     assert call(nnz=1 << 31, bytes=1 << 40) == ep.EP_EINVAL             # 32-bit offsets cannot hold it
     assert call(ws=None) == ep.EP_EWORKSPACE
     assert call(bytes=need - 1) == ep.EP_EWORKSPACE
+
+
+def test_cluster_and_balance_rejects_bad_arguments():
+    L = ep.lib()
+    fake, ws = C.c_void_p(0x1000), C.c_void_p(0x100000)
+    out = C.c_size_t(0)
+    p = ep.ep_problem(5000, 64, 64, 8, ep.EP_F32, 0)
+    assert L.cluster_and_balance_workspace_bytes(C.byref(p), -1, C.byref(out)) == ep.EP_EINVAL
+    assert L.cluster_and_balance_workspace_bytes(C.byref(p), 4, C.byref(out)) == ep.EP_EINVAL      # fewer than k rows
+    assert L.cluster_and_balance_workspace_bytes(C.byref(p), 5001, C.byref(out)) == ep.EP_EINVAL
+    assert L.cluster_and_balance_workspace_bytes(C.byref(p), 0, None) == ep.EP_EINVAL
+    need = ep.cluster_and_balance_workspace_bytes(p)
+    assert need >= ep.kmeans_workspace_bytes(p) + ep.balance_workspace_bytes(5000)
+    assert ep.cluster_and_balance_workspace_bytes(p, 1000) > need - ep.kmeans_workspace_bytes(p)
+    rows = (C.c_int64 * 8)(*range(8))
+
+    def call(**kw):
+        opt = ep.phase2_options(kw.get("beta", (1.05, 1.05, 1.1)), 3, kw.get("iters", 5), kw.get("rounds", 8),
+                                kw.get("sample", 0))
+        return L.cluster_and_balance(C.byref(kw.get("p", p)), kw.get("X", fake), kw.get("rowptr", fake), 0, None,
+                                     C.byref(opt) if kw.get("opt", True) else None, kw.get("rows", rows),
+                                     kw.get("C", fake), kw.get("labels", fake), kw.get("counts", fake),
+                                     kw.get("stats", fake), kw.get("ws", ws), kw.get("bytes", need), None)
+
+    assert call(opt=False) == ep.EP_EINVAL
+    assert call(stats=None) == ep.EP_EINVAL
+    assert call(rowptr=None) == ep.EP_EINVAL
+    assert call(beta=(1.05, 0.5, 1.1)) == ep.EP_EINVAL
+    assert call(rounds=ep.EP_BALANCE_MAX_ROUNDS + 1) == ep.EP_EINVAL
+    assert call(sample=4) == ep.EP_EINVAL
+    assert call(X=None) == ep.EP_EINVAL
+    assert call(C=None) == ep.EP_EINVAL
+    assert call(rows=None) == ep.EP_EINVAL
+    assert call(ws=None) == ep.EP_EWORKSPACE
+    assert call(bytes=need - 1) == ep.EP_EWORKSPACE
+    big = ep.ep_problem(5000, 64, 64, 300, ep.EP_F32, 0)
+    assert call(p=big) == ep.EP_EUNSUPPORTED                                  # balancing: partition-scale k only

@@ -87,3 +87,53 @@ def test_balance_is_reproducible_and_leaves_a_balanced_partition_alone():
     np.testing.assert_array_equal(sc, [0, 0, 0])
     d, _ = _device_balance(rowptr, labels, k, 1.05, 5, 16)         # another seed: other destinations
     assert not np.array_equal(a, d)
+
+
+@pytest.mark.parametrize("name,sample,with_classes", [("tiny", 0, True), ("arxiv_like", 0, False), ("tiny", 2048, True)])
+def test_cluster_and_balance_is_phase_two_of_the_method(name, sample, with_classes):
+    """The one-call form of the paper's Alg. 3 equals its parts bit for bit (same kernels, same order), and
+    the balancing it performs is the oracle's applied to the labels the clustering produced."""
+    from parity import Kmeans
+    w = synth.WORKLOADS[name]
+    X = synth.embeddings(w, DEV)
+    rowptr, _, _ = synth.sbm_graph(w, DEV)
+    rng = np.random.default_rng(w.seed)
+    vclass_np = rng.choice(3, size=w.n, p=[0.5, 0.2, 0.3]).astype(np.uint8) if with_classes else None
+    vclass = None if vclass_np is None else torch.from_numpy(vclass_np).to(DEV)
+    beta, seed, rounds = (1.05, 1.1, 1.2), 77, 16
+    rows = oracle.init_indices(w.seed, w.n, sample if sample else w.k)
+    rows_t = torch.as_tensor(np.asarray(rows), dtype=torch.int64)
+
+    p = ep.problem(X, w.k)
+    Cc = torch.empty((w.k, w.d), dtype=torch.float32, device=DEV)
+    labels = torch.full((w.n,), -7, dtype=torch.int32, device=DEV)
+    counts = torch.full((w.k,), -7, dtype=torch.int64, device=DEV)
+    stats = torch.full((9,), -7, dtype=torch.int64, device=DEV)
+    ws = ep.workspace(ep.cluster_and_balance_workspace_bytes(p, sample), DEV)
+    opt = ep.phase2_options(beta, seed, w.iters, rounds, sample)
+    ep.cluster_and_balance(p, X, rowptr, vclass, opt, rows_t, Cc, labels, counts, stats, ws)
+    torch.cuda.synchronize()
+
+    # the parts, called one by one
+    km = Kmeans(X, w.k)
+    if sample:
+        sws = ep.workspace(ep.kmeans_sampled_workspace_bytes(km.p, sample), DEV)
+        ep.kmeans_run_sampled(km.p, X, rows_t, w.iters, km.C, km.labels, km.counts, None, sws)
+    else:
+        km.init(rows)
+        ep.kmeans_run(km.p, X, w.iters, km.C, km.labels, km.counts, None, 0, km.ws)
+    torch.cuda.synchronize()
+    clustered = km.labels.cpu().numpy()
+    assert torch.equal(Cc, km.C) and torch.equal(counts, km.counts)
+
+    want, want_stats = clustered.copy(), []
+    rp_np = rowptr.cpu().numpy().astype(np.int64)
+    for cls in ([0, 1, 2] if with_classes else [2]):
+        want, st = oracle.balance(rp_np, want, w.k, beta[cls], seed + cls, rounds, vclass_np, cls)
+        want_stats.append(st)
+    np.testing.assert_array_equal(labels.cpu().numpy(), want)
+    got_stats = stats.cpu().numpy().reshape(3, 3)
+    np.testing.assert_array_equal(got_stats[3 - len(want_stats):], np.stack(want_stats))
+    sizes = np.bincount(want, minlength=w.k)
+    if not with_classes:
+        assert sizes.max() <= max(np.floor(beta[2] * w.n / w.k), np.ceil(w.n / w.k))
