@@ -569,7 +569,10 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         // piece of the fixed row-add rounds) spread evenly, in program order, over the 6 * KS groups of
         // matrix instructions.  The items hold no branch (lanes with nothing to do write to scrap
         // words instead), so the whole step is one basic block whose order the scheduling barriers fix.
-        constexpr int kFixedRounds = D >= 128 ? 3 : 2;   // these ranks without branches; higher ranks (rare) in a loop
+        // Ranks 0 and 1 without branches, higher ranks (a tenth of the sub-tiles at k = 64) in a loop.  A
+        // third fixed round was measured: its 8 row-add pieces per sub-tile cost more than the branches
+        // they save (16.6 -> 15.95 ms per round on 111 M points).
+        constexpr int kFixedRounds = 2;
         constexpr int kFirstAdd = 7;                       // items 0 .. 6: arg-max (4), labels, rank (2)
         constexpr int kItems = kFirstAdd + kFixedRounds * NJ;
         constexpr int kGroups = kScoreGroups;
