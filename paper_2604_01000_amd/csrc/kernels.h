@@ -52,6 +52,13 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
 
 // ---- K-Means, k <= 64, d in {64,128}, fp32: fused matrix-core kernels (kmeans_small.hip) --------
 constexpr int kSmallMaxBlocks = 512;  // workgroups (= partial sums) per launch; <= kUpdBlocksMax
+// Column count the fused small-k kernels are instantiated for (64, 128: k <= 64; 256: k <= 16): d rounded up;
+// rows with fewer columns are padded with zeros as they are read.  0: not a shape of these kernels.
+inline int small_padded_d(const ep_problem &p) {
+    if (p.d < 4 || p.d > 256 || p.d % 4 != 0) return 0;
+    const int dpad = p.d <= 64 ? 64 : p.d <= 128 ? 128 : 256;
+    return p.k <= (dpad == 256 ? 16 : 64) ? dpad : 0;
+}
 bool small_path_supported(const ep_problem &p);
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s);

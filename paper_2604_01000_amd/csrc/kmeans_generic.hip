@@ -391,7 +391,7 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
     }
     if (small_sliced_supported(p)) w.best_score = c.take<float>((size_t)p.n);
     if (!update_by_sorted_rows(p)) {
-        w.psum = c.take<float>((size_t)kUpdBlocksMax * kd);
+        w.psum = c.take<float>((size_t)kUpdBlocksMax * std::max(kd, (size_t)p.k * (size_t)small_padded_d(p)));
         w.pcnt = c.take<int32_t>((size_t)kUpdBlocksMax * p.k);
     } else {
         w.order = c.take<int32_t>((size_t)p.n);

@@ -163,9 +163,12 @@ __device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32
 // XT: element type of X.  bfloat16 rows are widened to fp32 as they arrive (exact) and the centroids
 // are rounded to bfloat16 for the scores (the reading taken for bfloat16 embeddings: see
 // large_assign_kernel); sums and means use the data in full precision.
-template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT>
+// PAD: the rows have d < D columns (d a multiple of 4, passed at run time); columns d .. D - 1 are
+// read as zeros (their loads are sent out of the buffer's range), which changes neither scores nor
+// sums, and only the first d columns of the centroids exist in memory.
+template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT, bool PAD>
 __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_small_kernel(
-    int64_t n, int64_t ld, int32_t k, int64_t subtiles_per_wave, int64_t waves_with_one_more,
+    int64_t n, int64_t ld, int32_t d, int32_t k, int64_t subtiles_per_wave, int64_t waves_with_one_more,
     const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
@@ -180,6 +183,8 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     constexpr bool kLdsSums = KT >= 2;
     constexpr bool kBf16 = !std::is_same<XT, float>::value;
     constexpr int kElem = (int)sizeof(XT);
+    const int dr = PAD ? d : D;                  // columns that exist in memory
+    constexpr int kOutOfRange = 0x7f000000;      // a byte offset beyond any sub-tile: the load returns zeros
     constexpr int kFlush = SmallLds<D, KT>::kFlush;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
     float *lds = reinterpret_cast<float *>(dyn_lds);                       // transposition tiles | per-wave sums
@@ -228,7 +233,8 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (real) v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * D + 16 * j + 4 * g);
+                    if (real && (!PAD || 16 * j + 4 * g < dr))
+                        v = *reinterpret_cast<const f32x4 *>(C + (int64_t)cent * dr + 16 * j + 4 * g);
                     if constexpr (kBf16) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = bf16_to_f32(f32_to_bf16_rne(v[e]));
@@ -310,7 +316,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         const bool live = st < last;
         const int64_t row0 = live ? st * kSub : 0;
         const int rows_here = (int)min((int64_t)kSub, n - row0);
-        const int bytes = live ? (int)(((rows_here - 1) * ld + D) * kElem) : 0;
+        const int bytes = live ? (int)(((rows_here - 1) * ld + dr) * kElem) : 0;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<XT *>(X + row0 * ld), 0, bytes, 0x00020000);
         // STREAM: a matrix larger than the last-level cache is read with the non-temporal hint (it
@@ -319,16 +325,21 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         constexpr int kAux = STREAM ? 2 : 0;
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
+            int va = voff_a, vr = voff[q / NH];
+            if constexpr (PAD) {   // pieces whose columns do not exist
+                va = 16 * q + 4 * g < dr ? va : kOutOfRange;
+                vr = 64 * (q % NH) + 4 * c < dr ? vr : kOutOfRange;
+            }
             if constexpr (kBf16) {   // the same four columns per piece, 8 bytes of them
                 const u32x2 raw = kPointPerLane
-                                      ? __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff_a, 32 * q, kAux)
-                                      : __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff[q / NH], 128 * (q % NH), kAux);
+                                      ? __builtin_amdgcn_raw_buffer_load_b64(rsrc, va, 32 * q, kAux)
+                                      : __builtin_amdgcn_raw_buffer_load_b64(rsrc, vr, 128 * (q % NH), kAux);
                 dst[q] = f32x4{__uint_as_float(raw[0] << 16), __uint_as_float(raw[0] & 0xffff0000u),
                                __uint_as_float(raw[1] << 16), __uint_as_float(raw[1] & 0xffff0000u)};
             } else {
                 const u32x4 raw = kPointPerLane
-                                      ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_a, 64 * q, kAux)
-                                      : __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[q / NH], 256 * (q % NH), kAux);
+                                      ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, va, 64 * q, kAux)
+                                      : __builtin_amdgcn_raw_buffer_load_b128(rsrc, vr, 256 * (q % NH), kAux);
                 dst[q] = __builtin_bit_cast(f32x4, raw);
             }
         }
@@ -845,19 +856,19 @@ constexpr int kFinCols = 32;                       // columns per workgroup
 constexpr int kFinSegs = kFinBlock / (kFinCols / 4);
 constexpr int kFinBatch = kSmallMaxBlocks / kFinSegs;
 __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
-    int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
+    int32_t d_pad, int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
     const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
     double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
     int64_t *__restrict__ counts, double *__restrict__ objective) {
     __shared__ double seg_sum[kFinSegs * kFinCols];
     __shared__ unsigned long long total_cnt;
-    const int slices = d / kFinCols;
+    const int slices = d_pad / kFinCols;   // the partial sums have d_pad columns, the centroids d <= d_pad
     const int j = blockIdx.x / slices, col0 = kFinCols * (blockIdx.x % slices), t = threadIdx.x;
     const int m4 = t % (kFinCols / 4), seg = t / (kFinCols / 4);
     // every load of this thread is issued before anything is waited for
     const int32_t my_cnt = t < parts ? pcnt[(int64_t)t * k + j] : 0;
-    const float4 *col = reinterpret_cast<const float4 *>(psum + (int64_t)j * d + col0) + m4;
-    const int64_t stride4 = (int64_t)k * d / 4;
+    const float4 *col = reinterpret_cast<const float4 *>(psum + (int64_t)j * d_pad + col0) + m4;
+    const int64_t stride4 = (int64_t)k * d_pad / 4;
     float4 v[kFinBatch];
 #pragma unroll
     for (int q = 0; q < kFinBatch; ++q) {
@@ -889,7 +900,7 @@ __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
         for (int q = 1; q < kFinSegs; ++q) tot += seg_sum[q * kFinCols + t];
         const int64_t cc = (int64_t)total_cnt;
         const int64_t at = (int64_t)j * d + col0 + t;
-        C_out[at] = cc > 0 ? (float)(tot / (double)cc) : C_prev[at];
+        if (col0 + t < d) C_out[at] = cc > 0 ? (float)(tot / (double)cc) : C_prev[at];
         if (t == 0 && col0 == 0) counts[j] = cc;
     } else if (t >= 64 && t < 128 && blockIdx.x == 0 && objective) {  // second wave
         write_objective(s_part, xsq_part, parts, fresh_xsq, xsq_total, objective, t - 64);
@@ -933,37 +944,43 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
     const bool stream_x = (double)p.n * (double)p.ld * (bf16 ? 2.0 : 4.0) > kLastLevelCacheBytes;
     double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s, true);
-#define EP_SMALL_LAUNCH_T(D_, KT_, XT_)                                                                       \
+#define EP_SMALL_LAUNCH_P(D_, KT_, XT_, PAD_)                                                                 \
     do {                                                                                                      \
         constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
         const XT_ *Xt = static_cast<const XT_ *>(X);                                                          \
-        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_>                              \
-                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_>;                            \
+        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_, PAD_>                        \
+                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_, PAD_>;                      \
         if (lds_bytes > 64 * 1024)                                                                            \
             EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
         if (prof.start_)   /* timed launch: the events get the kernel's own begin and end */                \
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
-                                  p.n, p.ld, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,       \
+                                  p.n, p.ld, p.d, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,  \
                                   labels_out, labels_in, min_d2,                                              \
                                   w.psum, w.pcnt, sp, xsq_part_of(w), label_base, best_score);                \
         else                                                                                                  \
-            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, geo.subtiles_per_wave,                 \
+            kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.d, p.k, geo.subtiles_per_wave,            \
                                                        geo.waves_with_one_more, Xt, C, labels_out, labels_in, \
                                                        min_d2, w.psum, w.pcnt, sp, xsq_part_of(w),            \
                                                        label_base, best_score);                               \
+    } while (0)
+#define EP_SMALL_LAUNCH_T(D_, KT_, XT_)                                                                       \
+    do {                                                                                                      \
+        if (p.d != D_) EP_SMALL_LAUNCH_P(D_, KT_, XT_, true); else EP_SMALL_LAUNCH_P(D_, KT_, XT_, false);    \
     } while (0)
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
         if (bf16) EP_SMALL_LAUNCH_T(D_, KT_, bf16_t); else EP_SMALL_LAUNCH_T(D_, KT_, float);                 \
     } while (0)
-    if (p.d == 256) {
+    const int dpad = small_padded_d(p);
+    if (dpad == 256) {
         EP_SMALL_LAUNCH(256, 1);
-    } else if (p.d == 128) {
+    } else if (dpad == 128) {
         if (kt == 1) EP_SMALL_LAUNCH(128, 1); else if (kt == 2) EP_SMALL_LAUNCH(128, 2); else EP_SMALL_LAUNCH(128, 4);
     } else {
         if (kt == 1) EP_SMALL_LAUNCH(64, 1); else if (kt == 2) EP_SMALL_LAUNCH(64, 2); else EP_SMALL_LAUNCH(64, 4);
     }
+#undef EP_SMALL_LAUNCH_P
 #undef EP_SMALL_LAUNCH_T
 #undef EP_SMALL_LAUNCH
     EP_LAUNCH_CHECK();
@@ -973,8 +990,7 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
 }  // namespace
 
 bool small_path_supported(const ep_problem &p) {
-    const bool shape = ((p.d == 64 || p.d == 128) && p.k <= 64) || (p.d == 256 && p.k <= 16);
-    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && shape && p.ld < ((int64_t)1 << 24);
+    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && small_padded_d(p) != 0 && p.ld < ((int64_t)1 << 24);
 }
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }
@@ -1020,8 +1036,9 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
                                  const KmeansWs &w, double *objective, bool fresh_xsq, hipStream_t s) {
     const int parts = small_blocks(p);
-    lloyd_small_finalize_kernel<<<p.k * (p.d / kFinCols), kFinBlock, 0, s>>>(
-        p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
+    const int dpad = small_padded_d(p);
+    lloyd_small_finalize_kernel<<<p.k * (dpad / kFinCols), kFinBlock, 0, s>>>(
+        dpad, p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
         C_out, counts, objective);
     EP_LAUNCH_CHECK();
     return EP_OK;

@@ -79,6 +79,11 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (3000, 64, 129, False, torch.float32, None),     # two full slices and one more centroid,
     (5001, 128, 1000, True, torch.float32, None),    # 16 slices; update: segments cut in parts
     (5000, 64, 200, False, torch.float32, 68),
+    (4001, 100, 12, True, torch.float32, None),      # d not a template size: columns padded with zeros on the fly
+    (3001, 36, 40, True, torch.float32, 40),         # (d = 36 in the 64-column kernel, four centroid tiles)
+    (2999, 200, 9, True, torch.bfloat16, None),      # (d = 200 in the 256-column kernel, bfloat16)
+    (3000, 4, 3, False, torch.float32, None),
+    (5000, 96, 64, True, torch.bfloat16, 104),
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -175,6 +180,8 @@ def test_run_matches_oracle_full_size(name):
                                                (6_011, 64, 40, torch.bfloat16, 6), (6_007, 128, 24, torch.bfloat16, 6),
                                                (9_001, 256, 12, torch.float32, 6), (9_003, 256, 16, torch.bfloat16, 6),
                                                (12_345, 128, 150, torch.float32, 4), (30_011, 64, 70, torch.bfloat16, 4),
+                                               (7_001, 100, 10, torch.float32, 6), (6_001, 72, 33, torch.bfloat16, 5),
+                                               (8_001, 20, 20, torch.float32, 6),
                                                (5_000, 48, 6, torch.float32, 10)])
 def test_run_matches_oracle_other_shapes(n, d, k, dtype, iters):
     X = _mixture(n, d, min(k, 47), seed=n, relu=True, dtype=dtype)
