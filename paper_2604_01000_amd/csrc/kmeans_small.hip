@@ -1,5 +1,8 @@
-// Lloyd round for partition-scale k (k <= 64) and d in {64, 128}, fp32 embeddings: one kernel
-// reads every embedding once, finds its nearest centroid and adds it to that centroid's sum.
+// Lloyd round for partition-scale k: one kernel reads every embedding once, finds its nearest
+// centroid and adds it to that centroid's sum.  Instantiated for 64 and 128 columns (k <= 64) and
+// 256 columns (k <= 16), fp32 or bfloat16 rows; d below the instantiated width (a multiple of 4) is
+// padded with zeros as the rows are read.  The assignment-only mode also serves fp32 rows with
+// k > 64, one slice of 64 centroids per launch (launch_small_assign_sliced).
 //
 // What it computes (EmbedPart paper, Alg. 3, step P <- KMeans(E, k)): the assignment
 // argmin_j ||x - c_j||^2 = argmax_j (x.c_j - ||c_j||^2 / 2), lowest j on ties, and the per-cluster
@@ -29,6 +32,8 @@
 //   * k <= 32 runs two waves per SIMD; 32 < k <= 64 leaves room for one, and its fused loop is
 //     software-pipelined by hand (the previous sub-tile's vector work sits between the matrix
 //     instructions of the current one).
+//   * bfloat16 rows are widened to fp32 on arrival; the centroids are rounded to bfloat16 for the
+//     scores, so for k > 16 one of the six split products is left.
 //   * At the end the four waves of a workgroup add their sums in wave order through LDS and store
 //     one partial per workgroup; lloyd_small_finalize_kernel reduces those in fp64.
 #include <hip/hip_ext.h>
