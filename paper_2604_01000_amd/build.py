@@ -4,6 +4,8 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
@@ -23,9 +25,7 @@ def sources():
     return sorted(CSRC.glob("*.hip"))
 
 
-def build_lib(verbose: bool = False, extra_flags=()) -> Path:
-    """Compile every .hip file under csrc/ into one shared library (always rebuilds)."""
-    cmd = [HIPCC, *FLAGS, *extra_flags, *map(str, sources()), "-o", str(LIB)]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -35,6 +35,20 @@ def build_lib(verbose: bool = False, extra_flags=()) -> Path:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build_lib(verbose: bool = False, extra_flags=()) -> Path:
+    """Compile every .hip file under csrc/ (one hipcc per file, side by side) and link them into one
+    shared library (always rebuilds).  The objects live in a temporary folder, not in the tree."""
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="embedpart_build_") as tmp:
+        objs = [str(Path(tmp) / (src.stem + ".o")) for src in sources()]
+        with ThreadPoolExecutor(max_workers=min(8, len(objs))) as pool:
+            jobs = [pool.submit(_run, [HIPCC, *compile_flags, *extra_flags, "-c", str(src), "-o", obj], verbose)
+                    for src, obj in zip(sources(), objs)]
+            for job in jobs:
+                job.result()
+        _run([HIPCC, "--offload-arch=gfx950", "-fPIC", "-shared", *objs, "-o", str(LIB)], verbose)
     return LIB
 
 
