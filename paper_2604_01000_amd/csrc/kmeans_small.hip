@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     // accumulation.  The dropped products (ml, lm, ll) are below 2^-23 |x_i c_i|, the size of fp32
     // rounding itself.  One bf16 instruction covers 32 columns: columns 16(2s) + 4g .. + 3 and
     // 16(2s+1) + 4g .. + 3 for K-step s, the same for both operands (the reduction index is free).
-    constexpr bool kSplit = KT >= 2;
+    constexpr bool kSplit = KT >= 2 || kBf16;   // scores on the bf16 instructions (bfloat16 rows: at any k)
     constexpr int KS = D / 32;       // K-steps of the bf16 instruction
     f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
     // bfloat16 data: x is its own high term and the rounded centroid has no lower terms either, so of
