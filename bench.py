@@ -32,7 +32,7 @@ MEASURED_TRAFFIC_BYTES = {
     "arxiv_like": 90_006_646,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
     "products_like": 1_285_319_468,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
     "products_reorder": 1_149_254_277,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
-    "papers_like": 57_349_581_665,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
+    "papers_like": 57_374_169_219,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
 }
 
 
