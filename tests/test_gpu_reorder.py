@@ -71,6 +71,19 @@ def test_reorder_long_rows_empty_rows_and_ragged_windows(i64):
         _check(rowptr, colidx, labels, k)
 
 
+def test_reorder_one_very_long_row():
+    """A vertex joined to 300,001 others (19 LDS tiles, five levels of merging on global memory) among
+    short rows, int64 offsets."""
+    rng = np.random.default_rng(31)
+    n = 400_000
+    deg = rng.integers(0, 6, n)
+    deg[123_456] = 300_001
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    colidx = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
+    labels = rng.integers(0, 50, n).astype(np.int32)
+    _check(torch.from_numpy(rowptr), torch.from_numpy(colidx), labels, 50)
+
+
 def test_reorder_small_and_degenerate():
     rng = np.random.default_rng(23)
     # one vertex with a self-loop; two vertices; no edges at all; one entry
