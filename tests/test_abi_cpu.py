@@ -242,3 +242,15 @@ def test_cluster_and_balance_rejects_bad_arguments():
     assert call(bytes=need - 1) == ep.EP_EWORKSPACE
     big = ep.ep_problem(5000, 64, 64, 300, ep.EP_F32, 0)
     assert call(p=big) == ep.EP_EUNSUPPORTED                                  # balancing: partition-scale k only
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark covers one GPU; asking for more ends with a message and a non-zero status before
+    anything touches a device."""
+    import subprocess
+    import sys
+    from pathlib import Path
+    bench = Path(__file__).resolve().parents[1] / "bench.py"
+    proc = subprocess.run([sys.executable, str(bench), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert proc.returncode != 0
+    assert "ONE GPU" in (proc.stderr + proc.stdout)
