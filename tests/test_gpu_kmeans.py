@@ -15,7 +15,7 @@ import oracle
 from paper_2604_01000_amd import embedpart as ep
 from paper_2604_01000_amd import synth
 
-from parity import (CENTROID_RTOL, DEV, Kmeans, centroid_rel_err, centroids_used, check_free_running, label_mismatches,
+from parity import (CENTROID_RTOL, DEV, Graph, Kmeans, centroid_rel_err, centroids_used, check_free_running, label_mismatches,
                     to_np32)
 
 pytestmark = pytest.mark.gpu
@@ -299,3 +299,32 @@ def test_sampled_run_matches_oracle(n, d, k, dtype, per_cluster, iters):
     if centroid_rel_err(got_C, orc["C"]) <= CENTROID_RTOL:
         np.testing.assert_array_equal(counts.cpu().numpy(), orc["counts"])
         assert np.count_nonzero(got_labels != orc["labels"]) <= max(3, n // 2000)
+
+
+def test_calls_run_on_the_callers_stream():
+    """Everything is enqueued on the stream the caller names: a run on a side stream (default priority),
+    with no device-wide synchronisation before its results are used on that same stream, equals the run
+    on the default stream."""
+    w = synth.WORKLOADS["tiny"]
+    X = synth.embeddings(w, DEV)
+    rowptr, colidx, _ = synth.sbm_graph(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    ref = Kmeans(X, w.k).init(idx).run(w.iters)
+    gr = Graph(rowptr, colidx, k_max=w.k)
+    cut_ref, sizes_ref = gr.quality(torch.from_numpy(ref["labels"]).to(DEV), w.k)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        km = Kmeans(X, w.k)
+        km.init(idx)
+        hist = torch.zeros(w.iters + 1, dtype=torch.float64, device=DEV)
+        ep.kmeans_run(km.p, km.X, w.iters, km.C, km.labels, km.counts, hist, 0, km.ws)
+        cut = torch.zeros(1, dtype=torch.int64, device=DEV)
+        sizes = torch.zeros(w.k, dtype=torch.int64, device=DEV)
+        ep.partition_quality(gr.n, gr.nnz, w.k, gr.rowptr, gr.colidx, km.labels, cut, sizes, gr.ws)
+        labels_side = km.labels.clone()
+    side.synchronize()
+    np.testing.assert_array_equal(labels_side.cpu().numpy(), ref["labels"])
+    np.testing.assert_array_equal(km.C.cpu().numpy(), ref["C"])
+    assert int(cut.item()) == cut_ref
+    np.testing.assert_array_equal(sizes.cpu().numpy(), sizes_ref)
