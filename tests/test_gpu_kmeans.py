@@ -328,3 +328,30 @@ def test_calls_run_on_the_callers_stream():
     np.testing.assert_array_equal(km.C.cpu().numpy(), ref["C"])
     assert int(cut.item()) == cut_ref
     np.testing.assert_array_equal(sizes.cpu().numpy(), sizes_ref)
+
+
+def test_kmeans_run_can_be_captured_in_a_graph():
+    """kmeans_run allocates nothing, copies nothing from the host and never synchronises, so a stream
+    capture can record it; every replay (with eager work and synchronisations in between) must give the
+    eager result."""
+    w = synth.WORKLOADS["tiny"]
+    X = synth.embeddings(w, DEV)
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    ref = Kmeans(X, w.k).init(idx).run(w.iters)
+    km = Kmeans(X, w.k).init(idx)
+    C0 = km.C.clone()
+    hist = torch.zeros(w.iters + 1, dtype=torch.float64, device=DEV)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ep.kmeans_run(km.p, km.X, w.iters, km.C, km.labels, km.counts, hist, 0, km.ws)
+    for replay in range(3):
+        km.C.copy_(C0)                                     # eager work between the replays
+        km.labels.fill_(-3)
+        hist.fill_(0.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(km.labels.cpu().numpy(), ref["labels"], err_msg=f"replay {replay}")
+        np.testing.assert_array_equal(km.C.cpu().numpy(), ref["C"])
+        np.testing.assert_array_equal(hist.cpu().numpy()[:w.iters], ref["obj_hist"][:w.iters])
