@@ -196,10 +196,30 @@ __global__ __launch_bounds__(kBlock) void edge_block_sweep_kernel(int64_t n, int
             }
             return c;
         };
+        // The attribute of an entry's column is a random gather: the gathers of step s + 1 are issued (all
+        // four of a lane at once, unconditionally, with the index clamped into range) before step s
+        // is worked on, and the entries of step s + 2 are loaded, so a lane has 8 gathers and one
+        // 16-byte load in flight instead of one gather at a time.
+        struct Gathered {
+            int32_t a[4];
+        };
+        auto gather4 = [&](const i32x4 &c) {
+            Gathered gt;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int32_t v = c[t];
+                const int32_t vi = (v >= 0 && v < n) ? v : 0;
+                gt.a[t] = attr ? (int32_t)attr[vi] : vi;
+            }
+            return gt;
+        };
         i32x4 cur = load4(start + 4 * lane);
+        i32x4 nxt = load4(start + 256 + 4 * lane);
+        Gathered gcur = gather4(cur);
         for (int64_t p0 = start; p0 < e_end; p0 += 256) {
             const int64_t p = p0 + 4 * lane;
-            const i32x4 nxt = load4(p + 256);
+            const i32x4 nn = load4(p + 512);
+            const Gathered gnxt = gather4(nxt);
             // j = row (relative to r0) of entry max(p, e_begin): the number of row ends <= it
             int j = 0;
             {
@@ -223,7 +243,7 @@ __global__ __launch_bounds__(kBlock) void edge_block_sweep_kernel(int64_t n, int
                     }
                     const int32_t v = cur[t];
                     if (v >= 0 && v < n) {
-                        const int64_t av = attr ? (int64_t)attr[v] : (int64_t)v;
+                        const int64_t av = (int64_t)gcur.a[t];
                         if (OP == kCut) {
                             const bool ok = sizeof(AttrT) == 1 ? (au != 255 && av != 255)
                                                                : (au >= 0 && au < k && av >= 0 && av < k);
@@ -236,6 +256,8 @@ __global__ __launch_bounds__(kBlock) void edge_block_sweep_kernel(int64_t n, int
             }
             if (OP == kCut) wave_cut += hits;
             cur = nxt;
+            gcur = gnxt;
+            nxt = nn;
         }
         __builtin_amdgcn_wave_barrier();
     }
