@@ -20,8 +20,9 @@
  *     256-byte aligned and at least as large as the matching *_workspace_bytes
  *     call reports.  The library allocates nothing, frees nothing and keeps no
  *     pointer after a call returns.  Its only global state is the code of the
- *     last failing HIP call (ep_last_hip_error) and the benchmark aid
- *     ep_profile_arm at the end of this file.
+ *     last failing HIP call (ep_last_hip_error), the static workspace of
+ *     kmeans_run_noalloc and the benchmark aid ep_profile_arm at the end of this
+ *     file.
  *   - Partition / cluster ids are 0-based, in [0, k).  (The paper numbers
  *     partitions 1..k.)
  *   - Return value: EP_OK (0) or a negative EP_E* code.  Arguments are checked
@@ -143,6 +144,25 @@ int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels,
 int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
                int32_t *labels, int64_t *counts, double *objective_hist, int flags,
                void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * kmeans_run for callers that cannot allocate device memory or carry a workspace: code under
+ * stream capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results (bit for bit) as kmeans_run, without `ws`: the workspace is a static device array
+ * of EP_NOALLOC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until
+ * the process ends.  The call allocates and frees nothing.
+ *   Limit: kmeans_workspace_bytes(p) <= EP_NOALLOC_SCRATCH_BYTES, else EP_EWORKSPACE.  Every shape of
+ *   the fused kernels (k <= 64 with d <= 128, k <= 16 with d <= 256, any n) fits; other shapes fit
+ *   for small n only, because their workspace grows with n.
+ *   The array is looked up once per device, at the first call made with that device current; the
+ *   current device must be the one `stream` belongs to.
+ *   All calls on one GPU share the array and it keeps the last call's contents (no call relies on
+ *   them): two calls whose work overlaps on one GPU (different streams, or threads) race.
+ */
+#define EP_NOALLOC_SCRATCH_BYTES (34 * 1024 * 1024)
+int kmeans_run_noalloc(const ep_problem *p, const void *X, int32_t iters, float *C,
+                       int32_t *labels, int64_t *counts, double *objective_hist, int flags,
+                       void *stream);
 
 /*
  * Sample-trained K-Means: the clustering as the paper's Sec. "Implementation" runs it. The

@@ -1,6 +1,7 @@
 // C-ABI entry points of libembedpart: argument checks on the host, then kernel launches.
 // See include/embedpart.h for the contract of every call.
 #include <atomic>
+#include <mutex>
 
 #include "kernels.h"
 
@@ -126,6 +127,31 @@ SampledWs carve_sampled_ws(const ep_problem &p, int64_t m, void *ws) {
     return w;
 }
 
+// ---- kmeans_run_noalloc: the K-Means workspace as a static device array ---------------------------
+// Every GPU the library runs on holds its own copy of this array at its own address.  The array's
+// name is only a host-side handle: host code never passes it anywhere but to hipGetSymbolAddress,
+// and uses the per-device address that call returns (g_scratch_ptr) for kernel arguments.
+static __device__ __align__(256) unsigned char scratch[EP_NOALLOC_SCRATCH_BYTES];
+constexpr int kScratchMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kScratchMaxDevices] = {};
+
+// Address of `scratch` on the current device (looked up once per device, with that device current).
+int scratch_of_current_device(void **out) {
+    int dev = -1;
+    EP_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchMaxDevices) return EP_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        EP_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return EP_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return EP_OK;
+}
+
 }  // namespace
 }  // namespace ep
 
@@ -232,6 +258,22 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int3
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return run_rounds(*p, X, iters, C, labels, counts, objective_hist, flags, w, s);
+}
+
+int kmeans_run_noalloc(const ep_problem *p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
+                       double *objective_hist, int flags, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if ((rc = check_x(p, X)) != EP_OK) return rc;
+    if (!C || !labels || !aligned(labels, 16) || !counts || iters < 0 || (flags & ~EP_RUN_FINAL_REASSIGN))
+        return EP_EINVAL;
+    // the problem must fit the static array: nothing is allocated to make room
+    if (carve_kmeans_ws(*p, nullptr).bytes > (size_t)EP_NOALLOC_SCRATCH_BYTES) return EP_EWORKSPACE;
+    void *ws = nullptr;
+    if ((rc = scratch_of_current_device(&ws)) != EP_OK) return rc;
+    // no part of the workspace has to start at zero: every kernel of a round writes what the next reads
+    return run_rounds(*p, X, iters, C, labels, counts, objective_hist, flags, carve_kmeans_ws(*p, ws),
+                      static_cast<hipStream_t>(stream));
 }
 
 int kmeans_sampled_workspace_bytes(const ep_problem *p, int64_t m, size_t *bytes_host) {

@@ -21,10 +21,12 @@ EP_RUN_FINAL_REASSIGN = 1
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
 EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the header
 EP_BALANCE_MAX_K, EP_BALANCE_MAX_ROUNDS = 255, 1024
+EP_NOALLOC_SCRATCH_BYTES = 34 * 1024 * 1024
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
-    "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_sampled_workspace_bytes",
+    "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_run_noalloc",
+    "kmeans_sampled_workspace_bytes",
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
     "balance_workspace_bytes", "partition_balance", "graph_reorder_workspace_bytes", "graph_reorder",
@@ -71,6 +73,7 @@ def lib() -> C.CDLL:
         L.kmeans_assign.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.kmeans_update.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.kmeans_run.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+        L.kmeans_run_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp]
         L.kmeans_sampled_workspace_bytes.argtypes = [pp, i64, C.POINTER(sz)]
         L.kmeans_run_sampled.argtypes = [pp, vp, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.graph_workspace_bytes.argtypes = [i64, i64, i32, C.POINTER(sz)]
@@ -171,6 +174,11 @@ def kmeans_update(p, X, labels, C_prev, C_out, counts, ws):
 def kmeans_run(p, X, iters, Cc, labels, counts, objective_hist, flags, ws):
     _check(lib().kmeans_run(C.byref(p), _ptr(X), iters, _ptr(Cc), _ptr(labels), _ptr(counts), _ptr(objective_hist),
                             flags, _ptr(ws), ws.numel(), _stream()), "kmeans_run")
+
+
+def kmeans_run_noalloc(p, X, iters, Cc, labels, counts, objective_hist, flags):
+    _check(lib().kmeans_run_noalloc(C.byref(p), _ptr(X), iters, _ptr(Cc), _ptr(labels), _ptr(counts),
+                                    _ptr(objective_hist), flags, _stream()), "kmeans_run_noalloc")
 
 
 def kmeans_sampled_workspace_bytes(p: ep_problem, m: int) -> int:
