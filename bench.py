@@ -4,20 +4,30 @@
 A step is one pass of the whole hot path over one batch of synthetic input that is already
 resident in HBM: seeded initial centroids, `iters` Lloyd rounds (kmeans_run), the integer
 partition-quality sweep over the CSR graph (partition_quality) and, for the reordering
-workload, the partition-sorted relabelling and its edge-gap sum.  The headline value is
+workload, the partition-sorted relabelling and its edge-gap sum.  The value is
 point-iterations per second over whole steps (n * iters / step time).
 
-Prints ONE JSON line.  `roofline` describes the kernel that reads X in every Lloyd round, timed
-with HIP events that the library hands to each of its launches (ep_profile_arm; the launch stamps
-them with the kernel's own begin and end) in a second pass of the same steps, so that the events
-do not perturb the headline timing.  `cpu_baseline` is the fp64
-oracle timed on this machine's host cores.
+Prints ONE JSON line.  The headline is the largest configuration that fits one GPU
+(`papers_like`: 111 M x 128 fp32, k = 64); the other four configurations of the benchmark
+definition follow under `more`, each a complete line of its own with fewer timed steps.
+Every line carries
+  roofline      the kernel that reads X in every Lloyd round, timed with HIP events that the
+                library hands to each of its launches (the launch stamps them with the
+                kernel's own begin and end) in a further pass of the same steps, so that the
+                events do not perturb the step timing;
+  edge_sweep    the same for the CSR sweep of partition_quality (and edge_gap_sum);
+  cpu_baseline  the fp64 oracle timed on this machine's host cores, at all cores and at one
+                thread, on a contiguous slice of the same rows sized for a few seconds each.
+`traffic` is the HBM byte count of the kernel from the rocprofv3 counter summary under
+profiles/ that `traffic_source` names (null when there is none): it is read from that file,
+not measured by this run.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes as C
 import json
+import re
 import sys
 import time
 from pathlib import Path
@@ -26,14 +36,23 @@ ROOT = Path(__file__).resolve().parent
 sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the roofline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/), scaled by the copy-kernel calibration; None where not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "arxiv_like": 90_006_646,            # profiles/lloyd_small_kernel_arxiv_like_hbm_traffic.txt
-    "products_like": 1_285_319_468,      # profiles/lloyd_small_kernel_products_like_hbm_traffic.txt
-    "products_reorder": 1_149_254_277,   # profiles/large_assign_kernel_products_reorder_hbm_traffic.txt
-    "papers_like": 57_374_169_219,       # profiles/lloyd_small_kernel_papers_like_hbm_traffic.txt
-}
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix rate
+LLC_BYTES = 256 * 1024 * 1024  # memory-side cache: a matrix below this is not served by HBM after round 1
+
+HEADLINE = "papers_like"
+OTHERS = "tiny,arxiv_like,products_like,products_reorder"
+# timed steps of the workloads under `more` (the headline takes --steps / --warmup)
+MORE_STEPS = {"tiny": (50, 5), "arxiv_like": (20, 3), "products_like": (10, 2), "products_reorder": (3, 1),
+              "papers_like": (3, 1)}
+
+
+def profile_traffic(kernel: str, workload: str):
+    """(bytes per launch, file) from the counter summary of `kernel` on `workload` under profiles/."""
+    path = ROOT / "profiles" / f"{kernel}_{workload}_hbm_traffic.txt"
+    if not path.exists():
+        return None, None
+    m = re.search(r"^traffic_bytes_per_launch\[" + re.escape(kernel) + r"\]\s*=\s*(\d+)", path.read_text(), re.M)
+    return (int(m.group(1)), f"profiles/{path.name}") if m else (None, None)
 
 
 class HipEvents:
@@ -59,7 +78,56 @@ class HipEvents:
             self.hip.hipEventDestroy(C.c_void_p(ev))
 
 
-def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variants: bool = True) -> dict:
+def oracle_baseline(w, X, idx, seconds: float) -> dict:
+    """The oracle's Lloyd rounds (assignment, then update, against all k centroids) on the first rows
+    of the workload, at all cores and at one thread.
+
+    The slice is sized from a short probe so that each of the two timings takes about `seconds`;
+    the full-size figure is an extrapolation (the oracle's cost is linear in the rows) and is
+    labelled as one."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    bf16 = w.dtype == "bf16"
+    cores = oracle.threads()
+    C0 = X[idx.to(X.device)].to("cpu", torch.float32).numpy().astype(np.float64)   # the workload's initial centroids
+
+    def timed(rows: int, iters: int, threads: int) -> float:
+        Xs = X[:rows].to("cpu", torch.float32).numpy()
+        Cc = C0
+        oracle.set_threads(threads)
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            labels, _, _, _ = oracle.assign(Xs, Cc, round_bf16=bf16)
+            Cc, _, _ = oracle.update(Xs, labels, Cc)
+        dt = time.perf_counter() - t0
+        oracle.set_threads(cores)
+        return dt
+
+    out = {}
+    for threads in (cores, 1):
+        probe_rows = int(min(w.n, max(64, 2_000_000_000 // (w.k * w.d * 40)) * threads))
+        per_point_iter = max(timed(probe_rows, 1, threads), 1e-4) / probe_rows
+        iters = w.iters if per_point_iter * w.iters * 4096 < seconds else 1
+        rows = int(min(w.n, max(64, seconds / (per_point_iter * iters))))
+        dt, runs = timed(rows, iters, threads), 1
+        while dt < 0.5 * seconds and runs < 200:     # a workload shorter than the budget is repeated
+            dt += timed(rows, iters, threads)
+            runs += 1
+        out[threads] = dict(rate=runs * rows * iters / dt / 1e6, rows=rows, iters=iters, seconds=dt, runs=runs)
+    a, one = out[cores], out[1]
+    return dict(value=a["rate"], unit="Mpts*iter/s", cores=cores, kind="oracle",
+                value_1_thread=one["rate"],
+                sample=f"Lloyd rounds (assign + update, all k={w.k} centroids) on the first {a['rows']} rows x {a['iters']} "
+                       f"round(s) x {a['runs']} run(s), {a['seconds']:.1f} s at {cores} threads; first {one['rows']} rows x "
+                       f"{one['iters']} round(s) x {one['runs']} run(s), {one['seconds']:.1f} s at 1 thread",
+                full_size_seconds_extrapolated=dict(all_cores=w.n * w.iters / (a["rate"] * 1e6),
+                                                    one_thread=w.n * w.iters / (one["rate"] * 1e6)))
+
+
+def run_workload(name: str, steps: int, warmup: int, cpu_seconds: float, variants: bool = True) -> dict:
     import numpy as np
     import torch
 
@@ -109,12 +177,12 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
     ms_per_step = 1e3 * elapsed / steps
     value = w.n * w.iters / (elapsed / steps) / 1e6
 
-    def timed_kernels(kernel_class: int, launches_per_step: int) -> float:
-        """Mean duration (ms) of one kernel class over a further pass of the same steps."""
-        launches = steps * launches_per_step
+    def timed_kernels(kernel_class: int, launches_per_step: int, passes: int) -> float:
+        """Mean duration (ms) of one kernel class over further passes of the same step."""
+        launches = passes * launches_per_step
         evs = HipEvents(2 * launches)
         assert ep.lib().ep_profile_arm(evs.arr, 2 * launches, kernel_class) == 0
-        for _ in range(steps):
+        for _ in range(passes):
             step()
         torch.cuda.synchronize()
         seen = ep.lib().ep_profile_count()
@@ -125,11 +193,12 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
         return ms
 
     # ---- further passes of the same steps with events around one kernel class at a time ----
-    kernel_ms = timed_kernels(ep.EP_PROF_LLOYD_MAIN, w.iters)
-    sweep_ms = timed_kernels(ep.EP_PROF_EDGE_SWEEP, 2 if reorder else 1)
+    passes = min(steps, 20)
+    kernel_ms = timed_kernels(ep.EP_PROF_LLOYD_MAIN, w.iters, passes)
+    sweep_ms = timed_kernels(ep.EP_PROF_EDGE_SWEEP, 2 if reorder else 1, passes)
 
     # ---- the variant the paper runs: centroids trained on 2^9 rows per cluster, then one assignment of
-    # ---- every row (kmeans_run_sampled); timed beside the headline, not part of it ----
+    # ---- every row (kmeans_run_sampled); timed beside the step, not part of it ----
     sampled = None
     m = min(w.n, 512 * w.k)
     if variants and m < w.n:
@@ -146,12 +215,12 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
         sampled = dict(sample_rows=m, iters=w.iters, ms=sampled_ms, Mpts_per_s=w.n / (sampled_ms * 1e-3) / 1e6,
                        objective=float(hist[w.iters].item()))
         del sws
-        # leave labels / counts / hist as the headline run produced them
+        # leave labels / counts / hist as the step produces them
         step()
         torch.cuda.synchronize()
 
     # ---- the balancing loops of the paper's Alg. 3 on the K-Means partition (partition-scale k only):
-    # ---- three vertex classes (seeded: 55% / 15% / 30%), beta = 1.05, timed beside the headline ----
+    # ---- three vertex classes (seeded: 55% / 15% / 30%), beta = 1.05, timed beside the step ----
     balance = None
     if variants and w.k <= ep.EP_BALANCE_MAX_K:
         g = torch.Generator(device="cpu").manual_seed(w.seed + 7)
@@ -186,7 +255,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
         del bws, blabels, vclass
 
     # ---- the graph rewritten under the new ids (the step that makes the reordering usable by a trainer),
-    # ---- timed beside the headline on the reordering workload; the metrics must carry over ----
+    # ---- timed beside the step on the reordering workload; the metrics must carry over ----
     rewrite = None
     if variants and reorder:
         rws = ep.workspace(ep.graph_reorder_workspace_bytes(w.n, nnz), dev)
@@ -222,18 +291,30 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
     elem = 2 if w.dtype == "bf16" else 4
     if reorder:   # dense contraction on the matrix cores: 2*n*k*d flop per launch
         flop = 2.0 * w.n * w.k * w.d
-        roofline = dict(bound="mfma", achieved=flop / (kernel_ms * 1e-3) / 1e12, peak=2500.0, unit="TFLOP/s")
+        main_kernel = "large_assign_kernel"
+        roofline = dict(bound="mfma", achieved=flop / (kernel_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS,
+                        unit="TFLOP/s", algorithmic_flop_per_launch=flop)
     else:         # streaming: X read once + one int32 label per point
         nbytes = w.n * (w.d * elem + 4)
-        roofline = dict(bound="hbm", achieved=nbytes / (kernel_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+        main_kernel = "lloyd_small_kernel"
+        roofline = dict(bound="hbm", achieved=nbytes / (kernel_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                        algorithmic_bytes_per_launch=nbytes)
+        if x_bytes <= LLC_BYTES:
+            roofline["note"] = ("the matrix fits the 256 MB memory-side cache and is served from it after the first "
+                                "round: the HBM peak is not this launch's bound, the fraction is quoted for reference")
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
+    roofline["traffic"], roofline["traffic_source"] = profile_traffic(main_kernel, w.name)
     roofline["kernel_ms"] = kernel_ms
-    roofline["kernel"] = "lloyd round kernel that reads X (EP_PROF_LLOYD_MAIN)"
+    roofline["kernel"] = main_kernel + ": the kernel that reads X in every Lloyd round"
+    # CSR sweep: 4 B per stored entry + the offsets + one label (or new id) per vertex, once
     sweep_bytes = 4 * nnz + rowptr.element_size() * (w.n + 1) + 4 * w.n
-    reference = dict(copy_GBs=2 * x_bytes / (copy_ms * 1e-3) / 1e9, copy_bytes_moved=2 * x_bytes,
-                     edge_sweep_ms=sweep_ms, edge_sweep_GBs=sweep_bytes / (sweep_ms * 1e-3) / 1e9,
-                     edge_sweep_Gentries_per_s=nnz / (sweep_ms * 1e-3) / 1e9)
+    edge_sweep = dict(bound="hbm", achieved=sweep_bytes / (sweep_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                      algorithmic_bytes_per_launch=sweep_bytes, kernel_ms=sweep_ms,
+                      Gentries_per_s=nnz / (sweep_ms * 1e-3) / 1e9,
+                      kernel="edge_block_sweep_kernel" + (": mean of the cut sweep and the gap sweep" if reorder else ""))
+    edge_sweep["frac"] = edge_sweep["achieved"] / edge_sweep["peak"]
+    edge_sweep["traffic"], edge_sweep["traffic_source"] = profile_traffic("edge_block_sweep_kernel", w.name)
+    reference = dict(copy_GBs=2 * x_bytes / (copy_ms * 1e-3) / 1e9, copy_bytes_moved=2 * x_bytes)
 
     torch.cuda.synchronize()
     result_labels = labels.cpu().numpy()
@@ -243,25 +324,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
         quality["mean_edge_gap"] = (int(gap.item()) & (2**64 - 1)) / max(nnz, 1)
 
     # ---- the oracle on this machine's host cores ----
-    cpu = None
-    if cpu_baseline:
-        import oracle
-        sample_n = min(w.n, 1 << 18 if w.k > 64 else 1 << 22)
-        sample_iters = w.iters if w.k <= 64 else 1
-        Xs = X[:sample_n].to("cpu", torch.float32).numpy()
-        kk = min(w.k, sample_n)
-        idx = oracle.init_indices(w.seed, sample_n, kk)
-        flags = oracle.FLAG_BF16_CENTROIDS if w.dtype == "bf16" else 0
-        runs, spent = 0, 0.0
-        while runs == 0 or (spent < 10.0 and runs < 100):     # short workloads are repeated: ~10 s of CPU work
-            t0 = time.perf_counter()
-            oracle.lloyd(Xs, kk, sample_iters, idx, flags=flags)
-            spent += time.perf_counter() - t0
-            runs += 1
-        cpu = dict(value=runs * sample_n * sample_iters / spent / 1e6, unit="Mpts*iter/s", cores=oracle.threads(),
-                   kind="oracle",
-                   sample=f"first {sample_n} rows of the workload, k={kk}, {sample_iters} Lloyd rounds, "
-                          f"{runs} run(s), {spent:.1f} s in all")
+    cpu = oracle_baseline(w, X, idx, cpu_seconds) if cpu_seconds > 0 else None
 
     return dict(metric="kmeans_point_iterations_per_s", value=value, unit="Mpts*iter/s", n_gpus=1, steps=steps,
                 warmup=warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
@@ -269,23 +332,26 @@ def run_workload(name: str, steps: int, warmup: int, cpu_baseline: bool, variant
                 config=dict(workload=w.name, n=w.n, d=w.d, k=w.k, iters=w.iters, nnz=nnz,
                             step="kmeans_init + kmeans_run + partition_quality" +
                                  (" + partition_permutation + edge_gap_sum" if reorder else "")),
-                roofline=roofline, cpu_baseline=cpu, reference=reference, quality=quality, sampled_variant=sampled, balance_variant=balance,
-                reorder_variant=rewrite,
+                roofline=roofline, edge_sweep=edge_sweep, cpu_baseline=cpu, reference=reference, quality=quality,
+                sampled_variant=sampled, balance_variant=balance, reorder_variant=rewrite,
                 labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="arxiv_like",
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=HEADLINE,
                     help="tiny | arxiv_like | products_like | products_reorder | papers_like")
-    ap.add_argument("--also", default="products_like",
-                    help="comma-separated further workloads reported under 'more' (fewer steps); '' for none")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads reported under 'more'; '' for none "
+                         "(default: the other four configurations)")
+    ap.add_argument("--cpu-seconds", type=float, default=4.0,
+                    help="CPU time of each oracle timing (two per workload: all cores, one thread); 0 = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
-                    help="skip the sample-trained and the balancing legs (for profiles of the headline kernels alone)")
+                    help="skip the sample-trained, balancing and graph-rewrite legs (for profiles of the step's kernels alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -293,11 +359,14 @@ def main() -> int:
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    out = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, not args.no_variants)
+    cpu_seconds = 0.0 if args.no_cpu_baseline else args.cpu_seconds
+    also = OTHERS if args.also is None else args.also
+    out = run_workload(args.workload, args.steps, args.warmup, cpu_seconds, not args.no_variants)
     more = []
-    for name in [v for v in args.also.split(",") if v and v != args.workload]:
+    for name in [v for v in also.split(",") if v and v != args.workload]:
         torch.cuda.empty_cache()
-        more.append(run_workload(name, max(3, args.steps // 4), 1, False, not args.no_variants))
+        s, wu = MORE_STEPS[name]
+        more.append(run_workload(name, s, wu, cpu_seconds, not args.no_variants))
     if more:
         out["more"] = more
     print(json.dumps(out))

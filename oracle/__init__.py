@@ -84,6 +84,13 @@ def threads() -> int:
     return int(v) if v else (os.cpu_count() or 1)
 
 
+def set_threads(count: int) -> None:
+    """Number of OpenMP threads of the following calls (timing aid of the benchmark's CPU baseline:
+    the arithmetic and its order inside a thread's share do not depend on it)."""
+    lib()
+    C.CDLL("libgomp.so.1").omp_set_num_threads(int(count))
+
+
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 

@@ -1,5 +1,6 @@
 // C-ABI entry points of libembedpart: argument checks on the host, then kernel launches.
 // See include/embedpart.h for the contract of every call.
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 
@@ -122,7 +123,12 @@ SampledWs carve_sampled_ws(const ep_problem &p, int64_t m, void *ws) {
     w.S = c.take<unsigned char>((size_t)m * (size_t)w.ld_s * (p.dtype == EP_BF16 ? 2 : 4));
     w.rows = c.take<int64_t>((size_t)m);
     w.labels = c.take<int32_t>((size_t)m);
-    w.km = c.take<unsigned char>(carve_kmeans_ws(p, nullptr).bytes);
+    // one K-Means workspace serves the sample's rounds (m dense rows of stride ld_s) and then the
+    // assignment of all n rows: the two shapes can take different kernels, so it is sized for both
+    ep_problem ps = p;
+    ps.n = m;
+    ps.ld = w.ld_s;
+    w.km = c.take<unsigned char>(std::max(carve_kmeans_ws(p, nullptr).bytes, carve_kmeans_ws(ps, nullptr).bytes));
     w.bytes = align_up(c.used, 256);
     return w;
 }

@@ -312,17 +312,21 @@ int launch_sweep_rows(int64_t n, int64_t nnz, int32_t k, const void *rowptr, boo
 constexpr int kRadix = 256;
 constexpr int kSortWaves = kBlock / 64;
 
+// clamp_k > 0: the keys are labels, and a label outside [0, clamp_k) sorts as clamp_k, behind every valid one.
 __device__ __forceinline__ int32_t sort_key(const int32_t *__restrict__ labels, const int32_t *__restrict__ order_in,
-                                            int64_t i, int shift, int32_t *vertex) {
+                                            int64_t i, int shift, uint32_t clamp_k, int32_t *vertex) {
     const int32_t v = order_in ? order_in[i] : (int32_t)i;
     *vertex = v;
-    return (int32_t)(((uint32_t)labels[v] >> shift) & (kRadix - 1));
+    uint32_t key = (uint32_t)labels[v];
+    if (clamp_k) key = min(key, clamp_k);   // a negative label is a large unsigned one
+    return (int32_t)((key >> shift) & (kRadix - 1));
 }
 
 __global__ __launch_bounds__(kBlock) void sort_hist_kernel(int64_t n, int64_t rows_per_block,
                                                             const int32_t *__restrict__ labels,
                                                             const int32_t *__restrict__ order_in, int shift,
-                                                            int32_t *__restrict__ hist, const int *__restrict__ enable) {
+                                                            uint32_t clamp_k, int32_t *__restrict__ hist,
+                                                            const int *__restrict__ enable) {
     if (enable && !*enable) return;   // uniform over the grid: a sort whose result nobody will use
     __shared__ int32_t h[kRadix];
     h[threadIdx.x] = 0;
@@ -330,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void sort_hist_kernel(int64_t n, int64_t ro
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
     for (int64_t i = b + threadIdx.x; i < e; i += kBlock) {
         int32_t v;
-        atomicAdd(&h[sort_key(labels, order_in, i, shift, &v)], 1);
+        atomicAdd(&h[sort_key(labels, order_in, i, shift, clamp_k, &v)], 1);
     }
     __syncthreads();
     hist[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];  // digit-major
@@ -369,6 +373,7 @@ __global__ __launch_bounds__(kRadix) void sort_scan_kernel(int32_t *__restrict__
 __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(int64_t n, int64_t rows_per_block,
                                                                const int32_t *__restrict__ labels,
                                                                const int32_t *__restrict__ order_in, int shift,
+                                                               uint32_t clamp_k,
                                                                const int32_t *__restrict__ offsets,
                                                                const int32_t *__restrict__ digit_total,
                                                                int32_t *__restrict__ order_out,
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(int64_t n, int64_t
         const int64_t i = tile + t;
         const bool valid = i < e;
         int32_t v = 0;
-        const int32_t key = valid ? sort_key(labels, order_in, i, shift, &v) : 0;
+        const int32_t key = valid ? sort_key(labels, order_in, i, shift, clamp_k, &v) : 0;
         // lanes of this wave that hold the same digit
         uint64_t peers = __ballot(valid);
         for (int bit = 0; bit < 8; ++bit) {
@@ -477,8 +482,8 @@ int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const 
                : launch_sweep_rows<int32_t, kBandwidth>(n, nnz, 0, rowptr, i64, colidx, new_id, out, s);
 }
 
-int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
-                       int32_t *hist, const int *enable, hipStream_t s) {
+static int sort_passes(int64_t n, int passes, uint32_t clamp_k, const int32_t *keys, int32_t *new_id, int32_t *order,
+                       int32_t *tmp, int32_t *hist, const int *enable, hipStream_t s) {
     int64_t rows_per_block = std::max<int64_t>(ceil_div(n, kSortBlocksMax), 2048);
     rows_per_block = ceil_div(rows_per_block, kBlock) * kBlock;
     const int blocks = (int)ceil_div(n, rows_per_block);
@@ -487,11 +492,11 @@ int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_
     for (int pass = 0; pass < passes; ++pass) {
         int32_t *dst = (passes - pass) % 2 == 1 ? order : tmp;
         const bool last = pass == passes - 1;
-        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist, enable);
+        sort_hist_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, clamp_k, hist, enable);
         EP_LAUNCH_CHECK();
         sort_scan_kernel<<<kRadix, kRadix, 0, s>>>(hist, blocks, hist + (size_t)kSortBlocksMax * kRadix, enable);
         EP_LAUNCH_CHECK();
-        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, hist,
+        sort_scatter_kernel<<<blocks, kBlock, 0, s>>>(n, rows_per_block, keys, src, 8 * pass, clamp_k, hist,
                                                       hist + (size_t)kSortBlocksMax * kRadix, dst,
                                                       last ? new_id : nullptr, enable);
         EP_LAUNCH_CHECK();
@@ -500,9 +505,16 @@ int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_
     return EP_OK;
 }
 
+int launch_sort_by_key(int64_t n, int passes, const int32_t *keys, int32_t *new_id, int32_t *order, int32_t *tmp,
+                       int32_t *hist, const int *enable, hipStream_t s) {
+    return sort_passes(n, passes, 0, keys, new_id, order, tmp, hist, enable, s);
+}
+
 int launch_sort_by_label(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order,
                          int32_t *tmp, int32_t *hist, hipStream_t s) {
-    return launch_sort_by_key(n, k <= kRadix ? 1 : 2, labels, new_id, order, tmp, hist, nullptr, s);   // k <= 65536
+    // keys 0 .. k (k = "outside [0, k)", sorted behind the valid labels); k <= 65536
+    const int passes = k < kRadix ? 1 : k < kRadix * kRadix ? 2 : 3;
+    return sort_passes(n, passes, (uint32_t)k, labels, new_id, order, tmp, hist, nullptr, s);
 }
 
 }  // namespace ep

@@ -227,15 +227,15 @@ __global__ __launch_bounds__(kBlock) void update_finalize_kernel(int32_t d, int3
 namespace {
 
 // ---- update, large k: rows sorted by label, one wave per cluster --------------------------------
-// seg[j] = first sorted position whose label is >= j  (seg[k] = n).
-// Labels are read through the mask the sort used for its keys, so the sequence is monotone
-// (and every seg entry is written) whatever the labels hold.
-__global__ void segment_offsets_kernel(int64_t n, int32_t k, uint32_t key_mask, const int32_t *__restrict__ labels,
+// seg[j] = first sorted position whose key is >= j, for j = 0 .. k.  The key is the one the sort used:
+// the label, or k for a label outside [0, k); such rows sit behind seg[k] and belong to no cluster.
+// The keys are monotone along `order`, so every seg entry is written exactly once.
+__global__ void segment_offsets_kernel(int64_t n, int32_t k, const int32_t *__restrict__ labels,
                                        const int32_t *__restrict__ order, int64_t *__restrict__ seg) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i > n) return;
-    const int32_t prev = i == 0 ? -1 : min((int32_t)((uint32_t)labels[order[i - 1]] & key_mask), k - 1);
-    const int32_t cur = i == n ? k : min((int32_t)((uint32_t)labels[order[i]] & key_mask), k - 1);
+    const int32_t prev = i == 0 ? -1 : (int32_t)min((uint32_t)labels[order[i - 1]], (uint32_t)k);
+    const int32_t cur = i == n ? k : (int32_t)min((uint32_t)labels[order[i]], (uint32_t)k);
     for (int32_t j = prev + 1; j <= cur; ++j) seg[j] = i;
 }
 
@@ -488,7 +488,7 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
                          float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
     int rc = launch_sort_by_label(p.n, p.k, labels, nullptr, w.order, w.order_tmp, w.sort_hist, s);
     if (rc != EP_OK) return rc;
-    segment_offsets_kernel<<<(unsigned)ceil_div(p.n + 1, kBlock), kBlock, 0, s>>>(p.n, p.k, p.k <= 256 ? 0xFFu : 0xFFFFu, labels, w.order, w.seg);
+    segment_offsets_kernel<<<(unsigned)ceil_div(p.n + 1, kBlock), kBlock, 0, s>>>(p.n, p.k, labels, w.order, w.seg);
     EP_LAUNCH_CHECK();
     return by_dtype(p, [&](auto *tag) {
         using XT = std::remove_cv_t<std::remove_pointer_t<decltype(tag)>>;

@@ -44,13 +44,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBlock = 256;
 constexpr int kWaves = 4;
 constexpr int kTile = 32;            // centroids per tile record, points per operand tile
-#ifndef EP_LARGE_POINT_TILES
-#define EP_LARGE_POINT_TILES 4
-#endif
-#ifndef EP_LARGE_OCC
-#define EP_LARGE_OCC 2
-#endif
-constexpr int kMainPointTiles = EP_LARGE_POINT_TILES;  // operand tiles of points a wave keeps in registers
+constexpr int kMainPointTiles = 4;   // operand tiles of points a wave keeps in registers
+constexpr int kMainOccupancy = 2;    // workgroups per compute unit of the sweep kernel
 constexpr float kNever = -3.0e38f;   // bias of a padding centroid
 
 template <int D> constexpr int record_bytes() { return (D / 16) * 1024 + kTile * 4; }
@@ -106,7 +101,7 @@ __global__ __launch_bounds__(kBlock) void large_prep_kernel(int32_t k, const flo
 // ---- 2. matrix-core sweep ------------------------------------------------------------------------
 // Rows [row_begin, n) in blocks of PT * 32 rows per wave, PT even.
 template <int D, int PT>
-__global__ __launch_bounds__(kBlock, EP_LARGE_OCC) void large_assign_kernel(int64_t row_begin, int64_t n, int64_t ld,
+__global__ __launch_bounds__(kBlock, kMainOccupancy) void large_assign_kernel(int64_t row_begin, int64_t n, int64_t ld,
                                                                   int32_t tiles, const bf16_t *__restrict__ X,
                                                                   const unsigned char *__restrict__ records,
                                                                   int32_t *__restrict__ best_code) {
@@ -391,7 +386,7 @@ int launch_large(const ep_problem &p, const bf16_t *X, const float *C, const Kme
         // and is slower: the chip is power-limited in this kernel, and the clock rises while the
         // last round drains.)
         const int64_t wg_blocks = ceil_div(ceil_div(p.n, (int64_t)kTile * kMainPointTiles), kWaves);
-        const int grid = (int)std::min<int64_t>(wg_blocks, 256 * EP_LARGE_OCC);
+        const int grid = (int)std::min<int64_t>(wg_blocks, 256 * kMainOccupancy);
         ProfScope prof(EP_PROF_LLOYD_MAIN, s, true);
         if (prof.start_)   // timed launch: the events get the kernel's own begin and end
             hipExtLaunchKernelGGL((large_assign_kernel<D, kMainPointTiles>), dim3(grid), dim3(kBlock), 0, s, prof.start_,

@@ -39,6 +39,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "kernels.h"
@@ -979,9 +980,17 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
         const XT_ *Xt = static_cast<const XT_ *>(X);                                                          \
         auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_, PAD_>                        \
                              : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_, PAD_>;                      \
-        if (lds_bytes > 64 * 1024)                                                                            \
-            EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                              \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));          \
+        if (lds_bytes > 64 * 1024) {   /* once per kernel variant and device */                              \
+            static std::atomic<uint64_t> attr_set[2];   /* one bit per device, per STREAM variant */          \
+            int dev_ = 0;                                                                                     \
+            EP_HIP_TRY(hipGetDevice(&dev_));                                                                  \
+            const uint64_t bit_ = 1ull << (dev_ & 63);                                                        \
+            if (!(attr_set[stream_x ? 1 : 0].load(std::memory_order_acquire) & bit_)) {                       \
+                EP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                          \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));      \
+                attr_set[stream_x ? 1 : 0].fetch_or(bit_, std::memory_order_release);                         \
+            }                                                                                                 \
+        }                                                                                                     \
         if (prof.start_)   /* timed launch: the events get the kernel's own begin and end */                \
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
                                   p.n, p.ld, p.d, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,  \

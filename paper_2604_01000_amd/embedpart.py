@@ -12,9 +12,7 @@ from pathlib import Path
 
 import torch
 
-import os as _os
-
-_LIB_PATH = Path(__file__).resolve().parent / _os.environ.get("EP_LIB_VARIANT", "libembedpart.so")
+_LIB_PATH = Path(__file__).resolve().parent / "libembedpart.so"
 
 EP_F32, EP_BF16 = 0, 1
 EP_RUN_FINAL_REASSIGN = 1

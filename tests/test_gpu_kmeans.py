@@ -149,16 +149,29 @@ def test_update_lockstep(n, d, k, relu, dtype, ld):
         np.testing.assert_array_equal(C_got[1], C_prev[1])
 
 
-def test_update_skips_out_of_range_labels():
-    X = _mixture(4000, 64, 4, seed=1)
+@pytest.mark.parametrize("n,d,k,dtype", [
+    (4000, 64, 4, torch.float32),          # fused small-k kernel
+    (4000, 128, 70, torch.float32),        # k > 64 at d = 128: rows sorted by label, one key byte
+    (4000, 128, 70, torch.bfloat16),
+    (6000, 128, 300, torch.bfloat16),      # two key bytes
+    (5000, 64, 256, torch.float32),        # k = 256: the out-of-range bucket needs the second key byte
+    (3000, 516, 20, torch.float32),        # k * d > 8192 on the generic kernels
+    (3000, 20, 5, torch.float32),          # per-workgroup partial sums of the generic kernels
+])
+def test_update_skips_out_of_range_labels(n, d, k, dtype):
+    X = _mixture(n, d, 4, seed=1, dtype=dtype)
     X32 = to_np32(X)
-    labels = np.random.default_rng(0).integers(0, 4, size=4000).astype(np.int32)
+    labels = np.random.default_rng(0).integers(0, k, size=n).astype(np.int32)
     bad = labels.copy()
-    bad[::7] = 99
+    bad[::7] = k + 29            # low byte of 99 at k = 70 would be a valid label
     bad[3::11] = -1
-    keep = (bad >= 0) & (bad < 4)
-    C_or, counts_or, _ = oracle.update(X32[keep], bad[keep], np.zeros((4, 64)))
-    C_got, counts = Kmeans(X, 4).update(bad, np.zeros((4, 64), dtype=np.float32))
+    bad[5::13] = k
+    bad[1::17] = 256 + 3         # low byte 3
+    bad[2::19] = -(2 ** 31)
+    keep = (bad >= 0) & (bad < k)
+    C_prev = np.random.default_rng(1).normal(size=(k, d)).astype(np.float32)
+    C_or, counts_or, _ = oracle.update(X32[keep], bad[keep], C_prev.astype(np.float64))
+    C_got, counts = Kmeans(X, k).update(bad, C_prev)
     np.testing.assert_array_equal(counts, counts_or)
     assert centroid_rel_err(C_got, C_or) <= CENTROID_RTOL
 
