@@ -20,9 +20,9 @@
  *     256-byte aligned and at least as large as the matching *_workspace_bytes
  *     call reports.  The library allocates nothing, frees nothing and keeps no
  *     pointer after a call returns.  Its only global state is the code of the
- *     last failing HIP call (ep_last_hip_error), the static workspace of
- *     kmeans_run_noalloc and the benchmark aid ep_profile_arm at the end of this
- *     file.
+ *     last failing HIP call (ep_last_hip_error) and the static workspace of
+ *     kmeans_run_noalloc.  (The benchmark aids of embedpart_bench.h, which are not
+ *     part of the method, add one more.)
  *   - Partition / cluster ids are 0-based, in [0, k).  (The paper numbers
  *     partitions 1..k.)
  *   - Return value: EP_OK (0) or a negative EP_E* code.  Arguments are checked
@@ -51,6 +51,10 @@ extern "C" {
 
 /* kmeans_run flags */
 #define EP_RUN_FINAL_REASSIGN 1  /* one more assignment against the final centroids */
+
+/* kmeans_update flags */
+#define EP_UPDATE_ACCUMULATE 1   /* add this call's rows to the sums and counts that earlier calls left in ws */
+#define EP_UPDATE_FINALIZE   2   /* form the means (C_out, counts) from everything accumulated */
 
 /* Limits of this build. */
 #define EP_MAX_D          1024
@@ -94,43 +98,73 @@ int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host);
 int kmeans_workspace_bytes(const ep_problem *p, size_t *bytes_host);
 
 /*
- * Initial centroids: C[j, :] = X[idx_host[j], :] widened to fp32.
- * idx_host: k row indices in [0, n) on the host (copied during the call).
+ * Initial centroids (the paper's Alg. 3 begins with P <- KMeans(E, k) and leaves the start of
+ * K-Means open; here it starts from k rows of E): C[j, :] = X[idx_host[j], :] widened to fp32.
+ * idx_host: k row indices in [0, n) on the host.  They are copied to the device during the call
+ * from pageable host memory: the call may wait on the host until earlier work on `stream` has
+ * drained, and it cannot be recorded into a stream capture (every other call of the K-Means
+ * group only enqueues).
  * C: k x d fp32, dense (row stride d), written.
  */
 int kmeans_init(const ep_problem *p, const void *X, const int64_t *idx_host,
                 float *C, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Assignment step of K-Means: labels[i] = argmin_j ||x_i - c_j||^2 (squared
- * Euclidean; the lowest j wins an exact tie), evaluated as
- * ||c_j||^2 - 2 x_i.c_j in fp32.  With EP_BF16 the centroids are rounded to
+ * Assignment step of K-Means (Alg. 3, P <- KMeans(E, k); Sec. "Phase 2: Clustering and
+ * Balancing": every vertex joins the cluster, i.e. the partition, of its nearest centroid):
+ * labels[i] = argmin_j ||x_i - c_j||^2 (squared Euclidean; the lowest j wins an exact tie),
+ * evaluated as ||c_j||^2 - 2 x_i.c_j in fp32.  With EP_BF16 the centroids are rounded to
  * bf16 (nearest-even) for the x.c products, which accumulate in fp32.
  *   C         k x d fp32, read
  *   labels    n int32, 16-byte aligned, written
  *   min_d2    n fp32 or NULL: ||x_i - c_label||^2 (clamped at 0), written
  *   objective 1 double or NULL: sum_i ||x_i - c_label||^2, written (not added to)
+ * Row ranges: rows are independent, so the rows [b, e) of a larger matrix are assigned by a call
+ * with n = e - b, X + b * ld (elements), labels + b and min_d2 + b (b a multiple of 4 keeps labels
+ * aligned); `objective` is then the range's own sum and the caller adds the ranges up.  For such a
+ * call k may exceed n.  A matrix that does not fit the device is streamed this way, chunk by
+ * chunk, with kmeans_update's flags for the other half of the round.
  */
 int kmeans_assign(const ep_problem *p, const void *X, const float *C,
                   int32_t *labels, float *min_d2, double *objective,
                   void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Update step of K-Means: C_out[j] = mean of the rows labelled j; a cluster
- * without rows keeps C_prev[j] and gets count 0.  Sums are fp32 over bounded
- * runs of rows, combined in fp64 in a fixed order.
+ * Update step of K-Means (Alg. 3, P <- KMeans(E, k): a centroid moves to the mean of the
+ * embeddings assigned to it): C_out[j] = mean of the rows labelled j; a cluster without rows
+ * keeps C_prev[j] and gets count 0.  Sums are fp32 over bounded runs of rows, combined in fp64 in
+ * a fixed order.
  *   labels  n int32 in [0, k), read (a label outside the range is undefined behaviour
  *           in the sense of a wrong result, never of an out-of-bounds access: such
- *           rows are skipped)
+ *           rows are skipped; ep_validate_labels counts them)
  *   C_prev  k x d fp32, read;  C_out k x d fp32, written (may alias C_prev)
  *   counts  k int64, written
+ *   flags   EP_UPDATE_FINALIZE: the whole update in one call, as described above.
+ *           Over row ranges (chunks of a matrix that is streamed through the device, in any sizes;
+ *           k may exceed a chunk's n): the first chunk with flags 0, the following ones with
+ *           EP_UPDATE_ACCUMULATE, the last one with EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE.
+ *           Between those calls the fp64 sums and the counts live at the start of `ws`, at a place
+ *           that depends on k and d only: pass the same ws (sized for the largest chunk) to all of
+ *           them; kmeans_assign calls in between leave it alone, any other call may not.  C_prev,
+ *           C_out and counts are used by the finalizing call only.  The result is the mean over all
+ *           chunks and, for given chunk boundaries, bit-reproducible.
  */
 int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels,
-                  const float *C_prev, float *C_out, int64_t *counts,
+                  const float *C_prev, float *C_out, int64_t *counts, int flags,
                   void *ws, size_t ws_bytes, void *stream);
 
 /*
- * `iters` Lloyd rounds (assign, then update) starting from the centroids in C.
+ * Check of a label vector against the paper's contract that every vertex carries exactly one
+ * partition id (Sec. "Graph Partitioning": the partitions are disjoint and cover V; ids here are 0 .. k-1).
+ * The hot calls skip labels outside [0, k) instead of testing for them; this call counts them.
+ *   result  2 int64, 8-byte aligned, written: [0] = number of labels outside [0, k),
+ *           [1] = index of the first one (n if there is none)
+ */
+int ep_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *result, void *stream);
+
+/*
+ * `iters` Lloyd rounds (assign, then update: the K-Means of Alg. 3's first step, run for a fixed
+ * number of rounds) starting from the centroids in C.
  *   C               k x d fp32: initial centroids in, final centroids out
  *   labels          n int32, 16-byte aligned, written: the labels of the last assignment performed
  *   counts          k int64, written: cluster sizes of round `iters`, of which C holds the means
@@ -177,6 +211,8 @@ int kmeans_run_noalloc(const ep_problem *p, const void *X, int32_t iters, float 
  *   objective_hist       iters + 1 doubles or NULL: [t] = the sample's objective in round t,
  *                        [iters] = the objective of the full assignment
  *   ws                   kmeans_sampled_workspace_bytes(p, m) bytes; holds the dense copy of the sample
+ * sample_rows_host is copied to the device during the call from pageable host memory: like
+ * kmeans_init, the call may wait on the host for earlier work on `stream` and cannot be captured.
  * Errors as kmeans_run; EP_EINVAL also for m outside [k, n] or a row index outside [0, n).
  */
 int kmeans_sampled_workspace_bytes(const ep_problem *p, int64_t m, size_t *bytes_host);
@@ -188,7 +224,9 @@ int kmeans_run_sampled(const ep_problem *p, const void *X, int64_t m, const int6
 int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host);
 
 /*
- * Quality of a partition over a CSR graph, in integers.
+ * Quality of a partition over a CSR graph, in integers (Sec. "Partitioning quality metrics": an
+ * edge (u,v) is cut iff pid(u) != pid(v); edge-cut ratio |C| / |E|; vertex balance
+ * max |P_i| / mean |P_i|).
  *   rowptr   n + 1 offsets, int32 or int64 (rowptr_is_i64), rowptr[n] == nnz
  *   colidx   nnz int32 column indices in [0, n), 16-byte aligned
  *   labels   n int32 partition ids in [0, k)
@@ -203,8 +241,9 @@ int partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, int
                       int64_t *cut, int64_t *sizes, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Reordering: vertices of one partition get consecutive ids; partitions in
- * increasing id, vertices inside a partition in increasing original id.
+ * Reordering (Sec. "Adapting EmbedPart for Reordering": vertices of one partition get
+ * consecutive ids): partitions in increasing id, vertices inside a partition in increasing
+ * original id.  Vertices whose label is outside [0, k) come last, in increasing id.
  *   new_id  n int32, written: pi(v)
  *   order   n int32, written: order[pi(v)] = v
  */
@@ -212,8 +251,8 @@ int partition_permutation(int64_t n, int32_t k, const int32_t *labels,
                           int32_t *new_id, int32_t *order, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Sum over stored CSR entries (u,v) of the gap |pi(u) - pi(v)|; new_id == NULL
- * means the identity.  gap_sum: 1 uint64, written.  Divide by nnz for the mean gap.
+ * Sum over stored CSR entries (u,v) of the gap xi_pi(u,v) = |pi(u) - pi(v)| (Eq. gap of the
+ * reordering section); new_id == NULL means the identity.  gap_sum: 1 uint64, written.  Divide by nnz for the mean gap.
  */
 int edge_gap_sum(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
                  const int32_t *colidx, const int32_t *new_id,
@@ -308,32 +347,6 @@ int graph_reorder_workspace_bytes(int64_t n, int64_t nnz, size_t *bytes_host);
 int graph_reorder(int64_t n, int64_t nnz, const void *rowptr, int rowptr_is_i64,
                   const int32_t *colidx, const int32_t *new_id, const int32_t *order,
                   void *new_rowptr, int32_t *new_colidx, void *ws, size_t ws_bytes, void *stream);
-
-/*
- * Benchmark aid, not part of the method: per-kernel timing with HIP events the caller owns.
- * While armed, launch number i (counted from arming) of a kernel of class `kernel_class` made by
- * any call is bracketed by events_host[2*i] and events_host[2*i+1] on that call's stream, for
- * i < capacity / 2; later launches are not timed.  The tuned Lloyd kernels hand the pair to the
- * launch itself, which stamps them with the kernel's own begin and end; the other kernels record
- * them on the stream just before and just after the launch.
- * events_host: host array of hipEvent_t handles created with timing enabled; it must stay
- * valid until disarmed.  ep_profile_arm(NULL, 0, 0) disarms.  This and the HIP error code are
- * the library's only process-global state; arming is not thread-safe.
- * ep_profile_count(): launches of the armed class seen since arming (may exceed capacity / 2).
- */
-#define EP_PROF_LLOYD_MAIN  1  /* the kernel that reads X in a Lloyd round (assignment, fused with the sums where fused) */
-#define EP_PROF_UPDATE_SUMS 2  /* the separate partial-sum / segment-mean kernel of kmeans_update */
-#define EP_PROF_EDGE_SWEEP  3  /* the CSR sweep of partition_quality / edge_gap_sum */
-int ep_profile_arm(void **events_host, int capacity, int kernel_class);
-int ep_profile_count(void);
-
-/*
- * Benchmark aid: plain streaming copy of `bytes` bytes (a multiple of 16, both pointers 16-byte
- * aligned) with 16-byte loads and stores.  It gives benchmarks a kernel of exactly known traffic
- * (bytes read + bytes written) to calibrate hardware counters and to quote the copy bandwidth of
- * the machine at hand next to the roofline figures.
- */
-int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

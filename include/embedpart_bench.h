@@ -1,0 +1,44 @@
+/*
+ * embedpart_bench.h -- benchmark aids of libembedpart.  NOT part of the method and not needed by
+ * any user of embedpart.h: they exist so that a benchmark can time single kernels of the library
+ * with events of its own and calibrate hardware counters against a kernel of known traffic.
+ */
+#ifndef EMBEDPART_BENCH_H
+#define EMBEDPART_BENCH_H
+
+#include "embedpart.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Benchmark aid, not part of the method: per-kernel timing with HIP events the caller owns.
+ * While armed, launch number i (counted from arming) of a kernel of class `kernel_class` made by
+ * any call is bracketed by events_host[2*i] and events_host[2*i+1] on that call's stream, for
+ * i < capacity / 2; later launches are not timed.  The tuned Lloyd kernels hand the pair to the
+ * launch itself, which stamps them with the kernel's own begin and end; the other kernels record
+ * them on the stream just before and just after the launch.
+ * events_host: host array of hipEvent_t handles created with timing enabled; it must stay
+ * valid until disarmed.  ep_profile_arm(NULL, 0, 0) disarms.  This and the HIP error code are
+ * process-global state; arming is not thread-safe.
+ * ep_profile_count(): launches of the armed class seen since arming (may exceed capacity / 2).
+ */
+#define EP_PROF_LLOYD_MAIN  1  /* the kernel that reads X in a Lloyd round (assignment, fused with the sums where fused) */
+#define EP_PROF_UPDATE_SUMS 2  /* the separate partial-sum / segment-mean kernel of kmeans_update */
+#define EP_PROF_EDGE_SWEEP  3  /* the CSR sweep of partition_quality / edge_gap_sum */
+int ep_profile_arm(void **events_host, int capacity, int kernel_class);
+int ep_profile_count(void);
+
+/*
+ * Benchmark aid: plain streaming copy of `bytes` bytes (a multiple of 16, both pointers 16-byte
+ * aligned) with 16-byte loads and stores.  It gives benchmarks a kernel of exactly known traffic
+ * (bytes read + bytes written) to calibrate hardware counters and to quote the copy bandwidth of
+ * the machine at hand next to the roofline figures.
+ */
+int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMBEDPART_BENCH_H */

@@ -41,6 +41,15 @@ int check_problem(const ep_problem *p) {
     return EP_OK;
 }
 
+// The same for a call that works on a row range of a larger matrix (kmeans_assign, kmeans_update): a
+// chunk may hold fewer rows than there are clusters.
+int check_problem_rows(const ep_problem *p) {
+    if (!p) return EP_EINVAL;
+    ep_problem q = *p;
+    if (q.n >= 1 && (int64_t)q.k > q.n && q.k <= EP_MAX_K) q.n = q.k;   // k > n is not an error here
+    return check_problem(&q);
+}
+
 int check_x(const ep_problem *p, const void *X) {
     if (!X || !aligned(X, 16)) return EP_EINVAL;
     (void)p;
@@ -70,10 +79,13 @@ int do_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs
 }
 
 int do_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
-              int64_t *counts, const KmeansWs &w, hipStream_t s) {
-    if (small_path_supported(p)) return launch_small_update(p, X, labels, C_prev, C_out, counts, w, s);
-    return update_by_sorted_rows(p) ? launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, s)
-                                    : launch_update_small(p, X, labels, C_prev, C_out, counts, w, s);
+              int64_t *counts, const KmeansWs &w, int flags, hipStream_t s) {
+    const UpdateAcc acc{w.acc_sum, w.acc_cnt, w.chunk_cnt, flags};
+    int rc = small_path_supported(p)    ? launch_small_update(p, X, labels, C_prev, C_out, counts, w, acc, s)
+             : update_by_sorted_rows(p) ? launch_update_sorted(p, X, labels, C_prev, C_out, counts, w, acc, s)
+                                        : launch_update_small(p, X, labels, C_prev, C_out, counts, w, acc, s);
+    if (rc != EP_OK || (flags & EP_UPDATE_FINALIZE)) return rc;
+    return launch_accumulate_counts(p.k, acc, s);   // the running counts take this chunk's
 }
 
 int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colidx) {
@@ -98,7 +110,7 @@ int run_rounds(const ep_problem &p, const void *X, int32_t iters, float *C, int3
     for (int32_t t = 0; t < iters; ++t) {
         if ((rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + t : nullptr, s)) != EP_OK)
             return rc;
-        if ((rc = do_update(p, X, labels, C, C, counts, w, s)) != EP_OK) return rc;
+        if ((rc = do_update(p, X, labels, C, C, counts, w, EP_UPDATE_FINALIZE, s)) != EP_OK) return rc;
     }
     if (flags & EP_RUN_FINAL_REASSIGN)
         rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
@@ -235,7 +247,7 @@ int kmeans_init(const ep_problem *p, const void *X, const int64_t *idx_host, flo
 
 int kmeans_assign(const ep_problem *p, const void *X, const float *C, int32_t *labels, float *min_d2,
                   double *objective, void *ws, size_t ws_bytes, void *stream) {
-    int rc = check_problem(p);
+    int rc = check_problem_rows(p);
     if (rc != EP_OK) return rc;
     if ((rc = check_x(p, X)) != EP_OK) return rc;
     if (!C || !labels || !aligned(labels, 16)) return EP_EINVAL;
@@ -244,13 +256,20 @@ int kmeans_assign(const ep_problem *p, const void *X, const float *C, int32_t *l
 }
 
 int kmeans_update(const ep_problem *p, const void *X, const int32_t *labels, const float *C_prev, float *C_out,
-                  int64_t *counts, void *ws, size_t ws_bytes, void *stream) {
-    int rc = check_problem(p);
+                  int64_t *counts, int flags, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_problem_rows(p);
     if (rc != EP_OK) return rc;
     if ((rc = check_x(p, X)) != EP_OK) return rc;
-    if (!labels || !C_prev || !C_out || !counts) return EP_EINVAL;
+    if (!labels || (flags & ~(EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE))) return EP_EINVAL;
+    if ((flags & EP_UPDATE_FINALIZE) && (!C_prev || !C_out || !counts)) return EP_EINVAL;
     if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
-    return do_update(*p, X, labels, C_prev, C_out, counts, carve_kmeans_ws(*p, ws), static_cast<hipStream_t>(stream));
+    return do_update(*p, X, labels, C_prev, C_out, counts, carve_kmeans_ws(*p, ws), flags,
+                     static_cast<hipStream_t>(stream));
+}
+
+int ep_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *result, void *stream) {
+    if (n < 1 || n >= EP_MAX_N || k < 1 || !labels || !result || !aligned(result, 8)) return EP_EINVAL;
+    return launch_validate_labels(n, k, labels, result, static_cast<hipStream_t>(stream));
 }
 
 int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,

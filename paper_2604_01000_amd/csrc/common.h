@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/embedpart.h"
+#include "../../include/embedpart_bench.h"
 
 namespace ep {
 

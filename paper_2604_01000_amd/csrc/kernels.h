@@ -18,8 +18,42 @@ inline bool update_by_sorted_rows(const ep_problem &p) {
     return (int64_t)p.k * p.d > kSmallKElems || (p.k > 64 && (p.d == 64 || p.d == 128));
 }
 
+// Chunked centroid update (the flags of kmeans_update): running sums and counts kept in the workspace
+// between the calls of one update, at a place that depends on k and d only.
+struct UpdateAcc {
+    double *sum;         // [k*d] sums of the chunks seen so far
+    int64_t *cnt;        // [k]   their counts
+    int64_t *chunk_cnt;  // [k]   counts of the current call (added to cnt after a call that does not finalize)
+    int flags;           // EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE
+};
+inline UpdateAcc whole_update() { return UpdateAcc{nullptr, nullptr, nullptr, EP_UPDATE_FINALIZE}; }
+
+#ifdef __HIPCC__
+// Last step of every update kernel for element `at` = j * d + column of centroid j, given this call's
+// sum `tot` and count `cnt` for it: add what earlier chunks left, then either form the mean (an empty
+// cluster keeps its previous centroid) or leave the running sum for the next chunk.  Every element is
+// owned by one thread; the running counts are only read here and are brought up to date by
+// launch_accumulate_counts afterwards, so no thread reads what another writes.
+__device__ __forceinline__ void finish_centroid_element(const UpdateAcc &a, int64_t at, int32_t j, bool first_column,
+                                                        double tot, int64_t cnt, const float *__restrict__ C_prev,
+                                                        float *__restrict__ C_out, int64_t *__restrict__ counts) {
+    if (a.flags & EP_UPDATE_ACCUMULATE) tot += a.sum[at];
+    if (a.flags & EP_UPDATE_FINALIZE) {
+        if (a.flags & EP_UPDATE_ACCUMULATE) cnt += a.cnt[j];
+        C_out[at] = cnt > 0 ? (float)(tot / (double)cnt) : C_prev[at];
+        if (first_column) counts[j] = cnt;
+    } else {
+        a.sum[at] = tot;
+        if (first_column) a.chunk_cnt[j] = cnt;
+    }
+}
+#endif
+
 struct KmeansWs {
     double *obj_part;     // [kObjBlocksMax]
+    double *acc_sum;      // [k*d]  running sums of a chunked update
+    int64_t *acc_cnt;     // [k]    running counts of a chunked update
+    int64_t *chunk_cnt;   // [k]    counts of the chunk in hand
     float *cnorm;         // [k]   generic path: ||c_j||^2; bf16 matrix-core path: -||c_j||^2 / 2 (of the rounded centroids)
     float *cq;            // [k*d] bf16-rounded centroids as fp32 (EP_BF16 only, else unused)
     bf16_t *cq16;         // [k*d] the same as bf16 (EP_BF16 only)
@@ -46,9 +80,13 @@ int launch_prep_centroids(const ep_problem &p, const float *C, const KmeansWs &w
 int launch_assign_generic(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                           float *min_d2, double *objective, hipStream_t s);
 int launch_update_small(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+                        float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s);
 int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+                         float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s);
+// After an update call that does not finalize: cnt[j] = (accumulate ? cnt[j] : 0) + chunk_cnt[j].
+int launch_accumulate_counts(int32_t k, const UpdateAcc &acc, hipStream_t s);
+// result[0] = number of labels outside [0, k), result[1] = index of the first one (n if none).
+int launch_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *result, hipStream_t s);
 
 // ---- K-Means, k <= 64, d in {64,128}, fp32: fused matrix-core kernels (kmeans_small.hip) --------
 constexpr int kSmallMaxBlocks = 512;  // workgroups (= partial sums) per launch; <= kUpdBlocksMax
@@ -63,7 +101,7 @@ bool small_path_supported(const ep_problem &p);
 int launch_small_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s);
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s);
+                        float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s);
 // fp32, d in {64,128}, k > 64: the same assignment kernel over slices of 64 centroids (k / 64 passes).
 bool small_sliced_supported(const ep_problem &p);
 int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,

@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kBlock) void update_finalize_kernel(int32_t d, int3
                                                                   const int32_t *__restrict__ pcnt,
                                                                   const float *__restrict__ C_prev,
                                                                   float *__restrict__ C_out,
-                                                                  int64_t *__restrict__ counts) {
+                                                                  int64_t *__restrict__ counts, UpdateAcc acc) {
     const int t = blockIdx.x * kBlock + threadIdx.x;
     const int kd = k * d;
     if (t >= kd) return;
@@ -220,8 +220,51 @@ __global__ __launch_bounds__(kBlock) void update_finalize_kernel(int32_t d, int3
         s += (double)psum[(int64_t)b * kd + t];
         c += pcnt[(int64_t)b * k + j];
     }
-    C_out[t] = c > 0 ? (float)(s / (double)c) : C_prev[t];
-    if (t % d == 0) counts[j] = c;
+    finish_centroid_element(acc, t, j, t % d == 0, s, c, C_prev, C_out, counts);
+}
+
+__global__ void accumulate_counts_kernel(int32_t k, UpdateAcc acc) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < k) acc.cnt[j] = ((acc.flags & EP_UPDATE_ACCUMULATE) ? acc.cnt[j] : 0) + acc.chunk_cnt[j];
+}
+
+// result[0] += labels outside [0, k) among this workgroup's, result[1] = min(result[1], first such index).
+__global__ __launch_bounds__(kBlock) void validate_labels_kernel(int64_t n, int32_t k,
+                                                                  const int32_t *__restrict__ labels,
+                                                                  unsigned long long *__restrict__ result) {
+    __shared__ unsigned long long bad_lds[kBlock / 64], first_lds[kBlock / 64];
+    unsigned long long bad = 0, first = (unsigned long long)n;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        if ((uint32_t)labels[i] >= (uint32_t)k) {   // a negative label is a large unsigned one
+            ++bad;
+            first = min(first, (unsigned long long)i);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        bad += __shfl_down(bad, off, 64);
+        first = min(first, (unsigned long long)__shfl_down(first, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        bad_lds[threadIdx.x >> 6] = bad;
+        first_lds[threadIdx.x >> 6] = first;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / 64; ++w) {
+            bad += bad_lds[w];
+            first = min(first, first_lds[w]);
+        }
+        if (bad) {   // integers: the order of the atomics does not matter
+            atomicAdd(&result[0], bad);
+            atomicMin(&result[1], first);
+        }
+    }
+}
+
+__global__ void validate_labels_init_kernel(int64_t n, unsigned long long *__restrict__ result) {
+    result[0] = 0;
+    result[1] = (unsigned long long)n;
 }
 
 namespace {
@@ -316,15 +359,14 @@ __global__ __launch_bounds__(kBlock) void segment_combine_kernel(int32_t d, int3
                                                                   const double *__restrict__ part,
                                                                   const float *__restrict__ C_prev,
                                                                   float *__restrict__ C_out,
-                                                                  int64_t *__restrict__ counts) {
+                                                                  int64_t *__restrict__ counts, UpdateAcc acc) {
     const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (t >= (int64_t)k * d) return;
     const int j = (int)(t / d), col = (int)(t % d);
     const int64_t cnt = seg[j + 1] - seg[j];
     double tot = 0.0;
     for (int piece = 0; piece < pieces; ++piece) tot += part[((int64_t)j * pieces + piece) * d + col];
-    C_out[t] = cnt > 0 ? (float)(tot / (double)cnt) : C_prev[t];
-    if (col == 0) counts[j] = cnt;
+    finish_centroid_element(acc, t, j, col == 0, tot, cnt, C_prev, C_out, counts);
 }
 
 template <typename XT, int kLanes>
@@ -334,22 +376,21 @@ __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t
                                                                const int64_t *__restrict__ seg,
                                                                const float *__restrict__ C_prev,
                                                                float *__restrict__ C_out,
-                                                               int64_t *__restrict__ counts) {
+                                                               int64_t *__restrict__ counts, UpdateAcc upd) {
     const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
     if (j >= k) return;
     const int lane = threadIdx.x & 63;
     const int64_t b = seg[j], e = seg[j + 1];
     const int64_t cnt = e - b;
-    if (lane == 0) counts[j] = cnt;
     if (kLanes > 0) {
         const int chunk = lane % (kLanes > 0 ? kLanes : 1), sub = lane / (kLanes > 0 ? kLanes : 1);
         double acc[8];
         sum_sorted_rows<XT, kLanes>(X, ld, order, b, e, lane, acc);
         if (sub == 0) {
-            float *co = C_out + (int64_t)j * d + 8 * chunk;
-            const float *cp = C_prev + (int64_t)j * d + 8 * chunk;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) co[q] = cnt > 0 ? (float)(acc[q] / (double)cnt) : cp[q];
+            for (int q = 0; q < 8; ++q)
+                finish_centroid_element(upd, (int64_t)j * d + 8 * chunk + q, j, chunk == 0 && q == 0, acc[q], cnt, C_prev,
+                                        C_out, counts);
         }
         return;
     }
@@ -362,10 +403,8 @@ __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t
                 s0 += (double)load_elem(x);
                 if (m + 1 < d) s1 += (double)load_elem(x + 1);
             }
-            float *co = C_out + (int64_t)j * d + m;
-            const float *cp = C_prev + (int64_t)j * d + m;
-            co[0] = cnt > 0 ? (float)(s0 / (double)cnt) : cp[0];
-            if (m + 1 < d) co[1] = cnt > 0 ? (float)(s1 / (double)cnt) : cp[1];
+            finish_centroid_element(upd, (int64_t)j * d + m, j, m == 0, s0, cnt, C_prev, C_out, counts);
+            if (m + 1 < d) finish_centroid_element(upd, (int64_t)j * d + m + 1, j, false, s1, cnt, C_prev, C_out, counts);
         }
     }
 }
@@ -383,6 +422,11 @@ KmeansWs carve_kmeans_ws(const ep_problem &p, void *ws) {
     KmeansWs w{};
     const size_t kd = (size_t)p.k * p.d;
     w.obj_part = c.take<double>(kObjBlocksMax);
+    // the running sums of a chunked update come first: their place must not depend on n, because the
+    // chunks of one update may differ in size
+    w.acc_sum = c.take<double>(kd);
+    w.acc_cnt = c.take<int64_t>(p.k);
+    w.chunk_cnt = c.take<int64_t>(p.k);
     w.cnorm = c.take<float>(p.k);
     w.idx = c.take<int64_t>(p.k);
     if (p.dtype == EP_BF16) {
@@ -459,8 +503,24 @@ int launch_assign_generic(const ep_problem &p, const void *X, const float *C, co
     return EP_OK;
 }
 
+int launch_accumulate_counts(int32_t k, const UpdateAcc &acc, hipStream_t s) {
+    accumulate_counts_kernel<<<(unsigned)ceil_div(k, kBlock), kBlock, 0, s>>>(k, acc);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
+
+int launch_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *result, hipStream_t s) {
+    auto out = reinterpret_cast<unsigned long long *>(result);
+    validate_labels_init_kernel<<<1, 1, 0, s>>>(n, out);
+    EP_LAUNCH_CHECK();
+    const unsigned grid = (unsigned)std::min<int64_t>(ceil_div(n, kBlock * 4), 2048);
+    validate_labels_kernel<<<grid, kBlock, 0, s>>>(n, k, labels, out);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
+
 int launch_update_small(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
+                        float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s) {
     const int kd = p.k * p.d;
     int dpad = 1;
     while (dpad < p.d && dpad < kBlock) dpad <<= 1;
@@ -479,13 +539,13 @@ int launch_update_small(const ep_problem &p, const void *X, const int32_t *label
     });
     if (rc != EP_OK) return rc;
     update_finalize_kernel<<<(unsigned)ceil_div(kd, kBlock), kBlock, 0, s>>>(p.d, p.k, blocks, w.psum, w.pcnt, C_prev,
-                                                                             C_out, counts);
+                                                                             C_out, counts, acc);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
 
 int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                         float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
+                         float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s) {
     int rc = launch_sort_by_label(p.n, p.k, labels, nullptr, w.order, w.order_tmp, w.sort_hist, s);
     if (rc != EP_OK) return rc;
     segment_offsets_kernel<<<(unsigned)ceil_div(p.n + 1, kBlock), kBlock, 0, s>>>(p.n, p.k, labels, w.order, w.seg);
@@ -504,16 +564,16 @@ int launch_update_sorted(const ep_problem &p, const void *X, const int32_t *labe
                 segment_partial_kernel<XT, 8><<<pgrid, kBlock, 0, s>>>(p.d, p.k, pieces, p.ld, Xt, w.order, w.seg, w.seg_part);
             EP_LAUNCH_CHECK();
             segment_combine_kernel<<<(unsigned)ceil_div((int64_t)p.k * p.d, kBlock), kBlock, 0, s>>>(
-                p.d, p.k, pieces, w.seg, w.seg_part, C_prev, C_out, counts);
+                p.d, p.k, pieces, w.seg, w.seg_part, C_prev, C_out, counts, acc);
             EP_LAUNCH_CHECK();
             return EP_OK;
         }
         if (p.d == 128)
-            segment_mean_kernel<XT, 16><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
+            segment_mean_kernel<XT, 16><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts, acc);
         else if (p.d == 64)
-            segment_mean_kernel<XT, 8><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
+            segment_mean_kernel<XT, 8><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts, acc);
         else
-            segment_mean_kernel<XT, 0><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts);
+            segment_mean_kernel<XT, 0><<<grid, kBlock, 0, s>>>(p.d, p.k, p.ld, Xt, w.order, w.seg, C_prev, C_out, counts, acc);
         EP_LAUNCH_CHECK();
         return EP_OK;
     });

@@ -889,7 +889,7 @@ __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
     int32_t d_pad, int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
     const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
     double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
-    int64_t *__restrict__ counts, double *__restrict__ objective) {
+    int64_t *__restrict__ counts, double *__restrict__ objective, UpdateAcc acc) {
     __shared__ double seg_sum[kFinSegs * kFinCols];
     __shared__ unsigned long long total_cnt;
     const int slices = d_pad / kFinCols;   // the partial sums have d_pad columns, the centroids d <= d_pad
@@ -930,8 +930,7 @@ __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
         for (int q = 1; q < kFinSegs; ++q) tot += seg_sum[q * kFinCols + t];
         const int64_t cc = (int64_t)total_cnt;
         const int64_t at = (int64_t)j * d + col0 + t;
-        if (col0 + t < d) C_out[at] = cc > 0 ? (float)(tot / (double)cc) : C_prev[at];
-        if (t == 0 && col0 == 0) counts[j] = cc;
+        if (col0 + t < d) finish_centroid_element(acc, at, j, t == 0 && col0 == 0, tot, cc, C_prev, C_out, counts);
     } else if (t >= 64 && t < 128 && blockIdx.x == 0 && objective) {  // second wave
         write_objective(s_part, xsq_part, parts, fresh_xsq, xsq_total, objective, t - 64);
     }
@@ -1072,21 +1071,22 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 }
 
 static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
-                                 const KmeansWs &w, double *objective, bool fresh_xsq, hipStream_t s) {
+                                 const KmeansWs &w, double *objective, bool fresh_xsq, const UpdateAcc &acc,
+                                 hipStream_t s) {
     const int parts = small_blocks(p);
     const int dpad = small_padded_d(p);
     lloyd_small_finalize_kernel<<<p.k * (dpad / kFinCols), kFinBlock, 0, s>>>(
         dpad, p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
-        C_out, counts, objective);
+        C_out, counts, objective, acc);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
 
 int launch_small_update(const ep_problem &p, const void *X, const int32_t *labels, const float *C_prev,
-                        float *C_out, int64_t *counts, const KmeansWs &w, hipStream_t s) {
+                        float *C_out, int64_t *counts, const KmeansWs &w, const UpdateAcc &acc, hipStream_t s) {
     int rc = launch_mode<kUpdateOnly, false>(p, X, nullptr, w, nullptr, labels, nullptr, false, s);
     if (rc != EP_OK) return rc;
-    return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, s);
+    return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, acc, s);
 }
 
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
@@ -1095,7 +1095,7 @@ int launch_small_round(const ep_problem &p, const void *X, float *C, const Kmean
     int rc = fresh ? launch_mode<kFused, true>(p, X, C, w, labels, nullptr, nullptr, true, s)
                    : launch_mode<kFused, false>(p, X, C, w, labels, nullptr, nullptr, objective != nullptr, s);
     if (rc != EP_OK) return rc;
-    return launch_small_finalize(p, C, C, counts, w, objective, fresh, s);
+    return launch_small_finalize(p, C, C, counts, w, objective, fresh, whole_update(), s);
 }
 
 }  // namespace ep

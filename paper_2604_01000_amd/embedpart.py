@@ -16,6 +16,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libembedpart.so"
 
 EP_F32, EP_BF16 = 0, 1
 EP_RUN_FINAL_REASSIGN = 1
+EP_UPDATE_ACCUMULATE, EP_UPDATE_FINALIZE = 1, 2
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
 EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the header
 EP_BALANCE_MAX_K, EP_BALANCE_MAX_ROUNDS = 255, 1024
@@ -23,7 +24,7 @@ EP_NOALLOC_SCRATCH_BYTES = 34 * 1024 * 1024
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
-    "kmeans_init", "kmeans_assign", "kmeans_update", "kmeans_run", "kmeans_run_noalloc",
+    "kmeans_init", "kmeans_assign", "kmeans_update", "ep_validate_labels", "kmeans_run", "kmeans_run_noalloc",
     "kmeans_sampled_workspace_bytes",
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
@@ -69,7 +70,8 @@ def lib() -> C.CDLL:
         L.kmeans_workspace_bytes.argtypes = [pp, C.POINTER(sz)]
         L.kmeans_init.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         L.kmeans_assign.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
-        L.kmeans_update.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.kmeans_update.argtypes = [pp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+        L.ep_validate_labels.argtypes = [i64, i32, vp, vp, vp]
         L.kmeans_run.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp, sz, vp]
         L.kmeans_run_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp]
         L.kmeans_sampled_workspace_bytes.argtypes = [pp, i64, C.POINTER(sz)]
@@ -164,9 +166,13 @@ def kmeans_assign(p, X, Cc, labels, min_d2, objective, ws):
                                _ptr(ws), ws.numel(), _stream()), "kmeans_assign")
 
 
-def kmeans_update(p, X, labels, C_prev, C_out, counts, ws):
-    _check(lib().kmeans_update(C.byref(p), _ptr(X), _ptr(labels), _ptr(C_prev), _ptr(C_out), _ptr(counts),
+def kmeans_update(p, X, labels, C_prev, C_out, counts, flags, ws):
+    _check(lib().kmeans_update(C.byref(p), _ptr(X), _ptr(labels), _ptr(C_prev), _ptr(C_out), _ptr(counts), flags,
                                _ptr(ws), ws.numel(), _stream()), "kmeans_update")
+
+
+def ep_validate_labels(n, k, labels, result):
+    _check(lib().ep_validate_labels(n, k, _ptr(labels), _ptr(result), _stream()), "ep_validate_labels")
 
 
 def kmeans_run(p, X, iters, Cc, labels, counts, objective_hist, flags, ws):

@@ -14,6 +14,25 @@ CENTROID_RTOL = 1e-4   # per-centroid relative L2 error allowed (fp32 device vs 
 DEV = "cuda:0"
 
 
+CANARY = 64            # elements behind every output buffer that no call may touch
+FILL = -7              # what output buffers hold before a call: an unwritten entry shows
+
+
+class Guarded:
+    """An output buffer with a canary tail: `t` is the view handed to the library, `check()` asserts
+    that nothing was written behind it."""
+
+    def __init__(self, shape, dtype, device=None, fill=FILL):
+        shape = tuple(shape) if isinstance(shape, (tuple, list)) else (shape,)
+        self.fill = fill
+        self.whole = torch.full((shape[0] + CANARY,) + shape[1:], fill, dtype=dtype, device=device or DEV)
+        self.t = self.whole[:shape[0]]
+
+    def check(self):
+        assert bool((self.whole[self.t.shape[0]:] == self.fill).all()), "a call wrote past the end of an output buffer"
+        return self.t
+
+
 def to_np32(X: torch.Tensor) -> np.ndarray:
     """Exact fp32 copy of a device matrix on the host (bf16 widens exactly)."""
     return X.detach().to("cpu", torch.float32).numpy()
@@ -28,9 +47,14 @@ class Kmeans:
         self.n, self.d = X.shape
         self.p = ep.problem(X, k)
         self.ws = ep.workspace(ep.kmeans_workspace_bytes(self.p), X.device)
-        self.C = torch.empty((k, self.d), dtype=torch.float32, device=X.device)
-        self.labels = torch.full((self.n,), -7, dtype=torch.int32, device=X.device)
-        self.counts = torch.full((k,), -7, dtype=torch.int64, device=X.device)
+        self._guards = [Guarded((k, self.d), torch.float32, X.device), Guarded(self.n, torch.int32, X.device),
+                        Guarded(k, torch.int64, X.device)]
+        self.C, self.labels, self.counts = (g.t for g in self._guards)
+
+    def _sync_and_check(self, *more):
+        torch.cuda.synchronize()
+        for g in (*self._guards, *more):
+            g.check()
 
     def init(self, idx):
         ep.kmeans_init(self.p, self.X, torch.as_tensor(np.asarray(idx), dtype=torch.int64), self.C, self.ws)
@@ -41,10 +65,12 @@ class Kmeans:
         return self
 
     def assign(self, want_d2=True, want_obj=True):
-        d2 = torch.empty(self.n, dtype=torch.float32, device=self.X.device) if want_d2 else None
-        obj = torch.zeros(1, dtype=torch.float64, device=self.X.device) if want_obj else None
+        gd2 = Guarded(self.n, torch.float32, self.X.device)
+        gobj = Guarded(1, torch.float64, self.X.device)
+        d2 = gd2.t if want_d2 else None
+        obj = gobj.t if want_obj else None
         ep.kmeans_assign(self.p, self.X, self.C, self.labels, d2, obj, self.ws)
-        torch.cuda.synchronize()
+        self._sync_and_check(gd2, gobj)
         return (self.labels.cpu().numpy(), None if d2 is None else d2.cpu().numpy(),
                 None if obj is None else float(obj.item()))
 
@@ -52,15 +78,18 @@ class Kmeans:
         if labels is not None:
             self.labels.copy_(torch.from_numpy(np.asarray(labels, dtype=np.int32)))
         Cp = self.C if C_prev is None else torch.from_numpy(np.asarray(C_prev, dtype=np.float32)).to(self.X.device)
-        out = torch.empty_like(self.C)
-        ep.kmeans_update(self.p, self.X, self.labels, Cp, out, self.counts, self.ws)
-        torch.cuda.synchronize()
+        gout = Guarded((self.k, self.d), torch.float32, self.X.device)
+        out = gout.t
+        ep.kmeans_update(self.p, self.X, self.labels, Cp, out, self.counts, ep.EP_UPDATE_FINALIZE, self.ws)
+        self._sync_and_check(gout)
         return out.cpu().numpy(), self.counts.cpu().numpy()
 
     def run(self, iters, flags=0):
-        hist = torch.full((iters + 1,), float("nan"), dtype=torch.float64, device=self.X.device)
+        ghist = Guarded(iters + 1, torch.float64, self.X.device)
+        hist = ghist.t
+        hist.fill_(float("nan"))
         ep.kmeans_run(self.p, self.X, iters, self.C, self.labels, self.counts, hist, flags, self.ws)
-        torch.cuda.synchronize()
+        self._sync_and_check(ghist)
         return dict(C=self.C.cpu().numpy(), labels=self.labels.cpu().numpy(), counts=self.counts.cpu().numpy(),
                     obj_hist=hist.cpu().numpy())
 
@@ -151,17 +180,19 @@ class Graph:
         self.ci_np = colidx.cpu().numpy()
 
     def quality(self, labels: torch.Tensor, k: int):
-        cut = torch.full((1,), -7, dtype=torch.int64, device=DEV)
-        sizes = torch.full((k,), -7, dtype=torch.int64, device=DEV)
+        gcut, gsizes = Guarded(1, torch.int64), Guarded(k, torch.int64)
+        cut, sizes = gcut.t, gsizes.t
         ep.partition_quality(self.n, self.nnz, k, self.rowptr, self.colidx, labels, cut, sizes, self.ws)
         torch.cuda.synchronize()
+        gcut.check(), gsizes.check()
         return int(cut.item()), sizes.cpu().numpy()
 
     def permutation(self, labels: torch.Tensor, k: int):
-        new_id = torch.full((self.n,), -7, dtype=torch.int32, device=DEV)
-        order = torch.full((self.n,), -7, dtype=torch.int32, device=DEV)
+        gid, gorder = Guarded(self.n, torch.int32), Guarded(self.n, torch.int32)
+        new_id, order = gid.t, gorder.t
         ep.partition_permutation(self.n, k, labels, new_id, order, self.ws)
         torch.cuda.synchronize()
+        gid.check(), gorder.check()
         return new_id, order
 
     def gap_sum(self, new_id):
@@ -178,9 +209,10 @@ class Graph:
 
     def reorder(self, new_id, order):
         """(new_rowptr, new_colidx) as numpy; outputs are pre-filled so that unwritten entries show."""
-        new_rowptr = torch.full_like(self.rowptr, -7)
-        new_colidx = torch.full_like(self.colidx, -7)
+        grp, gci = Guarded(self.n + 1, self.rowptr.dtype), Guarded(self.nnz, torch.int32)
+        new_rowptr, new_colidx = grp.t, gci.t
         ws = ep.workspace(ep.graph_reorder_workspace_bytes(self.n, self.nnz), DEV)
         ep.graph_reorder(self.n, self.nnz, self.rowptr, self.colidx, new_id, order, new_rowptr, new_colidx, ws)
         torch.cuda.synchronize()
+        grp.check(), gci.check()
         return new_rowptr.cpu().numpy(), new_colidx.cpu().numpy()

@@ -11,11 +11,14 @@ import pytest
 import oracle
 from paper_2604_01000_amd import embedpart as ep
 
-HEADER = Path(__file__).resolve().parent.parent / "include" / "embedpart.h"
+INCLUDE = Path(__file__).resolve().parent.parent / "include"
+HEADER = INCLUDE / "embedpart.h"
+BENCH_HEADER = INCLUDE / "embedpart_bench.h"
 
 
 def _declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    assert sorted(h.name for h in INCLUDE.glob("*.h")) == ["embedpart.h", "embedpart_bench.h"]
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text() + BENCH_HEADER.read_text(), flags=re.S)
     text = re.sub(r"typedef struct.*?\}\s*\w+;", "", text, flags=re.S)
     return set(re.findall(r"\b(?:int|const char \*)\s*(\w+)\s*\(", text))
 
@@ -32,10 +35,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_binding_constants_equal_the_header():
-    text = HEADER.read_text()
+    text = HEADER.read_text() + BENCH_HEADER.read_text()
     defines = dict(re.findall(r"#define\s+(EP_\w+)\s+\(?(-?\d+)\)?\s", text))
     for name in ("EP_OK", "EP_EINVAL", "EP_EUNSUPPORTED", "EP_EWORKSPACE", "EP_EHIP", "EP_F32", "EP_BF16",
-                 "EP_RUN_FINAL_REASSIGN", "EP_MAX_D", "EP_MAX_K", "EP_BALANCE_MAX_K", "EP_BALANCE_MAX_ROUNDS", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
+                 "EP_RUN_FINAL_REASSIGN", "EP_UPDATE_ACCUMULATE", "EP_UPDATE_FINALIZE", "EP_MAX_D", "EP_MAX_K", "EP_BALANCE_MAX_K", "EP_BALANCE_MAX_ROUNDS", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
                  "EP_PROF_EDGE_SWEEP"):
         assert int(defines[name]) == getattr(ep, name), name
     assert "((int64_t)1 << 31)" in text and ep.EP_MAX_N == 1 << 31
@@ -60,8 +63,11 @@ def test_bad_problems_are_rejected_on_the_host(kw, code):
     out = C.c_size_t(0)
     assert L.kmeans_workspace_bytes(C.byref(p), C.byref(out)) == code
     fake = C.c_void_p(0x1000)
-    assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, fake, 1 << 40, None) == code
     assert L.kmeans_run(C.byref(p), fake, 3, fake, fake, fake, None, 0, fake, 1 << 40, None) == code
+    assert L.kmeans_run_noalloc(C.byref(p), fake, 3, fake, fake, fake, None, 0, None) == code
+    if kw != dict(k=1001):   # a row range of a larger matrix may hold fewer rows than there are clusters
+        assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, fake, 1 << 40, None) == code
+        assert L.kmeans_update(C.byref(p), fake, fake, fake, fake, fake, 2, fake, 1 << 40, None) == code
 
 
 def test_null_pointers_workspace_and_flags():
@@ -79,8 +85,15 @@ def test_null_pointers_workspace_and_flags():
     assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, None, need, None) == ep.EP_EWORKSPACE
     assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, ws, need - 1, None) == ep.EP_EWORKSPACE
     assert L.kmeans_assign(C.byref(p), fake, fake, fake, None, None, C.c_void_p(0x100010), need, None) == ep.EP_EWORKSPACE
-    assert L.kmeans_update(C.byref(p), fake, None, fake, fake, fake, ws, need, None) == ep.EP_EINVAL
-    assert L.kmeans_update(C.byref(p), fake, fake, fake, fake, None, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_update(C.byref(p), fake, None, fake, fake, fake, 2, ws, need, None) == ep.EP_EINVAL
+    assert L.kmeans_update(C.byref(p), fake, fake, fake, fake, None, 2, ws, need, None) == ep.EP_EINVAL   # finalizing
+    assert L.kmeans_update(C.byref(p), fake, fake, fake, None, fake, 3, ws, need, None) == ep.EP_EINVAL   # needs outputs
+    assert L.kmeans_update(C.byref(p), fake, fake, fake, fake, fake, 4, ws, need, None) == ep.EP_EINVAL   # unknown flag
+    assert L.kmeans_update(C.byref(p), fake, fake, None, None, None, 1, None, need, None) == ep.EP_EWORKSPACE
+    assert L.ep_validate_labels(0, 4, fake, fake, None) == ep.EP_EINVAL
+    assert L.ep_validate_labels(10, 0, fake, fake, None) == ep.EP_EINVAL
+    assert L.ep_validate_labels(10, 4, None, fake, None) == ep.EP_EINVAL
+    assert L.ep_validate_labels(10, 4, fake, C.c_void_p(0x1004), None) == ep.EP_EINVAL
     assert L.kmeans_run(C.byref(p), fake, -1, fake, fake, fake, None, 0, ws, need, None) == ep.EP_EINVAL
     assert L.kmeans_run(C.byref(p), fake, 1, fake, fake, fake, None, 8, ws, need, None) == ep.EP_EINVAL
     idx = (C.c_int64 * 8)(*range(8))
