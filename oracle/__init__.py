@@ -52,9 +52,14 @@ def lib():
         L.or_assign.restype = C.c_double
         L.or_update.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, p, p, p]
         L.or_update.restype = C.c_int32
+        L.or_validate_labels.argtypes = [C.c_int64, C.c_int32, p, p]
+        L.or_validate_labels.restype = None
         L.or_lloyd.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, C.c_int32, p, C.c_int,
                                p, p, p, p, p]
         L.or_lloyd.restype = C.c_int
+        L.or_lloyd_bounds.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, C.c_int32, p, C.c_int, C.c_int,
+                                      p, p, p, p, p, p, p]
+        L.or_lloyd_bounds.restype = C.c_int
         L.or_sampled_kmeans.argtypes = [C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, C.c_int64, p, C.c_int32,
                                         C.c_int, p, p, p, p, p]
         L.or_sampled_kmeans.restype = C.c_int
@@ -141,6 +146,14 @@ def update(X, labels, C_prev):
     return Cn, counts, empty
 
 
+def validate_labels(labels, k: int):
+    """Returns (number of labels outside [0, k), index of the first one or n)."""
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    out = np.empty(2, dtype=np.int64)
+    lib().or_validate_labels(labels.shape[0], k, _ptr(labels), _ptr(out))
+    return int(out[0]), int(out[1])
+
+
 def lloyd(X, k: int, iters: int, idx, flags: int = 0):
     """Returns dict(C, labels, counts, obj_hist, obj_final)."""
     X, ld = _x32(X)
@@ -157,6 +170,29 @@ def lloyd(X, k: int, iters: int, idx, flags: int = 0):
     if rc != 0:
         raise ValueError("lloyd: bad arguments")
     return dict(C=Cc, labels=labels, counts=counts, obj_hist=hist[:iters], obj_final=fin.value)
+
+
+def lloyd_bounds(X, k: int, iters: int, idx, flags: int = 0, audit: bool = False):
+    """Lloyd rounds with bounds and incremental sums.  Returns dict(C, labels, counts, obj_hist, skipped, moved,
+    violations); with audit every skipped point is searched anyway and `violations` counts the labels that
+    would have changed."""
+    X, ld = _x32(X)
+    n, d = X.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    assert idx.shape == (k,)
+    Cc = np.empty((k, d), dtype=np.float64)
+    labels = np.empty(n, dtype=np.int32)
+    counts = np.zeros(k, dtype=np.int64)
+    hist = np.empty(max(iters, 1), dtype=np.float64)
+    skipped = np.zeros(max(iters, 1), dtype=np.int64)
+    moved = np.zeros(max(iters, 1), dtype=np.int64)
+    viol = C.c_int64(0)
+    rc = lib().or_lloyd_bounds(n, d, k, _ptr(X), ld, iters, _ptr(idx), flags, int(audit), _ptr(Cc), _ptr(labels),
+                               _ptr(counts), _ptr(hist), _ptr(skipped), _ptr(moved), C.addressof(viol))
+    if rc != 0:
+        raise ValueError("lloyd_bounds: bad arguments")
+    return dict(C=Cc, labels=labels, counts=counts, obj_hist=hist[:iters], skipped=skipped[:iters],
+                moved=moved[:iters], violations=viol.value)
 
 
 def sampled_kmeans(X, k: int, iters: int, rows, flags: int = 0):

@@ -31,6 +31,9 @@
  *
  * Pins (tests marked "not gpu"): brute force on integer coordinates, a
  * hand-worked 1-D Lloyd run, k = 1 and k = N special cases, separated blobs,
+ * a hand-counted label vector with ids outside [0, k); the rounds with bounds:
+ * equal to the plain rounds on every input tried, a hand-worked 1-D case
+ * with the skipped points named, an audit that searches every skipped point,
  * translation / permutation equivariance, monotone objective, mean property,
  * closed-form cuts on paths / cycles / complete graphs / matchings,
  * adjacency-matrix brute force, balance extremes, permutation bijectivity;
@@ -187,6 +190,22 @@ int32_t or_update(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
     return empty;
 }
 
+/*
+ * Every vertex carries exactly one of the k partition ids (Sec. "Graph
+ * Partitioning": the partitions are disjoint and cover V).  out[0] = number
+ * of labels outside [0, k), out[1] = index of the first one (n if none).
+ */
+void or_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *out)
+{
+    out[0] = 0;
+    out[1] = n;
+    for (int64_t i = 0; i < n; ++i) {
+        if (labels[i] >= 0 && labels[i] < k) continue;
+        if (out[0] == 0) out[1] = i;
+        out[0] += 1;
+    }
+}
+
 /* ---- Lloyd iterations ---------------------------------------------------- */
 
 /*
@@ -222,6 +241,150 @@ int or_lloyd(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
         double obj = or_assign(n, d, k, X, ld, C, q, labels, NULL, NULL);
         if (obj_final) *obj_final = obj;
     }
+    return 0;
+}
+
+/* ---- Lloyd rounds with bounds and incremental sums ------------------------------ */
+
+/*
+ * The same Lloyd rounds as or_lloyd, reached with less work: an exact
+ * acceleration (the paper's contribution list and Sec. "Phase 2: Clustering
+ * and Balancing" leave the clustering algorithm of Phase 2 open to more
+ * advanced ones).  The scheme is the published one of Hamerly ("Making
+ * k-means even faster", SDM 2010), restated:
+ *   every point keeps  u >= distance to its own centroid  and
+ *                      l <= distance to every other centroid;
+ *   when the centroids move by delta_j, u grows by delta of the own centroid
+ *   and l shrinks by the largest delta among the others (triangle
+ *   inequality); a point with u < l cannot change its label and is skipped;
+ *   any other point is searched in full, which also renews its bounds;
+ *   the sums are kept between rounds: only a point that changes its label
+ *   is taken out of one sum and put into another.
+ * Round 1 is a full round.  The distances, and so the bounds, are those to
+ * the centroids as the distances use them (bf16-rounded with the flag).
+ * A relative slack of 1e-12 on the test keeps fp64 rounding of the bounds
+ * from ever deciding a label.
+ *   skipped[t], moved[t] : points not searched / points that changed label in
+ *                          round t (t = 0 .. iters-1; skipped[0] = 0); may be NULL
+ *   *violations          : with `audit` != 0 every skipped point is searched
+ *                          anyway and counted here if its label would have
+ *                          changed (must stay 0); may be NULL
+ * Outputs otherwise as or_lloyd (obj_hist by the definition, over all
+ * points).  OR_FLAG_FINAL_REASSIGN is not supported here (returns -1).
+ */
+int or_lloyd_bounds(int64_t n, int32_t d, int32_t k, const float *X, int64_t ld,
+                    int32_t iters, const int64_t *idx, int flags, int audit,
+                    double *C, int32_t *labels, int64_t *counts, double *obj_hist,
+                    int64_t *skipped, int64_t *moved, int64_t *violations)
+{
+    if (n < 1 || d < 1 || k < 1 || (int64_t)k > n || ld < d || iters < 0) return -1;
+    if (flags & OR_FLAG_FINAL_REASSIGN) return -1;
+    for (int32_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || idx[j] >= n) return -1;
+        for (int32_t m = 0; m < d; ++m)
+            C[(int64_t)j * d + m] = (double)X[idx[j] * ld + m];
+    }
+    const int q = (flags & OR_FLAG_BF16_CENTROIDS) ? 1 : 0;
+    const size_t kd = (size_t)k * d;
+    double *u = (double *)malloc((size_t)n * sizeof(double));
+    double *l = (double *)malloc((size_t)n * sizeof(double));
+    double *sum = (double *)calloc(kd, sizeof(double));
+    double *Cu = (double *)malloc(kd * sizeof(double));      /* centroids as the distances use them */
+    double *Cu_old = (double *)malloc(kd * sizeof(double));
+    double *delta = (double *)malloc((size_t)k * sizeof(double));
+    if (violations) *violations = 0;
+    for (int32_t j = 0; j < k; ++j) counts[j] = 0;
+
+    for (int32_t t = 0; t < iters; ++t) {
+        for (size_t e = 0; e < kd; ++e) Cu[e] = q ? or_round_bf16(C[e]) : C[e];
+        int64_t n_skipped = 0, n_moved = 0;
+        if (t == 0) {
+            /* a full round: nearest and second-nearest distance of every point, sums from scratch */
+            or_assign(n, d, k, X, ld, C, q, labels, u, l);
+            for (int64_t i = 0; i < n; ++i) {
+                u[i] = sqrt(u[i]);
+                l[i] = sqrt(l[i]);                       /* HUGE_VAL when k == 1 */
+                for (int32_t m = 0; m < d; ++m) sum[(int64_t)labels[i] * d + m] += (double)X[i * ld + m];
+                counts[labels[i]] += 1;
+            }
+            n_moved = n;
+        } else {
+            /* the centroids moved since the bounds were taken */
+            double first = 0.0, second = 0.0;            /* largest and second-largest movement */
+            int32_t jfirst = -1;
+            for (int32_t j = 0; j < k; ++j) {
+                double s2 = 0.0;
+                for (int32_t m = 0; m < d; ++m) {
+                    double diff = Cu[(int64_t)j * d + m] - Cu_old[(int64_t)j * d + m];
+                    s2 += diff * diff;
+                }
+                delta[j] = sqrt(s2);
+                if (delta[j] > first) { second = first; first = delta[j]; jfirst = j; }
+                else if (delta[j] > second) { second = delta[j]; }
+            }
+            for (int64_t i = 0; i < n; ++i) {
+                const float *x = X + i * ld;
+                const int32_t a = labels[i];
+                u[i] += delta[a];
+                l[i] -= (a == jfirst) ? second : first;
+                const int skip = u[i] < l[i] * (1.0 - 1e-12);
+                if (skip && !audit) { ++n_skipped; continue; }
+                /* full search, as in or_assign */
+                double dmin = HUGE_VAL, dsec = HUGE_VAL;
+                int32_t jmin = 0;
+                for (int32_t j = 0; j < k; ++j) {
+                    const double *c = Cu + (int64_t)j * d;
+                    double d2 = 0.0;
+                    for (int32_t m = 0; m < d; ++m) {
+                        double diff = (double)x[m] - c[m];
+                        d2 += diff * diff;
+                    }
+                    if (d2 < dmin) { dsec = dmin; dmin = d2; jmin = j; }
+                    else if (d2 < dsec) { dsec = d2; }
+                }
+                if (skip) {                               /* audit: the bounds promised that nothing changes */
+                    ++n_skipped;
+                    if (jmin != a && violations) *violations += 1;
+                    continue;
+                }
+                u[i] = sqrt(dmin);
+                l[i] = sqrt(dsec);
+                if (jmin != a) {
+                    for (int32_t m = 0; m < d; ++m) {
+                        sum[(int64_t)a * d + m] -= (double)x[m];
+                        sum[(int64_t)jmin * d + m] += (double)x[m];
+                    }
+                    counts[a] -= 1;
+                    counts[jmin] += 1;
+                    labels[i] = jmin;
+                    ++n_moved;
+                }
+            }
+        }
+        if (obj_hist) {                                   /* by the definition, over all points */
+            double obj = 0.0;
+            for (int64_t i = 0; i < n; ++i) {
+                const double *c = Cu + (int64_t)labels[i] * d;
+                double d2 = 0.0;
+                for (int32_t m = 0; m < d; ++m) {
+                    double diff = (double)X[i * ld + m] - c[m];
+                    d2 += diff * diff;
+                }
+                obj += d2;
+            }
+            obj_hist[t] = obj;
+        }
+        if (skipped) skipped[t] = n_skipped;
+        if (moved) moved[t] = n_moved;
+        /* update step from the kept sums; an empty cluster keeps its centroid */
+        memcpy(Cu_old, Cu, kd * sizeof(double));
+        for (int32_t j = 0; j < k; ++j) {
+            if (counts[j] == 0) continue;
+            for (int32_t m = 0; m < d; ++m)
+                C[(int64_t)j * d + m] = sum[(int64_t)j * d + m] / (double)counts[j];
+        }
+    }
+    free(u); free(l); free(sum); free(Cu); free(Cu_old); free(delta);
     return 0;
 }
 

@@ -322,3 +322,15 @@ def test_sampled_order_of_the_sample_names_the_start_and_bad_arguments():
         oracle.sampled_kmeans(X, 3, 2, rows[:2])                   # fewer sample rows than clusters
     with pytest.raises(ValueError):
         oracle.sampled_kmeans(X, 3, 2, np.array([0, 1, 2, 300]))   # row out of range
+
+
+def test_validate_labels_hand_counted():
+    """Ids outside [0, k) counted by hand: k = 3, labels 0 3 -1 2 5 1 -> three offenders (3, -1, 5), the first at
+    index 1; a clean vector -> none, first = n."""
+    assert oracle.validate_labels([0, 3, -1, 2, 5, 1], 3) == (3, 1)
+    assert oracle.validate_labels([0, 1, 2, 2, 1], 3) == (0, 5)
+    assert oracle.validate_labels([2, 2, 2], 2) == (3, 0)
+    rng = np.random.default_rng(3)
+    lab = rng.integers(-2, 9, size=1000).astype(np.int32)
+    bad = np.nonzero((lab < 0) | (lab >= 7))[0]
+    assert oracle.validate_labels(lab, 7) == (len(bad), int(bad[0]))
