@@ -219,6 +219,51 @@ def run_workload(name: str, steps: int, warmup: int, cpu_seconds: float, variant
         step()
         torch.cuda.synchronize()
 
+    # ---- the same Lloyd rounds with distance bounds and kept sums (EP_RUN_BOUNDS): points whose bounds show that
+    # ---- their label cannot change are not read.  Timed beside the step (kmeans_init + kmeans_run only, with and
+    # ---- without the flag); `searched` is the number of rows read in each round, bytes_read_per_round what that
+    # ---- amounts to (a searched row + its label, plus 12 bytes of bounds and label per row in a bounded round)
+    bounded = None
+    if variants:
+        flags = ep.EP_RUN_BOUNDS
+        try:
+            bws = ep.workspace(ep.kmeans_run_workspace_bytes(p, w.iters, flags), dev)
+            hist_b = torch.zeros(w.iters + 1, dtype=torch.float64, device=dev)
+            labels_b = torch.empty_like(labels)
+            counts_b = torch.empty_like(counts)
+            C_b = torch.empty_like(Cc)
+            searched = torch.zeros(w.iters, dtype=torch.int64, device=dev)
+
+            def timed_runs(run_flags, lab, cnt, hst, Cx, wsx):
+                ep.kmeans_init(p, X, idx, Cx, wsx)
+                ep.kmeans_run(p, X, w.iters, Cx, lab, cnt, hst, run_flags, wsx)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(steps):
+                    ep.kmeans_init(p, X, idx, Cx, wsx)
+                    ep.kmeans_run(p, X, w.iters, Cx, lab, cnt, hst, run_flags, wsx)
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / steps
+
+            ms_b = timed_runs(flags, labels_b, counts_b, hist_b, C_b, bws)
+            ms_plain = timed_runs(0, labels, counts, hist, Cc, ws)
+            ep.kmeans_run_searched(p, w.iters, flags, bws, searched)
+            torch.cuda.synchronize()
+            sr = searched.cpu().tolist()
+            row_bytes = w.d * (2 if w.dtype == "bf16" else 4) + 4
+            bounded = dict(ms=ms_b, ms_plain_rounds=ms_plain, speedup=ms_plain / ms_b,
+                           Mpts_iter_per_s=w.n * w.iters / (ms_b * 1e-3) / 1e6, searched_per_round=sr,
+                           bytes_read_per_round=[r * row_bytes + (12 * w.n if t > 2 else 0) for t, r in enumerate(sr)],
+                           bytes_read_per_round_plain=w.n * row_bytes,
+                           labels_differing_from_plain=int((labels_b != labels).sum().item()),
+                           objective=float(hist_b[w.iters - 1].item()), objective_plain=float(hist[w.iters - 1].item()))
+            del bws, labels_b
+        except ep.EmbedPartError as e:      # the flag has no bounded kernels for this shape: the rounds run in full
+            if e.code != ep.EP_EUNSUPPORTED:
+                raise
+            bounded = dict(note="no bounded kernels for this shape (k > 64): the flag is accepted and the rounds run in full")
+
     # ---- the balancing loops of the paper's Alg. 3 on the K-Means partition (partition-scale k only):
     # ---- three vertex classes (seeded: 55% / 15% / 30%), beta = 1.05, timed beside the step ----
     balance = None
@@ -333,7 +378,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_seconds: float, variant
                             step="kmeans_init + kmeans_run + partition_quality" +
                                  (" + partition_permutation + edge_gap_sum" if reorder else "")),
                 roofline=roofline, edge_sweep=edge_sweep, cpu_baseline=cpu, reference=reference, quality=quality,
-                sampled_variant=sampled, balance_variant=balance, reorder_variant=rewrite,
+                sampled_variant=sampled, bounds_variant=bounded, balance_variant=balance, reorder_variant=rewrite,
                 labels_checksum=int(np.bitwise_xor.reduce(result_labels.astype(np.int64) * (np.arange(w.n) % 9973 + 1))))
 
 

@@ -51,6 +51,7 @@ extern "C" {
 
 /* kmeans_run flags */
 #define EP_RUN_FINAL_REASSIGN 1  /* one more assignment against the final centroids */
+#define EP_RUN_BOUNDS         2  /* skip points whose distance bounds show that their label cannot change */
 
 /* kmeans_update flags */
 #define EP_UPDATE_ACCUMULATE 1   /* add this call's rows to the sums and counts that earlier calls left in ws */
@@ -178,6 +179,35 @@ int ep_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *res
 int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
                int32_t *labels, int64_t *counts, double *objective_hist, int flags,
                void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * EP_RUN_BOUNDS: the same Lloyd rounds reached with less work (the paper's contribution list and
+ * Sec. "Phase 2: Clustering and Balancing" leave Phase 2 open to more advanced clustering
+ * algorithms; this is the exact one of Hamerly, "Making k-means even faster", SDM 2010).  Every
+ * point keeps an upper bound on the distance to its own centroid and a lower bound on the distance
+ * to all others; after an update the bounds are moved by how far the centroids moved, and a point
+ * whose bounds still separate is not read at all in the next round.  The per-cluster sums are kept
+ * in fp64 between rounds and only rows that change label are moved between them.  The first two
+ * rounds are ordinary ones, the third searches every point to take the bounds.
+ *   Results: a searched point goes through the score arithmetic of the plain rounds and the bounds
+ *   leave room for its rounding, so from equal centroids a round gives the labels of the plain round
+ *   bit for bit.  The centroids themselves agree with the plain run's to the order of the fp64
+ *   additions (about 1e-7 relative: kept sums against sums from scratch), which can decide a near-tie
+ *   the other way in a later round; every round still is an exact Lloyd round of its own centroids.
+ *   A run of T1 rounds followed by one of T2 is therefore not bit-equal to T1 + T2 rounds in one run,
+ *   as it is without the flag; the run itself is bit-reproducible.
+ *   Shapes: k in [2, 64], d = 64 or 128, fp32 or bfloat16 rows, iters >= 3; for any other shape the
+ *   flag is accepted and the rounds run in full.
+ *   Workspace: kmeans_run_workspace_bytes(p, iters, flags), which grows by 12 bytes per row.
+ * kmeans_run_workspace_bytes with flags without EP_RUN_BOUNDS equals kmeans_workspace_bytes.
+ * kmeans_run_searched copies out, from the workspace of a finished kmeans_run with EP_RUN_BOUNDS
+ * (same p, iters, flags), the number of rows whose distances were evaluated in each round:
+ *   searched  iters int64, 8-byte aligned, written (n for the full rounds);
+ *   EP_EUNSUPPORTED when the flag has no effect on this shape.
+ */
+int kmeans_run_workspace_bytes(const ep_problem *p, int32_t iters, int flags, size_t *bytes_host);
+int kmeans_run_searched(const ep_problem *p, int32_t iters, int flags, const void *ws, size_t ws_bytes,
+                        int64_t *searched, void *stream);
 
 /*
  * kmeans_run for callers that cannot allocate device memory or carry a workspace: code under

@@ -94,10 +94,65 @@ int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colid
     return EP_OK;
 }
 
+// Full rounds before the first bounded one: while the centroids still move far, no bound survives a round.
+constexpr int32_t kBoundsWarmRounds = 2;
+
+bool bounds_in_use(const ep_problem &p, int32_t iters, int flags) {
+    return (flags & EP_RUN_BOUNDS) && bounds_path_supported(p) && iters > kBoundsWarmRounds;
+}
+
+// Layout of a kmeans_run workspace: the K-Means workspace, then (EP_RUN_BOUNDS) the bounds and the lists.
+size_t run_ws_bytes(const ep_problem &p, int32_t iters, int flags) {
+    size_t bytes = align_up(carve_kmeans_ws(p, nullptr).bytes, 256);
+    if ((flags & EP_RUN_BOUNDS) && bounds_path_supported(p)) bytes += carve_bounds_ws(p, iters, nullptr).bytes;
+    return bytes;
+}
+BoundsWs bounds_ws_of(const ep_problem &p, int32_t iters, void *ws) {
+    return carve_bounds_ws(p, iters, static_cast<char *>(ws) + align_up(carve_kmeans_ws(p, nullptr).bytes, 256));
+}
+
+// `iters` rounds with EP_RUN_BOUNDS: kBoundsWarmRounds full rounds (the last one leaves its sums), one round
+// that searches every point to take the first bounds, then rounds that search only what the bounds let through.
+int run_rounds_bounded(const ep_problem &p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
+                       double *objective_hist, const KmeansWs &w, const BoundsWs &b, hipStream_t s) {
+    int rc = EP_OK;
+    const UpdateAcc keep{w.acc_sum, w.acc_cnt, w.chunk_cnt, EP_UPDATE_FINALIZE | kUpdateKeep};
+    const UpdateAcc add{w.acc_sum, w.acc_cnt, w.chunk_cnt, EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE | kUpdateKeep};
+    for (int32_t t = 0; t < kBoundsWarmRounds; ++t) {
+        const bool last_full = t == kBoundsWarmRounds - 1;
+        double *obj = objective_hist ? objective_hist + t : nullptr;   // round 1 also forms sum ||x||^2, kept for later
+        if ((rc = launch_small_round(p, X, C, w, labels, counts, obj, t == 0, s, last_full ? keep : whole_update())) != EP_OK)
+            return rc;
+        if (last_full && (rc = launch_accumulate_counts(p.k, keep, s)) != EP_OK) return rc;
+        if ((rc = launch_record_searched(p.n, b.searched + t, s)) != EP_OK) return rc;
+    }
+    for (int32_t t = kBoundsWarmRounds; t < iters; ++t) {
+        const bool all_points = t == kBoundsWarmRounds;
+        if (all_points) rc = launch_record_searched(p.n, b.searched + t, s);
+        else rc = launch_bounds_pass(p, labels, b, b.searched + t, s);
+        if (rc != EP_OK) return rc;
+        if ((rc = launch_keep_centroids(p, C, b, s)) != EP_OK) return rc;
+        if ((rc = launch_bounds_round(p, X, C, w, b, all_points, labels, s)) != EP_OK) return rc;
+        if ((rc = launch_small_finalize_parts(p, bounds_round_parts(p), C, counts, w, add, s)) != EP_OK) return rc;
+        if ((rc = launch_accumulate_counts(p.k, add, s)) != EP_OK) return rc;
+        if (objective_hist &&
+            (rc = launch_objective_from_sums(p, w, b, small_xsq_total(w), objective_hist + t, s)) != EP_OK)
+            return rc;
+        if (t + 1 < iters && (rc = launch_drift(p, C, b, s)) != EP_OK) return rc;
+    }
+    return EP_OK;
+}
+
 // `iters` Lloyd rounds from the centroids in C (see kmeans_run in the header).
 int run_rounds(const ep_problem &p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
-               double *objective_hist, int flags, const KmeansWs &w, hipStream_t s) {
+               double *objective_hist, int flags, const KmeansWs &w, hipStream_t s, void *ws_base = nullptr) {
     int rc = EP_OK;
+    if (ws_base && bounds_in_use(p, iters, flags)) {
+        rc = run_rounds_bounded(p, X, iters, C, labels, counts, objective_hist, w, bounds_ws_of(p, iters, ws_base), s);
+        if (rc == EP_OK && (flags & EP_RUN_FINAL_REASSIGN))
+            rc = do_assign(p, X, C, w, labels, nullptr, objective_hist ? objective_hist + iters : nullptr, s);
+        return rc;
+    }
     if (small_path_supported(p)) {  // fused rounds: X is read once per round
         for (int32_t t = 0; t < iters; ++t)
             if ((rc = launch_small_round(p, X, C, w, labels, counts, objective_hist ? objective_hist + t : nullptr,
@@ -272,17 +327,39 @@ int ep_validate_labels(int64_t n, int32_t k, const int32_t *labels, int64_t *res
     return launch_validate_labels(n, k, labels, result, static_cast<hipStream_t>(stream));
 }
 
+int kmeans_run_workspace_bytes(const ep_problem *p, int32_t iters, int flags, size_t *bytes_host) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!bytes_host || iters < 0 || (flags & ~(EP_RUN_FINAL_REASSIGN | EP_RUN_BOUNDS))) return EP_EINVAL;
+    *bytes_host = run_ws_bytes(*p, iters, flags);
+    return EP_OK;
+}
+
 int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
                double *objective_hist, int flags, void *ws, size_t ws_bytes, void *stream) {
     int rc = check_problem(p);
     if (rc != EP_OK) return rc;
     if ((rc = check_x(p, X)) != EP_OK) return rc;
-    if (!C || !labels || !aligned(labels, 16) || !counts || iters < 0 || (flags & ~EP_RUN_FINAL_REASSIGN))
+    if (!C || !labels || !aligned(labels, 16) || !counts || iters < 0 ||
+        (flags & ~(EP_RUN_FINAL_REASSIGN | EP_RUN_BOUNDS)))
         return EP_EINVAL;
-    if ((rc = check_ws(ws, ws_bytes, carve_kmeans_ws(*p, nullptr).bytes)) != EP_OK) return rc;
+    if ((rc = check_ws(ws, ws_bytes, run_ws_bytes(*p, iters, flags))) != EP_OK) return rc;
     const KmeansWs w = carve_kmeans_ws(*p, ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return run_rounds(*p, X, iters, C, labels, counts, objective_hist, flags, w, s);
+    return run_rounds(*p, X, iters, C, labels, counts, objective_hist, flags, w, s, ws);
+}
+
+int kmeans_run_searched(const ep_problem *p, int32_t iters, int flags, const void *ws, size_t ws_bytes,
+                        int64_t *searched, void *stream) {
+    int rc = check_problem(p);
+    if (rc != EP_OK) return rc;
+    if (!searched || !aligned(searched, 8) || iters < 1 || !(flags & EP_RUN_BOUNDS) ||
+        (flags & ~(EP_RUN_FINAL_REASSIGN | EP_RUN_BOUNDS)))
+        return EP_EINVAL;
+    if (!bounds_in_use(*p, iters, flags)) return EP_EUNSUPPORTED;
+    if ((rc = check_ws(ws, ws_bytes, run_ws_bytes(*p, iters, flags))) != EP_OK) return rc;
+    return launch_copy_searched(iters, bounds_ws_of(*p, iters, const_cast<void *>(ws)), searched,
+                                static_cast<hipStream_t>(stream));
 }
 
 int kmeans_run_noalloc(const ep_problem *p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,

@@ -24,8 +24,9 @@ struct UpdateAcc {
     double *sum;         // [k*d] sums of the chunks seen so far
     int64_t *cnt;        // [k]   their counts
     int64_t *chunk_cnt;  // [k]   counts of the current call (added to cnt after a call that does not finalize)
-    int flags;           // EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE
+    int flags;           // EP_UPDATE_ACCUMULATE | EP_UPDATE_FINALIZE | kUpdateKeep
 };
+constexpr int kUpdateKeep = 4;   // internal: a finalizing call also leaves the sums and counts (bounded rounds)
 inline UpdateAcc whole_update() { return UpdateAcc{nullptr, nullptr, nullptr, EP_UPDATE_FINALIZE}; }
 
 #ifdef __HIPCC__
@@ -39,10 +40,11 @@ __device__ __forceinline__ void finish_centroid_element(const UpdateAcc &a, int6
                                                         float *__restrict__ C_out, int64_t *__restrict__ counts) {
     if (a.flags & EP_UPDATE_ACCUMULATE) tot += a.sum[at];
     if (a.flags & EP_UPDATE_FINALIZE) {
-        if (a.flags & EP_UPDATE_ACCUMULATE) cnt += a.cnt[j];
-        C_out[at] = cnt > 0 ? (float)(tot / (double)cnt) : C_prev[at];
-        if (first_column) counts[j] = cnt;
-    } else {
+        const int64_t all = (a.flags & EP_UPDATE_ACCUMULATE) ? cnt + a.cnt[j] : cnt;
+        C_out[at] = all > 0 ? (float)(tot / (double)all) : C_prev[at];
+        if (first_column) counts[j] = all;
+    }
+    if (!(a.flags & EP_UPDATE_FINALIZE) || (a.flags & kUpdateKeep)) {
         a.sum[at] = tot;
         if (first_column) a.chunk_cnt[j] = cnt;
     }
@@ -111,7 +113,45 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 // first_round: the data-only term of the objective (sum ||x||^2) is computed and kept in the
 // workspace; later rounds of the same kmeans_run reuse it.
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
-                       int64_t *counts, double *objective, bool first_round, hipStream_t s);
+                       int64_t *counts, double *objective, bool first_round, hipStream_t s,
+                       const UpdateAcc &acc = whole_update());
+// Second pass over `parts` per-workgroup partials that another kernel left in w.psum / w.pcnt (the bounded
+// rounds): C <- means in place, no objective.
+int launch_small_finalize_parts(const ep_problem &p, int parts, float *C, int64_t *counts, const KmeansWs &w,
+                                const UpdateAcc &acc, hipStream_t s);
+// Where the fused rounds keep sum ||x||^2 between the rounds of a run.
+double *small_xsq_total(const KmeansWs &w);
+
+// ---- K-Means, k <= 64: rounds with distance bounds and incremental sums (kmeans_bounds.hip) ---------
+struct BoundsWs {
+    float *ub;               // [n] upper bound on the distance to the own centroid
+    float *lb;               // [n] lower bound on the distance to every other centroid
+    int32_t *active_idx;     // [n] rows to search this round, ascending
+    int32_t *block_counts;   // per-workgroup counts of the bounds pass
+    int64_t *block_offsets;  // their exclusive scan
+    int64_t *n_active;       // [1] rows to search this round
+    int64_t *searched;       // [iters] rows searched per round of the run
+    float *delta;            // [k] centroid movement of the last update
+    unsigned char *top;      // its two largest values, the centroid that moved most, max ||c||^2
+    float *C_old;            // [k*d] the centroids the round's assignment used
+    size_t bytes;
+};
+bool bounds_path_supported(const ep_problem &p);
+BoundsWs carve_bounds_ws(const ep_problem &p, int32_t iters, void *ws);
+int bounds_round_parts(const ep_problem &p);
+int launch_record_searched(int64_t value, int64_t *slot, hipStream_t s);
+int launch_copy_searched(int32_t iters, const BoundsWs &w, int64_t *out, hipStream_t s);
+int launch_keep_centroids(const ep_problem &p, const float *C, const BoundsWs &w, hipStream_t s);
+int launch_drift(const ep_problem &p, const float *C_new, const BoundsWs &w, hipStream_t s);
+int launch_objective_from_sums(const ep_problem &p, const KmeansWs &kw, const BoundsWs &w, const double *xsq_total,
+                               double *objective, hipStream_t s);
+// Applies the last drift to every point's bounds and lists the rows whose bounds no longer separate.
+int launch_bounds_pass(const ep_problem &p, const int32_t *labels, const BoundsWs &w, int64_t *searched_slot,
+                       hipStream_t s);
+// Searches the listed rows (all rows with all_points), renews their bounds, updates labels in place and
+// leaves per-workgroup partial sums of the rows that changed label in kw.psum / kw.pcnt.
+int launch_bounds_round(const ep_problem &p, const void *X, const float *C, const KmeansWs &kw, const BoundsWs &w,
+                        bool all_points, int32_t *labels, hipStream_t s);
 
 // ---- K-Means, k > 64, bf16, d in {64,128}: bf16 matrix-core assignment (kmeans_large.hip) -------
 bool large_path_supported(const ep_problem &p);

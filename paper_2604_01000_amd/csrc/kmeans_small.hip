@@ -43,15 +43,11 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "small_common.h"
 
 namespace ep {
 
 namespace {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
@@ -62,67 +58,6 @@ constexpr int kLabelFlush = 64;                  // sub-tiles whose labels are w
 enum Mode { kAssignOnly = 0, kUpdateOnly = 1, kFused = 2 };
 
 
-__device__ __forceinline__ void wave_lds_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Reductions over the 16 lanes of a DPP row; every lane of the row gets the result.
-// Steps: xor 1, xor 2 (quad permutes), then mirror within 8 and within 16 lanes.
-template <int CTRL>
-__device__ __forceinline__ int dpp_i(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
-}
-__device__ __forceinline__ int row16_max(int v) {
-    v = max(v, dpp_i<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = max(v, dpp_i<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = max(v, dpp_i<0x141>(v));  // row_half_mirror
-    v = max(v, dpp_i<0x140>(v));  // row_mirror
-    return v;
-}
-__device__ __forceinline__ int row16_min(int v) {
-    v = min(v, dpp_i<0xB1>(v));
-    v = min(v, dpp_i<0x4E>(v));
-    v = min(v, dpp_i<0x141>(v));
-    v = min(v, dpp_i<0x140>(v));
-    return v;
-}
-// Order-preserving map between finite floats and signed integers (its own inverse).
-__device__ __forceinline__ int float_key(float f) {
-    const int b = __float_as_int(f);
-    return b ^ ((b >> 31) & 0x7fffffff);
-}
-__device__ __forceinline__ float key_float(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
-
-// x0 = h0 + m0 + l0 and x1 = h1 + m1 + l1 exactly, every term a bf16: each term is what is left,
-// rounded to nearest even (fp32 has 24 significant bits, bf16 has 8, and both remainders are exact
-// in fp32).  The results are packed two to a word, x0's in the low half.
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-struct Split3 {
-    unsigned h, m, l;
-};
-__device__ __forceinline__ Split3 split3_pair(float x0, float x1) {
-    Split3 t;
-    t.h = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{x0, x1}, bf16x2_t));
-    const float r0 = x0 - __uint_as_float(t.h << 16), r1 = x1 - __uint_as_float(t.h & 0xffff0000u);
-    t.m = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{r0, r1}, bf16x2_t));
-    const float s0 = r0 - __uint_as_float(t.m << 16), s1 = r1 - __uint_as_float(t.m & 0xffff0000u);
-    t.l = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{s0, s1}, bf16x2_t));
-    return t;
-}
-typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ f32x4 mfma_bf16_k16(const u32x2 &a, const u32x2 &b, const f32x4 &acc) {
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4_t, a), __builtin_bit_cast(bf16x4_t, b),
-                                                      acc, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mfma_bf16_k32(const u32x4 &a, const u32x4 &b, const f32x4 &acc) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
-                                                   acc, 0, 0, 0);
-}
-
 // Dynamic LDS of lloyd_small_kernel: floats (transposition tiles, or per-wave tables of sums for
 // k > 16) followed by the per-wave label buffers.
 template <int D, int KT>
@@ -132,44 +67,6 @@ struct SmallLds {
     static constexpr int kFloatBytes = (KT >= 2 ? kWaves * (16 * KT + 1) * kStride : kWaves * kSub * kStride) * 4;
     static constexpr int kBytes = kFloatBytes + kWaves * kFlush * kSub * 4;
 };
-
-// sums[label of point c][:] += x_c for the 16 points of a sub-tile, in LDS, without atomics and in
-// a fixed order.  Lane (g, c) holds a quarter of point c's row (columns 16 j + 4 g .. + 3).  Points
-// of the sub-tile that share a label must not update the same row at once, so every point gets
-// its rank among the earlier points with the same label (15 DPP row shifts) and round r handles
-// the points of rank r: rows touched in one round are distinct, and every row receives its
-// points in ascending order.  The padded row stride spreads different labels over the banks.
-template <int CTRL>
-__device__ __forceinline__ int row_shr(int v) {
-    return __builtin_amdgcn_update_dpp(-2, v, CTRL, 0xF, 0xF, false);   // lanes shifted in from outside keep -2
-}
-template <int R, int R_LAST = 15>
-__device__ __forceinline__ int same_label_before(int lab, int acc) {
-    if constexpr (R > R_LAST) {
-        return acc;
-    } else {
-        acc += row_shr<0x110 + R>(lab) == lab ? 1 : 0;
-        return same_label_before<R + 1, R_LAST>(lab, acc);
-    }
-}
-template <int NJ, int STRIDE>
-__device__ __forceinline__ void add_rows_to_lds_sums(const f32x4 (&x)[NJ], int32_t lab_c, int g, float *wsums,
-                                                     int32_t *cnt_lds) {
-    int rank = same_label_before<1>(lab_c, 0);
-    if (lab_c < 0) rank = -1;
-    if (g == 0 && lab_c >= 0) atomicAdd(&cnt_lds[lab_c], 1);   // integer: order does not matter
-    float *row = wsums + (lab_c < 0 ? 0 : lab_c) * STRIDE + 4 * g;
-    for (int r = 0; __ballot(rank >= r) != 0; ++r) {
-        if (rank == r) {
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                f32x4 *p = reinterpret_cast<f32x4 *>(row + 16 * j);
-                *p = *p + x[j];
-            }
-        }
-        wave_lds_fence();
-    }
-}
 
 // XSQ: also accumulate sum ||x||^2 (needed once per data set for the objective).
 // XT: element type of X.  bfloat16 rows are widened to fp32 as they arrive (exact) and the centroids
@@ -1072,8 +969,8 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 
 static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
                                  const KmeansWs &w, double *objective, bool fresh_xsq, const UpdateAcc &acc,
-                                 hipStream_t s) {
-    const int parts = small_blocks(p);
+                                 hipStream_t s, int parts = 0) {
+    if (parts == 0) parts = small_blocks(p);
     const int dpad = small_padded_d(p);
     lloyd_small_finalize_kernel<<<p.k * (dpad / kFinCols), kFinBlock, 0, s>>>(
         dpad, p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
@@ -1089,13 +986,20 @@ int launch_small_update(const ep_problem &p, const void *X, const int32_t *label
     return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, acc, s);
 }
 
+int launch_small_finalize_parts(const ep_problem &p, int parts, float *C, int64_t *counts, const KmeansWs &w,
+                                const UpdateAcc &acc, hipStream_t s) {
+    return launch_small_finalize(p, C, C, counts, w, nullptr, false, acc, s, parts);
+}
+
+double *small_xsq_total(const KmeansWs &w) { return xsq_total_of(w); }
+
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
-                       int64_t *counts, double *objective, bool first_round, hipStream_t s) {
+                       int64_t *counts, double *objective, bool first_round, hipStream_t s, const UpdateAcc &acc) {
     const bool fresh = objective && first_round;  // sum ||x||^2 is computed in the first round and kept
     int rc = fresh ? launch_mode<kFused, true>(p, X, C, w, labels, nullptr, nullptr, true, s)
                    : launch_mode<kFused, false>(p, X, C, w, labels, nullptr, nullptr, objective != nullptr, s);
     if (rc != EP_OK) return rc;
-    return launch_small_finalize(p, C, C, counts, w, objective, fresh, whole_update(), s);
+    return launch_small_finalize(p, C, C, counts, w, objective, fresh, acc, s);
 }
 
 }  // namespace ep

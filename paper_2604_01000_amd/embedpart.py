@@ -15,7 +15,7 @@ import torch
 _LIB_PATH = Path(__file__).resolve().parent / "libembedpart.so"
 
 EP_F32, EP_BF16 = 0, 1
-EP_RUN_FINAL_REASSIGN = 1
+EP_RUN_FINAL_REASSIGN, EP_RUN_BOUNDS = 1, 2
 EP_UPDATE_ACCUMULATE, EP_UPDATE_FINALIZE = 1, 2
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
 EP_MAX_D, EP_MAX_K, EP_MAX_N = 1024, 65536, 1 << 31   # limits stated in the header
@@ -24,7 +24,7 @@ EP_NOALLOC_SCRATCH_BYTES = 34 * 1024 * 1024
 
 SYMBOLS = (
     "ep_version", "ep_strerror", "ep_last_hip_error", "kmeans_init_indices", "kmeans_workspace_bytes",
-    "kmeans_init", "kmeans_assign", "kmeans_update", "ep_validate_labels", "kmeans_run", "kmeans_run_noalloc",
+    "kmeans_init", "kmeans_assign", "kmeans_update", "ep_validate_labels", "kmeans_run", "kmeans_run_workspace_bytes", "kmeans_run_searched", "kmeans_run_noalloc",
     "kmeans_sampled_workspace_bytes",
     "kmeans_run_sampled", "graph_workspace_bytes",
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.kmeans_update.argtypes = [pp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
         L.ep_validate_labels.argtypes = [i64, i32, vp, vp, vp]
         L.kmeans_run.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+        L.kmeans_run_workspace_bytes.argtypes = [pp, i32, C.c_int, C.POINTER(sz)]
+        L.kmeans_run_searched.argtypes = [pp, i32, C.c_int, vp, sz, vp, vp]
         L.kmeans_run_noalloc.argtypes = [pp, vp, i32, vp, vp, vp, vp, C.c_int, vp]
         L.kmeans_sampled_workspace_bytes.argtypes = [pp, i64, C.POINTER(sz)]
         L.kmeans_run_sampled.argtypes = [pp, vp, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -178,6 +180,17 @@ def ep_validate_labels(n, k, labels, result):
 def kmeans_run(p, X, iters, Cc, labels, counts, objective_hist, flags, ws):
     _check(lib().kmeans_run(C.byref(p), _ptr(X), iters, _ptr(Cc), _ptr(labels), _ptr(counts), _ptr(objective_hist),
                             flags, _ptr(ws), ws.numel(), _stream()), "kmeans_run")
+
+
+def kmeans_run_workspace_bytes(p: ep_problem, iters: int, flags: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().kmeans_run_workspace_bytes(C.byref(p), iters, flags, C.byref(out)), "kmeans_run_workspace_bytes")
+    return out.value
+
+
+def kmeans_run_searched(p, iters, flags, ws, searched):
+    _check(lib().kmeans_run_searched(C.byref(p), iters, flags, _ptr(ws), ws.numel(), _ptr(searched), _stream()),
+           "kmeans_run_searched")
 
 
 def kmeans_run_noalloc(p, X, iters, Cc, labels, counts, objective_hist, flags):

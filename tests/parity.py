@@ -88,7 +88,11 @@ class Kmeans:
         ghist = Guarded(iters + 1, torch.float64, self.X.device)
         hist = ghist.t
         hist.fill_(float("nan"))
-        ep.kmeans_run(self.p, self.X, iters, self.C, self.labels, self.counts, hist, flags, self.ws)
+        ws = self.ws
+        if flags & ep.EP_RUN_BOUNDS:    # the bounds and the search lists ride behind the K-Means workspace
+            ws = self.run_ws = ep.workspace(ep.kmeans_run_workspace_bytes(self.p, iters, flags), self.X.device)
+            ws.fill_(0xEE)              # nothing may rely on what the workspace held
+        ep.kmeans_run(self.p, self.X, iters, self.C, self.labels, self.counts, hist, flags, ws)
         self._sync_and_check(ghist)
         return dict(C=self.C.cpu().numpy(), labels=self.labels.cpu().numpy(), counts=self.counts.cpu().numpy(),
                     obj_hist=hist.cpu().numpy())
