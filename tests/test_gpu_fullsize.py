@@ -42,11 +42,43 @@ def _sampled_round_check(X, km, C_before, got, k, bf16, rng, n_points=4096, n_cl
         if members.numel() == 0:
             np.testing.assert_array_equal(got["C"][j], np.asarray(C_before, dtype=np.float32)[j])
             continue
-        Xm = X[members].to("cpu", torch.float32).numpy()
-        C_or, cnt_or, _ = oracle.update(Xm, np.zeros(len(Xm), dtype=np.int32), np.zeros((1, X.shape[1])))
-        assert cnt_or[0] == counts[j]
-        assert centroid_rel_err(got["C"][j:j + 1], C_or) <= CENTROID_RTOL
+        # the oracle's mean of the members, taken over chunks of 2^20 rows so that the host never holds more
+        # (the chunks' means are put together with their counts in fp64)
+        total, seen = np.zeros(X.shape[1]), 0
+        for lo in range(0, members.numel(), 1 << 20):
+            Xm = X[members[lo:lo + (1 << 20)]].to("cpu", torch.float32).numpy()
+            C_or, cnt_or, _ = oracle.update(Xm, np.zeros(len(Xm), dtype=np.int32), np.zeros((1, X.shape[1])))
+            total += C_or[0] * float(cnt_or[0])
+            seen += int(cnt_or[0])
+        assert seen == counts[j]
+        assert centroid_rel_err(got["C"][j:j + 1], (total / seen)[None, :]) <= CENTROID_RTOL
     return differing
+
+
+def _all_rounds(X, w, bf16, rng, sampled_rounds, n_points, n_clusters_last):
+    """The `iters` rounds the benchmark times, one device round at a time: every round's counts are the
+    histogram of its labels and add up to n, the objective never rises, and the rounds named in
+    `sampled_rounds` (the last one among them) are checked on samples against the oracle."""
+    idx = oracle.init_indices(w.seed, w.n, w.k)
+    km = Kmeans(X, w.k).init(idx)
+    objs, got, C_before = [], None, None
+    for t in range(w.iters):
+        C_before = km.C.cpu().numpy().astype(np.float64)
+        got = km.run(1)
+        counts = np.bincount(got["labels"], minlength=w.k)
+        np.testing.assert_array_equal(got["counts"], counts)
+        assert counts.sum() == w.n and got["labels"].min() >= 0 and got["labels"].max() < w.k
+        objs.append(got["obj_hist"][0])
+        note = ""
+        if t in sampled_rounds:
+            last = t == w.iters - 1
+            d = _sampled_round_check(X, km, C_before, got, w.k, bf16, rng, n_points=n_points,
+                                     n_clusters=n_clusters_last if last else 3)
+            note = f", sampled labels differing {d}"
+        print(f"{w.name} round {t + 1}: objective {objs[-1]:.6e}, empty clusters {int((counts == 0).sum())}{note}",
+              flush=True)
+    assert all(b <= a * (1 + 1e-9) for a, b in zip(objs, objs[1:])), objs      # non-increasing over all rounds
+    return km, got, C_before
 
 
 def _graph_check(w, labels_np, k, reorder=False):
@@ -119,21 +151,12 @@ def test_products_like_full():
 def test_products_reorder_full():
     w = synth.WORKLOADS["products_reorder"]
     X = synth.embeddings(w, DEV)
-    idx = oracle.init_indices(w.seed, w.n, w.k)
     rng = np.random.default_rng(7)
-    km = Kmeans(X, w.k).init(idx)
-    objs = []
-    for t in range(3):                                   # three rounds, each checked on samples
-        C_before = km.C.cpu().numpy().astype(np.float64)
-        got = km.run(1)
-        d = _sampled_round_check(X, km, C_before, got, w.k, True, rng)
-        objs.append(got["obj_hist"][0])
-        print(f"products_reorder round {t}: objective {objs[-1]:.6e}, sampled labels differing {d}, "
-              f"empty clusters {int((got['counts'] == 0).sum())}")
-    assert objs[1] <= objs[0] and objs[2] <= objs[1]
-    full = Kmeans(X, w.k).init(idx).run(3)               # the driver equals the three steps
+    km, got, _ = _all_rounds(X, w, True, rng, sampled_rounds={0, 1, 2, w.iters - 1}, n_points=4096, n_clusters_last=24)
+    full = Kmeans(X, w.k).init(oracle.init_indices(w.seed, w.n, w.k)).run(w.iters)   # the driver equals its steps
     np.testing.assert_array_equal(full["labels"], got["labels"])
     np.testing.assert_array_equal(full["C"], got["C"])
+    # the permutation, the gap sums and the rewritten graph of the FINAL labelling against the oracle's integer routines
     _graph_check(w, got["labels"], w.k, reorder=True)
 
 
@@ -143,18 +166,10 @@ def test_papers_like_full():
     if free < 150 * 2**30:
         pytest.skip("needs about 150 GB of free device memory")
     X = synth.embeddings(w, DEV)
-    idx = oracle.init_indices(w.seed, w.n, w.k)
     rng = np.random.default_rng(11)
-    km = Kmeans(X, w.k).init(idx)
-    objs = []
-    for t in range(2):
-        C_before = km.C.cpu().numpy().astype(np.float64)
-        got = km.run(1)
-        d = _sampled_round_check(X, km, C_before, got, w.k, False, rng, n_points=16384, n_clusters=3)
-        objs.append(got["obj_hist"][0])
-        print(f"papers_like round {t}: objective {objs[-1]:.6e}, sampled labels differing {d}")
-    assert objs[1] <= objs[0]
-    # a contiguous slice follows the oracle exactly: same rows, same centroids, lockstep
+    km, got, C_before = _all_rounds(X, w, False, rng, sampled_rounds={0, 1, w.iters - 1}, n_points=16384,
+                                    n_clusters_last=16)
+    # a contiguous slice of the last round follows the oracle exactly: same rows, same centroids, lockstep
     lo, hi = 55_000_000, 55_000_000 + (1 << 18)
     Xs = X[lo:hi].to("cpu", torch.float32).numpy()
     used = centroids_used(C_before, False)
