@@ -48,6 +48,7 @@ extern "C" {
 
 #define EP_F32  0             /* embeddings stored as IEEE binary32 */
 #define EP_BF16 1             /* embeddings stored as bfloat16; all accumulation is fp32 or wider */
+#define EP_F16  2             /* embeddings stored as IEEE binary16: widened to fp32 on arrival (exact), then as EP_F32 */
 
 /* kmeans_run flags */
 #define EP_RUN_FINAL_REASSIGN 1  /* one more assignment against the final centroids */
@@ -67,13 +68,13 @@ extern "C" {
 /* The clustering problem: n embeddings of dimension d, row-major with row
  * stride ld (elements, ld >= d), to be grouped into k clusters.
  * X must be 16-byte aligned; ld must be a multiple of 4 (EP_F32) or of 8
- * (EP_BF16), so that every row starts 16-byte aligned. */
+ * (EP_BF16, EP_F16), so that every row starts 16-byte aligned. */
 typedef struct ep_problem {
     int64_t n;
     int64_t ld;
     int32_t d;
     int32_t k;
-    int32_t dtype;     /* EP_F32 or EP_BF16 */
+    int32_t dtype;     /* EP_F32, EP_BF16 or EP_F16 */
     int32_t reserved;  /* must be 0 */
 } ep_problem;
 

@@ -35,7 +35,7 @@ int check_problem(const ep_problem *p) {
     if (!p) return EP_EINVAL;
     if (p->n < 1 || p->n >= EP_MAX_N || p->d < 1 || p->k < 1 || (int64_t)p->k > p->n || p->ld < p->d) return EP_EINVAL;
     if (p->reserved != 0) return EP_EINVAL;
-    if (p->dtype != EP_F32 && p->dtype != EP_BF16) return EP_EUNSUPPORTED;
+    if (p->dtype != EP_F32 && p->dtype != EP_BF16 && p->dtype != EP_F16) return EP_EUNSUPPORTED;
     if (p->d > EP_MAX_D || p->k > EP_MAX_K) return EP_EUNSUPPORTED;
     if (p->ld % (p->dtype == EP_F32 ? 4 : 8) != 0) return EP_EINVAL;
     return EP_OK;
@@ -185,9 +185,9 @@ struct SampledWs {
 SampledWs carve_sampled_ws(const ep_problem &p, int64_t m, void *ws) {
     Carver c(ws);
     SampledWs w{};
-    const int64_t unit = p.dtype == EP_BF16 ? 8 : 4;   // rows stay 16-byte aligned
+    const int64_t unit = 16 / elem_bytes(p.dtype);   // rows stay 16-byte aligned
     w.ld_s = (p.d + unit - 1) / unit * unit;
-    w.S = c.take<unsigned char>((size_t)m * (size_t)w.ld_s * (p.dtype == EP_BF16 ? 2 : 4));
+    w.S = c.take<unsigned char>((size_t)m * (size_t)w.ld_s * (size_t)elem_bytes(p.dtype));
     w.rows = c.take<int64_t>((size_t)m);
     w.labels = c.take<int32_t>((size_t)m);
     // one K-Means workspace serves the sample's rounds (m dense rows of stride ld_s) and then the

@@ -66,11 +66,22 @@ __device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
     return static_cast<bf16_t>(u >> 16);
 }
 
+typedef _Float16 f16_t;   // storage type of IEEE binary16 (widening to fp32 is exact)
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+inline int elem_bytes(int dtype) { return dtype == EP_F32 ? 4 : 2; }
+
 __device__ __forceinline__ float load_elem(const float *p) { return *p; }
+__device__ __forceinline__ float load_elem(const f16_t *p) { return (float)*p; }
 __device__ __forceinline__ float load_elem(const bf16_t *p) { return bf16_to_f32(*p); }
 
 // Four consecutive elements starting at a 4-element-aligned column.
 __device__ __forceinline__ float4 load4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 load4(const f16_t *p) {
+    const f32x4_t v = __builtin_convertvector(*reinterpret_cast<const f16x4_t *>(p), f32x4_t);
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
 __device__ __forceinline__ float4 load4(const bf16_t *p) {
     uint2 r = *reinterpret_cast<const uint2 *>(p);
     return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),

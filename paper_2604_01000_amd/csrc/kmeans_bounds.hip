@@ -257,7 +257,8 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     constexpr int NJ = D / 16;
     constexpr int NX = NJ;
     constexpr int STRIDE = D + 4;
-    constexpr bool kBf16 = !std::is_same<XT, float>::value;
+    constexpr bool kBf16 = std::is_same<XT, bf16_t>::value;
+    constexpr bool kHalf = std::is_same<XT, f16_t>::value;
     constexpr bool kSplit = KT >= 2 || kBf16;
     constexpr bool kThreeTerms = kSplit && !kBf16;
     constexpr int KS = D / 32;
@@ -296,6 +297,8 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
                 const u32x2 raw = *reinterpret_cast<const u32x2 *>(ptr + 16 * q);
                 dst[q] = f32x4{__uint_as_float(raw[0] << 16), __uint_as_float(raw[0] & 0xffff0000u),
                                __uint_as_float(raw[1] << 16), __uint_as_float(raw[1] & 0xffff0000u)};
+            } else if constexpr (kHalf) {
+                dst[q] = __builtin_convertvector(*reinterpret_cast<const f16x4_t *>(ptr + 16 * q), f32x4);
             } else {
                 dst[q] = *reinterpret_cast<const f32x4 *>(ptr + 16 * q);
             }
@@ -636,7 +639,9 @@ int launch_bounds_round(const ep_problem &p, const void *X, const float *C, cons
     } while (0)
 #define EP_BOUNDS_LAUNCH_T(D_, KT_)                                                                             \
     do {                                                                                                        \
-        if (p.dtype == EP_BF16) EP_BOUNDS_LAUNCH(D_, KT_, bf16_t); else EP_BOUNDS_LAUNCH(D_, KT_, float);       \
+        if (p.dtype == EP_BF16) EP_BOUNDS_LAUNCH(D_, KT_, bf16_t);                                              \
+        else if (p.dtype == EP_F16) EP_BOUNDS_LAUNCH(D_, KT_, f16_t);                                           \
+        else EP_BOUNDS_LAUNCH(D_, KT_, float);                                                                  \
     } while (0)
     if (p.d == 128) {
         if (kt == 1) EP_BOUNDS_LAUNCH_T(128, 1); else if (kt == 2) EP_BOUNDS_LAUNCH_T(128, 2); else EP_BOUNDS_LAUNCH_T(128, 4);

@@ -293,6 +293,11 @@ __device__ __forceinline__ void load8<float>(const float *p, float (&v)[8]) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 template <>
+__device__ __forceinline__ void load8<f16_t>(const f16_t *p, float (&v)[8]) {
+    const float4 a = load4(p), b = load4(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
 __device__ __forceinline__ void load8<bf16_t>(const bf16_t *p, float (&v)[8]) {
     const uint4 r = *reinterpret_cast<const uint4 *>(p);
     v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
@@ -412,6 +417,7 @@ __global__ __launch_bounds__(kBlock) void segment_mean_kernel(int32_t d, int32_t
 template <typename F>
 int by_dtype(const ep_problem &p, F &&f) {
     if (p.dtype == EP_F32) return f(static_cast<const float *>(nullptr));
+    if (p.dtype == EP_F16) return f(static_cast<const f16_t *>(nullptr));
     return f(static_cast<const bf16_t *>(nullptr));
 }
 

@@ -90,7 +90,8 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     // spend k/16 times the work of the scores on mostly-zero one-hot products, so every wave keeps
     // its own padded k x d table of sums in LDS and adds rows to it (see add_rows_to_lds_sums).
     constexpr bool kLdsSums = KT >= 2;
-    constexpr bool kBf16 = !std::is_same<XT, float>::value;
+    constexpr bool kBf16 = std::is_same<XT, bf16_t>::value;
+    constexpr bool kHalf = std::is_same<XT, f16_t>::value;   // widened on arrival, then handled as fp32 rows
     constexpr int kElem = (int)sizeof(XT);
     const int dr = PAD ? d : D;                  // columns that exist in memory
     constexpr int kOutOfRange = 0x7f000000;      // a byte offset beyond any sub-tile: the load returns zeros
@@ -245,6 +246,11 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
                                       : __builtin_amdgcn_raw_buffer_load_b64(rsrc, vr, 128 * (q % NH), kAux);
                 dst[q] = f32x4{__uint_as_float(raw[0] << 16), __uint_as_float(raw[0] & 0xffff0000u),
                                __uint_as_float(raw[1] << 16), __uint_as_float(raw[1] & 0xffff0000u)};
+            } else if constexpr (kHalf) {
+                const u32x2 raw = kPointPerLane
+                                      ? __builtin_amdgcn_raw_buffer_load_b64(rsrc, va, 32 * q, kAux)
+                                      : __builtin_amdgcn_raw_buffer_load_b64(rsrc, vr, 128 * (q % NH), kAux);
+                dst[q] = __builtin_convertvector(__builtin_bit_cast(f16x4_t, raw), f32x4);
             } else {
                 const u32x4 raw = kPointPerLane
                                       ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, va, 64 * q, kAux)
@@ -866,8 +872,7 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
                 float *best_score = nullptr) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
-    const bool bf16 = p.dtype == EP_BF16;
-    const bool stream_x = (double)p.n * (double)p.ld * (bf16 ? 2.0 : 4.0) > kLastLevelCacheBytes;
+    const bool stream_x = (double)p.n * (double)p.ld * (double)elem_bytes(p.dtype) > kLastLevelCacheBytes;
     double *sp = want_obj ? s_part_of(w) : nullptr;
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s, true);
 #define EP_SMALL_LAUNCH_P(D_, KT_, XT_, PAD_)                                                                 \
@@ -904,7 +909,9 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
     } while (0)
 #define EP_SMALL_LAUNCH(D_, KT_)                                                                              \
     do {                                                                                                      \
-        if (bf16) EP_SMALL_LAUNCH_T(D_, KT_, bf16_t); else EP_SMALL_LAUNCH_T(D_, KT_, float);                 \
+        if (p.dtype == EP_BF16) EP_SMALL_LAUNCH_T(D_, KT_, bf16_t);                                           \
+        else if (p.dtype == EP_F16) EP_SMALL_LAUNCH_T(D_, KT_, f16_t);                                        \
+        else EP_SMALL_LAUNCH_T(D_, KT_, float);                                                               \
     } while (0)
     const int dpad = small_padded_d(p);
     if (dpad == 256) {
@@ -924,7 +931,7 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
 }  // namespace
 
 bool small_path_supported(const ep_problem &p) {
-    return (p.dtype == EP_F32 || p.dtype == EP_BF16) && small_padded_d(p) != 0 && p.ld < ((int64_t)1 << 24);
+    return small_padded_d(p) != 0 && p.ld < ((int64_t)1 << 24);
 }
 
 int small_blocks(const ep_problem &p) { return geometry(p.n).blocks; }
@@ -946,7 +953,7 @@ int launch_small_assign(const ep_problem &p, const void *X, const float *C, cons
 // with the exact arithmetic of the k <= 64 kernel.  Ties go to the lower index: a later slice must
 // beat the earlier ones strictly.
 bool small_sliced_supported(const ep_problem &p) {
-    return p.dtype == EP_F32 && (p.d == 64 || p.d == 128) && p.k > 64 && p.ld < ((int64_t)1 << 24);
+    return (p.dtype == EP_F32 || p.dtype == EP_F16) && (p.d == 64 || p.d == 128) && p.k > 64 && p.ld < ((int64_t)1 << 24);
 }
 
 int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,

@@ -14,7 +14,7 @@ import torch
 
 _LIB_PATH = Path(__file__).resolve().parent / "libembedpart.so"
 
-EP_F32, EP_BF16 = 0, 1
+EP_F32, EP_BF16, EP_F16 = 0, 1, 2
 EP_RUN_FINAL_REASSIGN, EP_RUN_BOUNDS = 1, 2
 EP_UPDATE_ACCUMULATE, EP_UPDATE_FINALIZE = 1, 2
 EP_OK, EP_EINVAL, EP_EUNSUPPORTED, EP_EWORKSPACE, EP_EHIP = 0, -1, -2, -3, -4
@@ -117,15 +117,17 @@ def _stream():
 
 
 def problem(X: torch.Tensor, k: int) -> ep_problem:
-    """ep_problem for a 2-D float32 / bfloat16 tensor with unit column stride."""
+    """ep_problem for a 2-D float32 / bfloat16 / float16 tensor with unit column stride."""
     if X.dim() != 2 or X.stride(1) != 1:
         raise ValueError("X must be 2-D with contiguous rows")
     if X.dtype == torch.float32:
         dt = EP_F32
     elif X.dtype == torch.bfloat16:
         dt = EP_BF16
+    elif X.dtype == torch.float16:
+        dt = EP_F16
     else:
-        raise ValueError("X must be float32 or bfloat16")
+        raise ValueError("X must be float32, bfloat16 or float16")
     return ep_problem(n=X.shape[0], ld=X.stride(0), d=X.shape[1], k=k, dtype=dt, reserved=0)
 
 

@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_constants_equal_the_header():
     text = HEADER.read_text() + BENCH_HEADER.read_text()
     defines = dict(re.findall(r"#define\s+(EP_\w+)\s+\(?(-?\d+)\)?\s", text))
-    for name in ("EP_OK", "EP_EINVAL", "EP_EUNSUPPORTED", "EP_EWORKSPACE", "EP_EHIP", "EP_F32", "EP_BF16",
+    for name in ("EP_OK", "EP_EINVAL", "EP_EUNSUPPORTED", "EP_EWORKSPACE", "EP_EHIP", "EP_F32", "EP_BF16", "EP_F16",
                  "EP_RUN_FINAL_REASSIGN", "EP_RUN_BOUNDS", "EP_UPDATE_ACCUMULATE", "EP_UPDATE_FINALIZE", "EP_MAX_D", "EP_MAX_K", "EP_BALANCE_MAX_K", "EP_BALANCE_MAX_ROUNDS", "EP_PROF_LLOYD_MAIN", "EP_PROF_UPDATE_SUMS",
                  "EP_PROF_EDGE_SWEEP"):
         assert int(defines[name]) == getattr(ep, name), name

@@ -80,7 +80,7 @@ SHAPES = [  # n, d, k, dtype, iters, components
     (20_011, 128, 16, torch.float32, 12, 20), (9_001, 128, 64, torch.float32, 10, 40), (7_003, 64, 30, torch.float32, 10, 12),
     (12_000, 128, 8, torch.bfloat16, 12, 10), (5_000, 64, 50, torch.bfloat16, 8, 30), (6_001, 128, 24, torch.bfloat16, 9, 16),
     (4_099, 64, 4, torch.float32, 15, 8), (37, 128, 5, torch.float32, 6, 3), (500, 128, 64, torch.float32, 7, 5),
-    (3_000, 128, 2, torch.float32, 8, 6),
+    (3_000, 128, 2, torch.float32, 8, 6), (8_000, 128, 40, torch.float16, 9, 25), (6_000, 64, 12, torch.float16, 10, 9),
 ]
 
 

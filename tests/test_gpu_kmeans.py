@@ -84,6 +84,12 @@ SHAPES = [  # n, d, k, relu, dtype, ld
     (2999, 200, 9, True, torch.bfloat16, None),      # (d = 200 in the 256-column kernel, bfloat16)
     (3000, 4, 3, False, torch.float32, None),
     (5000, 96, 64, True, torch.bfloat16, 104),
+    (4099, 128, 64, True, torch.float16, None),      # float16 rows: widened on arrival, then the fp32 kernels
+    (7777, 128, 16, True, torch.float16, 136),
+    (3001, 64, 30, False, torch.float16, None),
+    (3001, 20, 5, False, torch.float16, 24),         # (generic kernels)
+    (6000, 128, 100, True, torch.float16, None),     # (k > 64: slices of 64 centroids, update by sorted rows)
+    (2999, 200, 9, True, torch.float16, None),       # (columns padded on the fly)
     (64, 128, 64, False, torch.float32, None),      # k == n
     (1, 64, 1, False, torch.float32, None),
 ]
@@ -186,6 +192,8 @@ def test_run_matches_oracle_full_size(name):
 
 
 @pytest.mark.parametrize("n,d,k,dtype,iters", [(20_011, 128, 16, torch.float32, 8), (9_000, 128, 64, torch.float32, 6),
+                                               (20_011, 128, 16, torch.float16, 8), (9_000, 128, 64, torch.float16, 6),
+                                               (5_003, 128, 90, torch.float16, 4), (6_011, 64, 40, torch.float16, 6),
                                                (12_345, 128, 700, torch.bfloat16, 4),
                                                (6_007, 128, 24, torch.float32, 6), (6_011, 64, 40, torch.float32, 6),
                                                (8_009, 64, 300, torch.bfloat16, 4),
