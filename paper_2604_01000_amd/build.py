@@ -1,6 +1,7 @@
 """Builds libembedpart.so (HIP, gfx950 only) in-tree with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -37,20 +38,42 @@ def _run(cmd, verbose):
         print(err, file=sys.stderr)
 
 
-def build_lib(verbose: bool = False, extra_flags=()) -> Path:
+def _stamp(src: Path, flags) -> str:
+    """What an object file depends on: its source, every header beside it and in include/, and the flags."""
+    h = hashlib.sha256(" ".join(flags).encode())
+    for f in [src, *sorted(CSRC.glob("*.h")), *sorted((PKG.parent / "include").glob("*.h"))]:
+        h.update(f.read_bytes())
+    return h.hexdigest()
+
+
+def build_lib(verbose: bool = False, extra_flags=(), object_cache: Path | None = None) -> Path:
     """Compile every .hip file under csrc/ (one hipcc per file, side by side) and link them into one
-    shared library (always rebuilds).  The objects live in a temporary folder, not in the tree."""
+    shared library.  By default everything is compiled again and the objects live in a temporary folder,
+    not in the tree; with `object_cache` (a folder outside the tree) an object whose source, headers and
+    flags have not changed is taken from there instead."""
     compile_flags = [f for f in FLAGS if f != "-shared"]
     with tempfile.TemporaryDirectory(prefix="embedpart_build_") as tmp:
-        objs = [str(Path(tmp) / (src.stem + ".o")) for src in sources()]
-        with ThreadPoolExecutor(max_workers=min(8, len(objs))) as pool:
-            jobs = [pool.submit(_run, [HIPCC, *compile_flags, *extra_flags, "-c", str(src), "-o", obj], verbose)
-                    for src, obj in zip(sources(), objs)]
+        where = Path(object_cache) if object_cache else Path(tmp)
+        where.mkdir(parents=True, exist_ok=True)
+        todo, objs = [], []
+        for src in sources():
+            obj, stamp_file = where / (src.stem + ".o"), where / (src.stem + ".stamp")
+            objs.append(str(obj))
+            stamp = _stamp(src, [*compile_flags, *extra_flags])
+            if object_cache and obj.exists() and stamp_file.exists() and stamp_file.read_text() == stamp:
+                continue
+            todo.append((src, obj, stamp_file, stamp))
+        with ThreadPoolExecutor(max_workers=min(8, max(1, len(todo)))) as pool:
+            jobs = [pool.submit(_run, [HIPCC, *compile_flags, *extra_flags, "-c", str(src), "-o", str(obj)], verbose)
+                    for src, obj, _, _ in todo]
             for job in jobs:
                 job.result()
+        for _, _, stamp_file, stamp in todo:
+            stamp_file.write_text(stamp)
         _run([HIPCC, "--offload-arch=gfx950", "-fPIC", "-shared", *objs, "-o", str(LIB)], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_lib(verbose=True))
+    # `python -m paper_2604_01000_amd.build [object cache folder]`
+    print(build_lib(verbose=True, object_cache=Path(sys.argv[1]) if len(sys.argv) > 1 else None))

@@ -416,7 +416,7 @@ int kmeans_run_sampled(const ep_problem *p, const void *X, int64_t m, const int6
 int graph_workspace_bytes(int64_t n, int64_t nnz, int32_t k, size_t *bytes_host) {
     if (n < 1 || n >= EP_MAX_N || nnz < 0 || k < 1 || !bytes_host) return EP_EINVAL;
     if (k > EP_MAX_K) return EP_EUNSUPPORTED;
-    *bytes_host = carve_graph_ws(n, nnz, k, nullptr).bytes;
+    *bytes_host = carve_graph_ws(n, nnz, k, nullptr, true).bytes;
     return EP_OK;
 }
 
@@ -426,9 +426,9 @@ int partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, int
     if (rc != EP_OK) return rc;
     if (k < 1 || !labels || !cut || !sizes) return EP_EINVAL;
     if (k > EP_MAX_K) return EP_EUNSUPPORTED;
-    if ((rc = check_ws(ws, ws_bytes, carve_graph_ws(n, nnz, k, nullptr).bytes)) != EP_OK) return rc;
+    if ((rc = check_ws(ws, ws_bytes, carve_graph_ws(n, nnz, k, nullptr, true).bytes)) != EP_OK) return rc;
     return launch_partition_quality(n, nnz, k, rowptr, rowptr_is_i64 != 0, colidx, labels, cut, sizes,
-                                    carve_graph_ws(n, nnz, k, ws), static_cast<hipStream_t>(stream));
+                                    carve_graph_ws(n, nnz, k, ws, true), static_cast<hipStream_t>(stream));
 }
 
 int partition_permutation(int64_t n, int32_t k, const int32_t *labels, int32_t *new_id, int32_t *order, void *ws,

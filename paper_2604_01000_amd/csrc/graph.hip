@@ -441,8 +441,7 @@ int launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
 
 size_t sort_hist_elems() { return (size_t)kSortBlocksMax * kRadix + kRadix; }  // histograms + digit totals
 
-GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws) {
-    (void)nnz; (void)k;
+GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws, bool with_buckets) {
     Carver c(ws);
     GraphWs w{};
     w.partial = c.take<int64_t>(kGraphBlocksMax);
@@ -450,6 +449,15 @@ GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws) {
     w.order_tmp = c.take<int32_t>((size_t)n);
     w.order_tmp2 = c.take<int32_t>((size_t)n);
     w.label8 = c.take<uint8_t>((size_t)n);
+    const BucketPlan pl = with_buckets ? bucket_plan(n, nnz, k) : BucketPlan{0, 0};
+    if (pl.shift) {
+        w.bucket_hist = c.take<int64_t>(kBucketsMax);
+        w.bucket_base = c.take<int64_t>(kBucketsMax + 1);
+        w.bucket_cursor = c.take<int64_t>((size_t)kBucketsMax * 16);   // one 128-byte line per cursor
+        w.bucket_items = c.take<int64_t>(kBucketsMax + 1);
+        w.bucket_dropped = c.take<int64_t>(1);
+        w.bucket_records = c.take<uint32_t>(bucket_record_slots(nnz, pl));
+    }
     w.bytes = align_up(c.used, 256);
     return w;
 }
@@ -464,6 +472,8 @@ int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowp
     EP_LAUNCH_CHECK();
     if (nnz <= 0) return EP_OK;
     auto out = reinterpret_cast<unsigned long long *>(cut);
+    const BucketPlan pl = bucket_plan(n, nnz, k);
+    if (pl.shift && w.bucket_records) return launch_cut_bucketed(n, nnz, pl, rowptr, i64, colidx, w, out, s);
     ProfScope prof(EP_PROF_EDGE_SWEEP, s);
     return bytes ? launch_sweep_rows<uint8_t, kCut>(n, nnz, k, rowptr, i64, colidx, w.label8, out, s)
                  : launch_sweep_rows<int32_t, kCut>(n, nnz, k, rowptr, i64, colidx, labels, out, s);

@@ -1,0 +1,448 @@
+// Cut count of a partition over a CSR graph whose label vector is beyond every on-chip cache.
+//
+// What it computes (EmbedPart paper, Sec. "Partitioning quality metrics"): the number of stored entries
+// (u, v) with pid(u) != pid(v), the numerator of the edge-cut ratio |C| / |E|.  Integer arithmetic only:
+// the result does not depend on the order in which entries are met.
+//
+// Why a second path: the plain sweep (graph.hip) gathers pid(v) for every entry.  With 111 M vertices the
+// byte copy of the labels is 111 MB, every gather misses the L2 and pulls a whole cache line over the
+// fabric for one useful byte, and the sweep runs at the fabric's line rate (~50 G entries/s).  Here the
+// entries are first bucketed by the vertex range of v, so that the labels a bucket needs are 256 KB (L2)
+// and, in two pieces, 128 KB (LDS):
+//   bucket_hist_kernel     entries per bucket (one streaming read of colidx)
+//   bucket_scan_kernel     bucket offsets (each bucket starts on a 128-byte line), work items of the last pass
+//   bucket_scatter_kernel  streams colidx with its rows' labels (64-row windows as in the plain sweep) and
+//                          writes one 32-bit record per entry, (v - bucket start) | pid(u) << shift, to
+//                          the entry's bucket: a workgroup sorts a tile of 8,192 entries by bucket in LDS and
+//                          every bucket's run leaves as a contiguous stream of whole 64-byte blocks, its place
+//                          reserved with one integer atomic per bucket and tile
+//   bucket_sweep_kernel    a workgroup takes 64 K records of one bucket into registers, walks the bucket's
+//                          label slice through LDS 128 KB at a time and compares each record against the
+//                          piece that holds its v
+// Traffic: colidx twice, the records once out and once in, 4 bytes each: 16 bytes per entry in streams
+// instead of one 128-byte line per entry.
+#include <algorithm>
+#include <atomic>
+
+#include "kernels.h"
+
+namespace ep {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / 64;
+// Atomics on one cache line queue up behind each other: every bucket's cursor has a 128-byte line of its own.
+constexpr int kCursorStride = 16;
+constexpr int kAlign = 16;                 // records per 64-byte block: every write to the record buffer is whole blocks
+constexpr int kScatterGridMax = 256 * 2;   // workgroups of the scatter pass (two per compute unit)
+constexpr int kSliceShift = 17;            // label piece held in LDS: 2^17 bytes
+constexpr int kSweepBlock = 1024;
+constexpr int kSweepPerThread = 64;
+constexpr int kChunk = kSweepBlock * kSweepPerThread;   // records per work item of the last pass
+constexpr int kSweepGrid = 1024;
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void wave_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kBlock) void bucket_clear_kernel(int nb, unsigned long long *__restrict__ hist,
+                                                               unsigned long long *__restrict__ dropped) {
+    const int t = blockIdx.x * kBlock + threadIdx.x;
+    if (t < nb) hist[t] = 0;
+    if (t == 0) *dropped = 0;
+}
+
+__global__ __launch_bounds__(kBlock) void bucket_hist_kernel(int64_t n, int64_t nnz, int shift, int nb,
+                                                              const int32_t *__restrict__ colidx,
+                                                              unsigned long long *__restrict__ hist) {
+    __shared__ unsigned int h[kBucketsMax];
+    for (int b = threadIdx.x; b < nb; b += kBlock) h[b] = 0;
+    __syncthreads();
+    const int64_t quads = nnz / 4, stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x; q < quads; q += stride) {
+        const i32x4 c = *reinterpret_cast<const i32x4 *>(colidx + 4 * q);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (c[t] >= 0 && c[t] < n) atomicAdd(&h[c[t] >> shift], 1u);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(nnz - 4 * quads)) {   // the last nnz % 4 entries
+        const int32_t v = colidx[4 * quads + threadIdx.x];
+        if (v >= 0 && v < n) atomicAdd(&h[v >> shift], 1u);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < nb; b += kBlock)
+        if (h[b]) atomicAdd(&hist[b], (unsigned long long)h[b]);   // integers: the order does not matter
+}
+
+// base[b] = start of bucket b in the record buffer, cursor[b] = base[b], item_prefix[b] = number of
+// kChunk-record work items before bucket b.  A bucket has room for its entries rounded up to whole blocks plus
+// one block per workgroup of the scatter pass (the padded last flush of each).  One thread: nb <= kBucketsMax.
+__global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long long *__restrict__ hist,
+                                   int64_t *__restrict__ base, unsigned long long *__restrict__ cursor,
+                                   int64_t *__restrict__ item_prefix) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int64_t at = 0, items = 0;
+    for (int b = 0; b < nb; ++b) {
+        base[b] = at;
+        cursor[b * kCursorStride] = (unsigned long long)at;
+        item_prefix[b] = items;
+        const int64_t room = ((int64_t)hist[b] + kAlign - 1) / kAlign * kAlign + (int64_t)kAlign * scatter_grid;
+        at += room;
+        items += (room + kChunk - 1) / kChunk;
+    }
+    base[nb] = at;
+    item_prefix[nb] = items;
+}
+
+// A workgroup gathers a tile of up to kTile entries, sorts it by bucket in LDS and writes every bucket's run
+// to the bucket's next free slots, reserved with one integer atomic per bucket and tile.
+//   phase A  every wave streams its rows' entries (64-row windows as in edge_block_sweep_kernel, 256 entries
+//            per step, kTileSteps steps, the next step's entries in flight); an entry takes its rank inside
+//            its bucket from an LDS counter and stays in registers as (record, bucket | rank)
+//   phase B  the counters are scanned (start of every bucket's run inside the tile) and thread b reserves the
+//            run of bucket b in the record buffer
+//   phase C  the records go to their sorted place in LDS, then every run leaves as one contiguous stream
+constexpr int kScatterBlock = 512;
+constexpr int kScatterWaves = kScatterBlock / 64;
+constexpr int kTileSteps = 4;
+constexpr int kTile = kScatterWaves * kTileSteps * 256;
+
+template <typename RowT>
+__global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n, int64_t nnz, int shift, int nb,
+                                                                        const RowT *__restrict__ rowptr,
+                                                                        const int32_t *__restrict__ colidx,
+                                                                        const uint8_t *__restrict__ label8,
+                                                                        const int64_t *__restrict__ base,
+                                                                        unsigned long long *__restrict__ cursor,
+                                                                        uint32_t *__restrict__ records,
+                                                                        unsigned long long *__restrict__ dropped) {
+    static_assert(kBucketsMax <= kScatterBlock, "one thread per bucket in the scan of a tile");
+    __shared__ uint32_t sorted[kTile];
+    __shared__ int32_t tile_cnt[kBucketsMax];        // entries of the tile per bucket
+    __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
+    __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
+    __shared__ int64_t rp_lds[kScatterWaves][66];
+    __shared__ int32_t au_lds[kScatterWaves][64];
+    __shared__ int32_t wave_total[kScatterWaves];
+    __shared__ int32_t any_work;
+    // Records of earlier tiles that did not fill a whole 64-byte block of their bucket wait here for the next
+    // tile, so that every write to the record buffer is a run of whole blocks at a block-aligned place (a
+    // partial block costs the memory a read-modify-write).
+    extern __shared__ __attribute__((aligned(16))) uint32_t resid[];   // nb * (kAlign - 1) records
+    __shared__ int32_t resid_cnt[kBucketsMax];
+    __shared__ int32_t run_out[kBucketsMax];         // records of (waiting + run) that leave with this tile
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int64_t *rp = rp_lds[wave];
+    int32_t *aus = au_lds[wave];
+    const int64_t row_blocks = (n + 63) / 64;
+    const int64_t rb_stride = (int64_t)gridDim.x * kScatterWaves;
+    for (int b = threadIdx.x; b < kBucketsMax; b += kScatterBlock) {
+        tile_cnt[b] = 0;
+        resid_cnt[b] = 0;
+    }
+    if (threadIdx.x == 0) any_work = 0;
+    __syncthreads();
+
+    // this wave's position in its stream of entries
+    int64_t rb = (int64_t)blockIdx.x * kScatterWaves + wave - rb_stride;   // current row block (none yet)
+    int64_t p0 = 0, e_begin = 0, e_end = 0;   // next 256-entry step of the block, the block's entry range
+    i32x4 ahead = {-1, -1, -1, -1};           // this lane's four entries of the step at p0, loaded one step early
+    unsigned long long lost = 0;
+
+    auto load4 = [&](int64_t p) {
+        i32x4 c = {-1, -1, -1, -1};
+        if (p < e_end) {
+            if (p + 3 < nnz) c = *reinterpret_cast<const i32x4 *>(colidx + p);
+            else for (int t = 0; t < 4; ++t) if (p + t < nnz) c[t] = colidx[p + t];
+        }
+        return c;
+    };
+    // the next row block of this wave that has entries; false when the wave has none left
+    auto next_block = [&]() -> bool {
+        for (;;) {
+            rb += rb_stride;
+            if (rb >= row_blocks) {
+                p0 = e_begin = e_end = 0;
+                return false;
+            }
+            const int64_t r0 = rb * 64;
+            wave_fence();   // the window of the previous block is no longer read
+            const int64_t r = min(r0 + lane, n);
+            rp[lane] = min(max((int64_t)rowptr[r], (int64_t)0), nnz);
+            if (lane == 0) rp[64] = min(max((int64_t)rowptr[min(r0 + 64, n)], (int64_t)0), nnz);
+            aus[lane] = r0 + lane < n ? (int32_t)label8[r0 + lane] : 255;
+            wave_fence();
+            e_begin = rp[0];
+            e_end = rp[64];
+            p0 = e_begin & ~(int64_t)3;
+            if (e_end > e_begin) {
+                ahead = load4(p0 + 4 * lane);
+                return true;
+            }
+        }
+    };
+
+    for (;;) {
+        // ---- phase A ----
+        uint32_t rec[kTileSteps * 4], where[kTileSteps * 4];   // where = bucket | rank << 9; 0xffffffff: no entry
+        bool worked = false;
+#pragma unroll
+        for (int st = 0; st < kTileSteps; ++st) {
+            bool have = p0 < e_end;
+            if (!have) have = next_block();
+#pragma unroll
+            for (int t = 0; t < 4; ++t) where[4 * st + t] = 0xffffffffu;
+            if (have) {   // uniform over the wave
+                worked = true;
+                const int64_t p = p0 + 4 * lane;
+                const i32x4 c = ahead;
+                ahead = load4(p + 256);   // the next step of this block, in flight while this one is ranked
+                int j = 0;
+                {
+                    const int64_t q = max(p, e_begin);
+#pragma unroll
+                    for (int step = 32; step > 0; step >>= 1)
+                        if (rp[j + step] <= q) j += step;
+                }
+                int64_t row_end = rp[min(j + 1, 64)];
+                uint32_t lu = (uint32_t)aus[min(j, 63)];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int64_t pe = p + t;
+                    const bool live = pe >= e_begin && pe < e_end;
+                    if (live) {
+                        while (pe >= row_end) {   // ends: pe < e_end = rp[64]
+                            ++j;
+                            row_end = rp[j + 1];
+                            lu = (uint32_t)aus[j];
+                        }
+                    }
+                    const int32_t v = c[t];
+                    if (live && v >= 0 && v < n) {
+                        const int b = v >> shift;
+                        const int rank = atomicAdd(&tile_cnt[b], 1);   // integer, LDS: the order inside a run is free
+                        rec[4 * st + t] = ((uint32_t)v & ((1u << shift) - 1u)) | (lu << shift);
+                        where[4 * st + t] = (uint32_t)b | ((uint32_t)rank << 9);
+                    }
+                }
+                p0 += 256;
+            }
+        }
+        if (worked && lane == 0) any_work = 1;
+        __syncthreads();
+        if (!any_work) break;   // uniform over the workgroup: no wave had a step
+        // ---- phase B: exclusive scan of tile_cnt[0 .. nb), one counter per thread; reservations ----
+        {
+            const int t = threadIdx.x;
+            const int cnt = t < nb ? tile_cnt[t] : 0;
+            int incl = cnt;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += up;
+            }
+            if (lane == 63) wave_total[wave] = incl;
+            const int out = t < nb ? ((resid_cnt[t] + cnt) & ~(kAlign - 1)) : 0;   // whole blocks of waiting + new records
+            int64_t dest = -1;
+            if (out > 0) {   // one integer atomic per bucket and tile; all of them in flight together
+                const unsigned long long pos = atomicAdd(&cursor[t * kCursorStride], (unsigned long long)out);
+                if ((int64_t)pos + out <= base[t + 1]) dest = (int64_t)pos;   // never write past a bucket
+                else lost += (unsigned long long)out;
+            }
+            __syncthreads();
+            int before = 0;
+            for (int w = 0; w < wave; ++w) before += wave_total[w];
+            if (t < nb) {
+                run_start[t] = before + incl - cnt;
+                run_dest[t] = dest;
+                run_out[t] = out;
+            }
+            if (t == kScatterBlock - 1) run_start[nb] = before + incl;   // nb <= kScatterBlock: the total
+        }
+        __syncthreads();
+        // ---- phase C ----
+#pragma unroll
+        for (int i = 0; i < kTileSteps * 4; ++i)
+            if (where[i] != 0xffffffffu) sorted[run_start[where[i] & 511u] + (int)(where[i] >> 9)] = rec[i];
+        __syncthreads();
+        for (int b = wave; b < nb; b += kScatterWaves) {
+            // the bucket's stream = the records that waited, then this tile's run; `out` of them leave
+            const int first = run_start[b], cnt = run_start[b + 1] - first;
+            const int waiting = resid_cnt[b], out = run_out[b];
+            const int64_t dest = run_dest[b];
+            uint32_t *wait_b = resid + b * (kAlign - 1);
+            if (dest >= 0)
+                for (int i = lane; i < out; i += 64) records[dest + i] = i < waiting ? wait_b[i] : sorted[first + i - waiting];
+            const int keep = waiting + cnt - out;   // < kAlign
+            wave_fence();
+            if (out == 0) {                          // nothing left: the run joins the waiting records
+                if (lane < cnt) wait_b[waiting + lane] = sorted[first + lane];
+            } else if (lane < keep) {                // out >= kAlign > waiting: the tail of the run waits
+                wait_b[lane] = sorted[first + out - waiting + lane];
+            }
+            if (lane == 0) resid_cnt[b] = keep;
+        }
+        __syncthreads();
+        for (int b = threadIdx.x; b < nb; b += kScatterBlock) tile_cnt[b] = 0;
+        if (threadIdx.x == 0) any_work = 0;
+        __syncthreads();
+    }
+    // what still waits leaves as one block per bucket, filled up with records that count for nothing
+    for (int b = wave; b < nb; b += kScatterWaves) {
+        const int waiting = resid_cnt[b];
+        if (waiting == 0) continue;   // uniform over the wave
+        unsigned long long pos = 0;
+        if (lane == 0) pos = atomicAdd(&cursor[b * kCursorStride], (unsigned long long)kAlign);
+        pos = __shfl(pos, 0, 64);
+        if ((int64_t)pos + kAlign <= base[b + 1]) {
+            if (lane < kAlign) records[pos + lane] = lane < waiting ? resid[b * (kAlign - 1) + lane] : (255u << shift);
+        } else if (lane == 0) {
+            lost += (unsigned long long)waiting;
+        }
+    }
+    if (lost) atomicAdd(dropped, lost);
+}
+
+// Work item w = kChunk consecutive records of one bucket.  The records stay in registers while the bucket's
+// label slice passes through LDS in pieces of 2^kSliceShift bytes.
+__global__ __launch_bounds__(kSweepBlock) void bucket_sweep_kernel(int64_t n, int shift, int nb,
+                                                                    const uint8_t *__restrict__ label8,
+                                                                    const unsigned long long *__restrict__ cursor,
+                                                                    const int64_t *__restrict__ base,
+                                                                    const int64_t *__restrict__ item_prefix,
+                                                                    const uint32_t *__restrict__ records,
+                                                                    unsigned long long *__restrict__ out) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char slice[];   // 2^kSliceShift label bytes
+    __shared__ int64_t prefix_lds[kBucketsMax + 1];
+    __shared__ unsigned long long red[kSweepBlock / 64];
+    for (int b = threadIdx.x; b <= nb; b += kSweepBlock) prefix_lds[b] = item_prefix[b];
+    __syncthreads();
+    const int64_t items = prefix_lds[nb];
+    const uint32_t vmask = (1u << shift) - 1u;
+    const int pieces = 1 << (shift - kSliceShift);
+    unsigned long long cut = 0;
+    for (int64_t w = blockIdx.x; w < items; w += gridDim.x) {
+        int b = 0;   // the bucket of item w: the last b with item_prefix[b] <= w
+        for (int step = kBucketsMax / 2; step > 0; step >>= 1)
+            if (b + step < nb && prefix_lds[b + step] <= w) b += step;
+        const int64_t first = base[b] + (w - prefix_lds[b]) * kChunk;
+        const int64_t end = min((int64_t)cursor[b * kCursorStride], base[b + 1]);   // what the scatter pass wrote
+        uint32_t rec[kSweepPerThread];
+#pragma unroll
+        for (int q = 0; q < kSweepPerThread; ++q) {
+            const int64_t at = first + (int64_t)q * kSweepBlock + threadIdx.x;
+            rec[q] = at < end ? records[at] : (255u << shift);   // pid(u) = 255: counts for nothing
+        }
+        const int64_t v0 = (int64_t)b << shift;
+        for (int piece = 0; piece < pieces; ++piece) {
+            __syncthreads();   // the previous piece is no longer read
+            const int64_t p0 = v0 + ((int64_t)piece << kSliceShift);
+            for (int i = threadIdx.x; i < (1 << kSliceShift) / 16; i += kSweepBlock) {
+                const int64_t g = p0 + 16 * (int64_t)i;
+                u32x4 val = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+                if (g + 15 < n) {
+                    val = *reinterpret_cast<const u32x4 *>(label8 + g);
+                } else {
+                    for (int e = 0; e < 16; ++e)
+                        if (g + e < n) reinterpret_cast<uint8_t *>(&val)[e] = label8[g + e];
+                }
+                reinterpret_cast<u32x4 *>(slice)[i] = val;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < kSweepPerThread; ++q) {
+                asm volatile("" : "+v"(rec[q]));   // keeps the fields from being split out of all 64 records ahead of the loop (spills)
+                const uint32_t vl = rec[q] & vmask;
+                if ((int)(vl >> kSliceShift) == piece) {
+                    const uint32_t lu = rec[q] >> shift, lv = slice[vl & ((1u << kSliceShift) - 1u)];
+                    cut += (lu != 255u && lv != 255u && lu != lv) ? 1u : 0u;
+                }
+            }
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) cut += __shfl_down(cut, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = cut;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long total = 0;
+        for (int w = 0; w < kSweepBlock / 64; ++w) total += red[w];
+        if (total) atomicAdd(out, total);
+    }
+}
+
+// Dynamic LDS beyond 64 KB has to be allowed per kernel: done once per kernel and device (`done`: one word per
+// kernel of this file, one bit per device).
+int set_big_lds(const void *kern, std::atomic<uint64_t> &done, int bytes) {
+    if (bytes <= 64 * 1024) return EP_OK;
+    int dev = 0;
+    EP_HIP_TRY(hipGetDevice(&dev));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(done.load(std::memory_order_acquire) & bit)) {
+        EP_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+        done.fetch_or(bit, std::memory_order_release);
+    }
+    return EP_OK;
+}
+std::atomic<uint64_t> g_sweep_lds{0};
+
+}  // namespace
+
+BucketPlan bucket_plan(int64_t n, int64_t nnz, int32_t k) {
+    BucketPlan pl{0, 0};
+    // Worth it only when the byte labels are far beyond the L2 caches and the rows are not nearly empty.
+    if (k > 255 || n < kBucketMinVertices || nnz < 4 * n) return pl;
+    pl.shift = 18;   // 256 KB of labels per bucket: two LDS pieces in the last pass
+    while (ceil_div(n, (int64_t)1 << pl.shift) > kBucketsMax) ++pl.shift;
+    pl.nb = (int)ceil_div(n, (int64_t)1 << pl.shift);
+    return pl;
+}
+
+int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void *rowptr, bool i64,
+                        const int32_t *colidx, const GraphWs &w, unsigned long long *cut, hipStream_t s) {
+    auto hist = reinterpret_cast<unsigned long long *>(w.bucket_hist);
+    auto cursor = reinterpret_cast<unsigned long long *>(w.bucket_cursor);
+    auto dropped = reinterpret_cast<unsigned long long *>(w.bucket_dropped);
+    ProfScope prof(EP_PROF_EDGE_SWEEP, s);   // the four kernels together are this path's sweep
+    bucket_clear_kernel<<<(unsigned)ceil_div(pl.nb, kBlock), kBlock, 0, s>>>(pl.nb, hist, dropped);
+    EP_LAUNCH_CHECK();
+    const unsigned hgrid = (unsigned)std::min<int64_t>(ceil_div(nnz / 4 + 1, kBlock * 8), 256 * 8);
+    bucket_hist_kernel<<<hgrid, kBlock, 0, s>>>(n, nnz, pl.shift, pl.nb, colidx, hist);
+    EP_LAUNCH_CHECK();
+    const int64_t row_blocks = ceil_div(n, 64);
+    const unsigned sgrid = (unsigned)std::min<int64_t>(ceil_div(row_blocks, kScatterWaves), kScatterGridMax);
+    bucket_scan_kernel<<<1, 64, 0, s>>>(pl.nb, (int)sgrid, hist, w.bucket_base, cursor, w.bucket_items);
+    EP_LAUNCH_CHECK();
+    {
+        const int resid_bytes = pl.nb * (kAlign - 1) * 4;   // <= 30 KB
+        if (i64) {
+            bucket_scatter_kernel<int64_t><<<sgrid, kScatterBlock, resid_bytes, s>>>(
+                n, nnz, pl.shift, pl.nb, static_cast<const int64_t *>(rowptr), colidx, w.label8, w.bucket_base, cursor,
+                w.bucket_records, dropped);
+        } else {
+            bucket_scatter_kernel<int32_t><<<sgrid, kScatterBlock, resid_bytes, s>>>(
+                n, nnz, pl.shift, pl.nb, static_cast<const int32_t *>(rowptr), colidx, w.label8, w.bucket_base, cursor,
+                w.bucket_records, dropped);
+        }
+        EP_LAUNCH_CHECK();
+        int rc = set_big_lds(reinterpret_cast<const void *>(bucket_sweep_kernel), g_sweep_lds, 1 << kSliceShift);
+        if (rc != EP_OK) return rc;
+        bucket_sweep_kernel<<<kSweepGrid, kSweepBlock, 1 << kSliceShift, s>>>(n, pl.shift, pl.nb, w.label8, cursor,
+                                                                              w.bucket_base, w.bucket_items,
+                                                                              w.bucket_records, cut);
+        EP_LAUNCH_CHECK();
+    }
+    return EP_OK;
+}
+
+size_t bucket_record_slots(int64_t nnz, const BucketPlan &pl) {
+    return (size_t)nnz + (size_t)pl.nb * kAlign * (kScatterGridMax + 1) + kAlign;
+}
+
+}  // namespace ep

@@ -162,16 +162,37 @@ int launch_large_assign(const ep_problem &p, const void *X, const float *C, cons
 
 // ---- graph kernels (graph.hip) ---------------------------------------------------
 constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass
+// Cut count through buckets of destination ranges (graph_bucket.hip): used when the byte labels are far
+// beyond the caches.  shift == 0: not used for this graph.
+constexpr int kBucketsMax = 512;
+constexpr int64_t kBucketMinVertices = 6 * 1024 * 1024;
+struct BucketPlan {
+    int shift;   // a bucket holds the entries whose column lies in [b << shift, (b + 1) << shift)
+    int nb;      // number of buckets, <= kBucketsMax
+};
+BucketPlan bucket_plan(int64_t n, int64_t nnz, int32_t k);
+size_t bucket_record_slots(int64_t nnz, const BucketPlan &pl);
+
 struct GraphWs {
     int64_t *partial;     // [kGraphBlocksMax] per-workgroup partial counts / sums
     int32_t *sort_hist;   // [kSortBlocksMax * 256]
     int32_t *order_tmp;   // [n]
     int32_t *order_tmp2;  // [n]
     uint8_t *label8;      // [n] byte copy of the labels for the cut sweep (k <= 255)
+    // bucketed cut count only (carved last, so that the layout before them is the same for every graph call)
+    int64_t *bucket_hist;     // [kBucketsMax] entries per bucket
+    int64_t *bucket_base;     // [kBucketsMax + 1] bucket starts in bucket_records
+    int64_t *bucket_cursor;   // [kBucketsMax * 16] next free slot per bucket, one 128-byte line each
+    int64_t *bucket_items;    // [kBucketsMax + 1] work items of the last pass before each bucket
+    int64_t *bucket_dropped;  // [1] records that found no room (0 for a well-formed graph)
+    uint32_t *bucket_records; // [nnz + padding] one 32-bit record per entry, grouped by bucket
     size_t bytes;
 };
 constexpr int kGraphBlocksMax = 8192;
-GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws);
+// with_buckets: also the buffers of the bucketed cut count, if bucket_plan(n, nnz, k) uses it.
+GraphWs carve_graph_ws(int64_t n, int64_t nnz, int32_t k, void *ws, bool with_buckets = false);
+int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void *rowptr, bool i64,
+                        const int32_t *colidx, const GraphWs &w, unsigned long long *cut, hipStream_t s);
 size_t sort_hist_elems();
 
 int launch_partition_quality(int64_t n, int64_t nnz, int32_t k, const void *rowptr, bool i64, const int32_t *colidx,

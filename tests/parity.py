@@ -179,7 +179,9 @@ class Graph:
     def __init__(self, rowptr: torch.Tensor, colidx: torch.Tensor, k_max: int = 65536):
         self.rowptr, self.colidx = rowptr.to(DEV), colidx.to(DEV)
         self.n, self.nnz = rowptr.numel() - 1, colidx.numel()
-        self.ws = ep.workspace(ep.graph_workspace_bytes(self.n, self.nnz, k_max), DEV)
+        # (a large graph needs more for k <= 255, where the cut count goes through buckets of column ranges)
+        self.ws = ep.workspace(max(ep.graph_workspace_bytes(self.n, self.nnz, k_max),
+                                   ep.graph_workspace_bytes(self.n, self.nnz, 1)), DEV)
         self.rp_np = rowptr.cpu().numpy().astype(np.int64)
         self.ci_np = colidx.cpu().numpy()
 

@@ -89,3 +89,52 @@ def test_out_of_range_labels_are_skipped_not_read_out_of_bounds():
     b = bad.numpy()
     assert cut == int(np.count_nonzero(both & (b[src] != b[gr.ci_np])))
     assert sizes.tolist() == np.bincount(b[ok], minlength=4).tolist()
+
+
+@pytest.mark.parametrize("rowptr_i64", [True, False])
+def test_cut_count_through_buckets_on_a_graph_beyond_the_caches(rowptr_i64):
+    """6.4 M vertices: the cut count goes through buckets of column ranges (two buckets of 2^20 vertices and more,
+    a ragged last one).  Hubs, empty rows, labels outside [0, k) and every k the byte labels allow, bit-exact
+    against the oracle; then a graph whose columns all fall into one bucket."""
+    from paper_2604_01000_amd import embedpart as ep
+    n = 6_400_123
+    w = synth.WORKLOADS["papers_like"].scaled(n)
+    rowptr, colidx, blocks = synth.sbm_graph(w, DEV)
+    rp = rowptr.cpu().numpy().astype(np.int64)
+    ci = colidx.cpu().numpy().copy()
+    rng = np.random.default_rng(5)
+    hub = rng.integers(0, n, size=300_000).astype(np.int32)          # one row of 300,000 entries, many rows emptied
+    deg = np.diff(rp)
+    deg[rng.random(n) < 0.2] = 0
+    keep = np.repeat(deg > 0, np.diff(rp))
+    ci = ci[keep]
+    rp = np.concatenate([[0], np.cumsum(deg)])
+    at = int(rp[n // 3])
+    ci = np.concatenate([ci[:at], hub, ci[at:]])
+    rp[n // 3 + 1:] += len(hub)
+    assert rp[-1] == len(ci) and len(ci) >= 4 * n
+    gr = Graph(torch.from_numpy(rp).to(torch.int64 if rowptr_i64 else torch.int32), torch.from_numpy(ci))
+    assert ep.graph_workspace_bytes(n, len(ci), 64) >= 4 * len(ci)    # the record buffer is part of the workspace
+    for k, seed in ((64, 1), (2, 2), (255, 3)):
+        lab = _labels(n, k, seed)
+        cut, sizes = gr.quality(lab.to(DEV), k)
+        cut_or, sizes_or = oracle.partition_quality(gr.rp_np, gr.ci_np, lab.numpy(), k)
+        assert cut == cut_or
+        np.testing.assert_array_equal(sizes, sizes_or)
+    bad = _labels(n, 7, 4)
+    bad[::5] = 1 << 20
+    bad[1::9] = -3
+    cut, sizes = gr.quality(bad.to(DEV), 7)
+    ok = ((bad >= 0) & (bad < 7)).numpy()
+    src = np.repeat(np.arange(n), np.diff(gr.rp_np))
+    b = bad.numpy()
+    assert cut == int(np.count_nonzero(ok[src] & ok[gr.ci_np] & (b[src] != b[gr.ci_np])))
+    # k = 256 does not fit a byte: the plain sweep, same answer as the oracle
+    lab = _labels(n, 256, 6)
+    cut, _ = gr.quality(lab.to(DEV), 256)
+    assert cut == oracle.partition_quality(gr.rp_np, gr.ci_np, lab.numpy(), 256)[0]
+    # every column in the first bucket
+    ci2 = (gr.ci_np % 1000).astype(np.int32)
+    gr2 = Graph(torch.from_numpy(gr.rp_np).to(torch.int64 if rowptr_i64 else torch.int32), torch.from_numpy(ci2))
+    lab = _labels(n, 9, 8)
+    assert gr2.quality(lab.to(DEV), 9)[0] == oracle.partition_quality(gr2.rp_np, ci2, lab.numpy(), 9)[0]
