@@ -4,20 +4,28 @@
 // and in integers.
 //
 // A migration round:
-//   1. loads L_i of the class per partition (LDS histogram, integer atomics);
-//   2. plan (one thread; k <= 255): capacity C = max(floor(beta |S| / k), ceil(|S| / k)),
+//   1. per partition, the number of class members of every degree 0 .. B-2 and of degree >= B-1 (LDS
+//      histogram, integer atomics); the loads L_i are the row sums;
+//   2. plan (one workgroup; k <= 255): capacity C = max(floor(beta |S| / k), ceil(|S| / k)),
 //      m_i = L_i - C on the overloaded partitions, the running sum of the free capacities C - L_i
-//      of the underloaded ones, their total F;
-//   3. key per vertex: (partition << 24) | min(degree, 2^24 - 1) for class members of overloaded
-//      partitions, all ones for everyone else;
-//   4. stable radix sort of the vertex ids by key (4 passes): inside a partition the members come
-//      by ascending degree, equal degrees by ascending id;
-//   5. the first m_i vertices of partition i's run move; the destination of vertex v is the
-//      partition whose interval of the running sum holds (mix(seed, round, v) mod F).
+//      of the underloaded ones, their total F; and, from the degree counts, the degree t_i at which
+//      the m_i-th smallest member of partition i sits and how many members of exactly that degree
+//      still have to go (need_i);
+//   3. selection instead of a sort: the movers of partition i are its members of degree < t_i and,
+//      among those of degree t_i, the need_i with the smallest ids.  Their rank by id comes from
+//      per-workgroup counts of the degree-t_i members (vertex ranges in order), a scan over the
+//      workgroups and an ordered count inside the workgroup;
+//   4. the destination of a mover v is the partition whose interval of the running sum holds
+//      (mix(seed, round, v) mod F).
+//   Only if some t_i falls into the last histogram bin (more movers than members below degree B-1) the
+//   round falls back to sorting: key (partition << 24) | min(degree, 2^24 - 1), stable 4-pass radix
+//   sort of the vertex ids, the first m_i of every partition's run move.  Both ways pick the same
+//   vertices (ascending degree, equal degrees by ascending id).
 // The draw is a function of (seed, round, v) only, so the result does not depend on the order in
 // which threads get to the vertices.  Rounds whose plan finds nothing overloaded do nothing (every
-// kernel after the plan reads its `active` flag and returns): the host enqueues max_rounds rounds
-// without ever reading anything back.
+// kernel after the plan reads its flags and returns, and once a plan has found nothing overloaded even
+// the counting passes of the later rounds return at once): the host enqueues max_rounds rounds without
+// ever reading anything back.
 #include <algorithm>
 
 #include "kernels.h"
@@ -39,52 +47,162 @@ struct BalPlan {
     long long F;                  // total free capacity
     int active;                   // this round moves vertices
     int round;                    // rounds completed before this one (enters the draw)
+    int by_sort;                  // ... by the sorting fallback (a threshold degree in the last bin)
+    int by_select;                // ... by selection
+    int finished;                 // a plan found nothing overloaded: later rounds do nothing
+    int tdeg[256];                // threshold degree t_i of the overloaded partitions
+    long long need[256];          // members of degree t_i that move (the smallest ids)
 };
 
-__global__ void bal_reset_kernel(BalPlan *plan, int64_t *stats, int first) {
-    const int t = threadIdx.x;
-    plan->L[t] = 0;
+constexpr int kHistCounters = 16384;   // LDS counters of the degree histogram (64 KB)
+constexpr int kBinsMax = 256;
+constexpr int kSelBlocksMax = 1024;    // vertex ranges of the selection passes
+inline int degree_bins(int32_t k) { return std::min(kBinsMax, kHistCounters / k); }   // >= 64 for k <= 255
+
+__global__ __launch_bounds__(kBlock) void bal_reset_kernel(BalPlan *plan, int64_t *stats, int first, int cells,
+                                                            unsigned int *__restrict__ dhist) {
+    const int t = blockIdx.x * kBlock + threadIdx.x;
+    if (first && t == 0) {
+        plan->round = 0;
+        plan->finished = 0;
+    }
     if (first && t < 3) stats[t] = 0;
-    if (first && t == 0) plan->round = 0;
+    if (t < cells) dhist[t] = 0;   // (later rounds: the plan clears the rows it has read)
 }
 
-__global__ __launch_bounds__(kBlock) void bal_count_kernel(int64_t n, int32_t k, const uint8_t *__restrict__ vclass,
-                                                            int32_t class_id, const int32_t *__restrict__ labels,
-                                                            BalPlan *plan) {
-    __shared__ unsigned int h[256];
-    h[threadIdx.x] = 0;
+// dhist[l * bins + min(degree, bins - 1)] += 1 for every class member v of partition l.
+template <typename RowT>
+__global__ __launch_bounds__(kBlock) void bal_count_kernel(int64_t n, int32_t k, int bins,
+                                                            const RowT *__restrict__ rowptr,
+                                                            const uint8_t *__restrict__ vclass, int32_t class_id,
+                                                            const int32_t *__restrict__ labels,
+                                                            const BalPlan *__restrict__ plan,
+                                                            unsigned int *__restrict__ dhist) {
+    if (plan->finished) return;   // uniform over the grid
+    __shared__ unsigned int h[kHistCounters];
+    const int cells = k * bins;
+    for (int i = threadIdx.x; i < cells; i += kBlock) h[i] = 0;
     __syncthreads();
     for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n; v += (int64_t)gridDim.x * kBlock) {
         if (vclass && vclass[v] != class_id) continue;
         const int32_t l = labels[v];
-        if (l >= 0 && l < k) atomicAdd(&h[l], 1u);
+        if (l < 0 || l >= k) continue;
+        const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
+        atomicAdd(&h[l * bins + (int)std::min<int64_t>(std::max<int64_t>(deg, 0), bins - 1)], 1u);
     }
     __syncthreads();
-    if (h[threadIdx.x]) atomicAdd(&plan->L[threadIdx.x], (unsigned long long)h[threadIdx.x]);
+    for (int i = threadIdx.x; i < cells; i += kBlock)
+        if (h[i]) atomicAdd(&dhist[i], h[i]);   // integers: the order does not matter
 }
 
-// One thread: k <= 255 partitions.  `allow` is 0 for the closing evaluation after the last round.
-__global__ void bal_plan_kernel(int32_t k, double beta, int allow, BalPlan *plan, int64_t *stats) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    long long total = 0;
-    for (int i = 0; i < k; ++i) total += (long long)plan->L[i];
-    long long cap = (long long)floor(beta * (double)total / (double)k);
-    const long long reach = (total + k - 1) / k;
-    if (cap < reach) cap = reach;
-    long long F = 0, over = 0;
-    for (int i = 0; i < k; ++i) {
-        const long long L = (long long)plan->L[i];
-        if (L < cap) F += cap - L;
-        plan->cumf[i] = F;
-        plan->m[i] = L > cap ? L - cap : 0;
-        if (L > cap) ++over;
+// One workgroup of 256 threads, thread i = partition i (k <= 255).  `allow` is 0 for the closing evaluation
+// after the last round.
+__global__ __launch_bounds__(256) void bal_plan_kernel(int32_t k, int bins, double beta, int allow, BalPlan *plan,
+                                                        unsigned int *__restrict__ dhist, int64_t *stats) {
+    if (plan->finished) return;
+    __shared__ long long load_lds[256];
+    __shared__ long long cap_lds;
+    __shared__ int sort_lds;
+    const int i = threadIdx.x;
+    long long L = 0;
+    if (i < k)
+        for (int b = 0; b < bins; ++b) L += dhist[i * bins + b];
+    load_lds[i] = L;
+    if (i == 0) sort_lds = 0;
+    __syncthreads();
+    if (i == 0) {
+        long long total = 0;
+        for (int j = 0; j < k; ++j) total += load_lds[j];
+        long long cap = (long long)floor(beta * (double)total / (double)k);
+        const long long reach = (total + k - 1) / k;
+        if (cap < reach) cap = reach;
+        cap_lds = cap;
+        long long F = 0, over = 0;
+        for (int j = 0; j < k; ++j) {
+            const long long Lj = load_lds[j];
+            if (Lj < cap) F += cap - Lj;
+            plan->cumf[j] = F;
+            if (Lj > cap) ++over;
+        }
+        plan->F = F;
+        stats[2] = over;
+        const int active = allow && over > 0;
+        plan->active = active;
+        plan->round = (int)stats[0];
+        if (active) stats[0] += 1;
+        if (over == 0) plan->finished = 1;
     }
-    plan->F = F;
-    stats[2] = over;
-    const int active = allow && over > 0;
-    plan->active = active;
-    plan->round = (int)stats[0];
-    if (active) stats[0] += 1;
+    __syncthreads();
+    const long long cap = cap_lds;
+    long long m = 0, need = 0;
+    int tdeg = 0;
+    if (i < k) {
+        plan->L[i] = (unsigned long long)L;
+        m = L > cap ? L - cap : 0;
+        if (m > 0) {   // the degree of the m-th smallest member: the first bin at which the running count reaches m
+            long long below = 0;
+            int b = 0;
+            for (; b < bins - 1; ++b) {
+                const long long c = dhist[i * bins + b];
+                if (below + c >= m) break;
+                below += c;
+            }
+            tdeg = b;
+            need = m - below;
+            if (b == bins - 1) sort_lds = 1;   // the last bin holds several degrees: this round sorts
+        }
+        plan->m[i] = m;
+        plan->tdeg[i] = tdeg;
+        plan->need[i] = need;
+    }
+    __syncthreads();
+    if (i == 0) {
+        plan->by_sort = plan->active && sort_lds;
+        plan->by_select = plan->active && !sort_lds;
+    }
+    if (i < k)   // the next round's count starts from zero
+        for (int b = 0; b < bins; ++b) dhist[i * bins + b] = 0;
+}
+
+// ---- selection: the movers are the members below the threshold degree and the first need_i (by id) at it ----
+// Vertex ranges of rows_per_block vertices, one per workgroup, in order.
+// Pass 1: tie[b * k + l] = members of partition l with degree exactly t_l in range b.
+template <typename RowT>
+__global__ __launch_bounds__(kBlock) void bal_tie_count_kernel(int64_t n, int32_t k, int64_t rows_per_block,
+                                                                const RowT *__restrict__ rowptr,
+                                                                const uint8_t *__restrict__ vclass, int32_t class_id,
+                                                                const int32_t *__restrict__ labels,
+                                                                const BalPlan *__restrict__ plan,
+                                                                int32_t *__restrict__ tie) {
+    if (!plan->by_select) return;   // uniform over the grid
+    __shared__ int32_t cnt[256];
+    __shared__ int32_t tdeg[256];
+    cnt[threadIdx.x] = 0;
+    tdeg[threadIdx.x] = (int)threadIdx.x < k && plan->m[threadIdx.x] > 0 ? plan->tdeg[threadIdx.x] : -1;
+    __syncthreads();
+    const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
+    for (int64_t v = b + threadIdx.x; v < e; v += kBlock) {
+        if (vclass && vclass[v] != class_id) continue;
+        const int32_t l = labels[v];
+        if (l < 0 || l >= k) continue;
+        if ((int64_t)(rowptr[v + 1] - rowptr[v]) == (int64_t)tdeg[l]) atomicAdd(&cnt[l], 1);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < k) tie[(int64_t)blockIdx.x * k + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// Pass 2: per partition, exclusive scan of the counts over the ranges (thread l = partition l).
+__global__ __launch_bounds__(256) void bal_tie_scan_kernel(int32_t k, int blocks, const BalPlan *__restrict__ plan,
+                                                            int32_t *__restrict__ tie) {
+    if (!plan->by_select) return;
+    const int l = threadIdx.x;
+    if (l >= k) return;
+    int32_t run = 0;
+    for (int b = 0; b < blocks; ++b) {
+        const int32_t c = tie[(int64_t)b * k + l];
+        tie[(int64_t)b * k + l] = run;
+        run += c;
+    }
 }
 
 template <typename RowT>
@@ -93,27 +211,29 @@ __global__ __launch_bounds__(kBlock) void bal_keys_kernel(int64_t n, int32_t k, 
                                                            const int32_t *__restrict__ labels,
                                                            const BalPlan *__restrict__ plan,
                                                            int32_t *__restrict__ keys) {
-    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v >= n || !plan->active) return;
-    uint32_t key = kStay;
-    if (!vclass || vclass[v] == class_id) {
-        const int32_t l = labels[v];
-        if (l >= 0 && l < k && plan->m[l] > 0) {
-            const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
-            key = ((uint32_t)l << 24) | (uint32_t)std::min<int64_t>(deg, (int64_t)kDegreeMask);
+    if (!plan->by_sort) return;   // uniform over the grid
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n; v += (int64_t)gridDim.x * kBlock) {
+        uint32_t key = kStay;
+        if (!vclass || vclass[v] == class_id) {
+            const int32_t l = labels[v];
+            if (l >= 0 && l < k && plan->m[l] > 0) {
+                const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
+                key = ((uint32_t)l << 24) | (uint32_t)std::min<int64_t>(deg, (int64_t)kDegreeMask);
+            }
         }
+        keys[v] = (int32_t)key;
     }
-    keys[v] = (int32_t)key;
 }
 
 // seg[j] = first sorted position whose partition byte is >= j (j = 0 .. 256).
 __global__ void bal_segments_kernel(int64_t n, const int32_t *__restrict__ keys, const int32_t *__restrict__ order,
                                     BalPlan *plan) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n || !plan->active) return;
-    const int prev = i == 0 ? -1 : (int)((uint32_t)keys[order[i - 1]] >> 24);
-    const int cur = i == n ? 256 : (int)((uint32_t)keys[order[i]] >> 24);
-    for (int j = prev + 1; j <= cur; ++j) plan->seg[j] = i;
+    if (!plan->by_sort) return;   // uniform over the grid
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i <= n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int prev = i == 0 ? -1 : (int)((uint32_t)keys[order[i - 1]] >> 24);
+        const int cur = i == n ? 256 : (int)((uint32_t)keys[order[i]] >> 24);
+        for (int j = prev + 1; j <= cur; ++j) plan->seg[j] = i;
+    }
 }
 
 __device__ __forceinline__ uint64_t draw64(uint64_t seed, uint32_t round, int64_t v) {
@@ -128,28 +248,113 @@ __global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, 
                                                            const int32_t *__restrict__ order,
                                                            const BalPlan *__restrict__ plan, int32_t *__restrict__ labels,
                                                            int64_t *__restrict__ stats) {
-    if (!plan->active) return;   // uniform over the grid
+    if (!plan->by_sort) return;   // uniform over the grid
     __shared__ long long cumf[256];
     cumf[threadIdx.x] = (int)threadIdx.x < k ? plan->cumf[threadIdx.x] : plan->F;
     __syncthreads();
-    const int64_t pos = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    int moved = 0;
-    if (pos < n) {
-        const int32_t v = order[pos];
-        const uint32_t part = (uint32_t)keys[v] >> 24;
-        if (part < (uint32_t)k && pos - plan->seg[part] < plan->m[part]) {
-            const uint64_t r = draw64(seed, (uint32_t)plan->round, v) % (uint64_t)plan->F;
+    unsigned long long moved_total = 0;
+    const int64_t padded = (n + kBlock - 1) / kBlock * kBlock;   // every lane of a wave takes the same number of turns
+    for (int64_t pos = (int64_t)blockIdx.x * kBlock + threadIdx.x; pos < padded; pos += (int64_t)gridDim.x * kBlock) {
+        int moved = 0;
+        if (pos < n) {
+            const int32_t v = order[pos];
+            const uint32_t part = (uint32_t)keys[v] >> 24;
+            if (part < (uint32_t)k && pos - plan->seg[part] < plan->m[part]) {
+                const uint64_t r = draw64(seed, (uint32_t)plan->round, v) % (uint64_t)plan->F;
+                int lo = 0, hi = k - 1;               // first partition whose running sum exceeds r
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if ((uint64_t)cumf[mid] > r) hi = mid; else lo = mid + 1;
+                }
+                labels[v] = lo;
+                moved = 1;
+            }
+        }
+        const unsigned long long b = __ballot(moved);
+        if ((threadIdx.x & 63) == 0) moved_total += (unsigned long long)__popcll(b);
+    }
+    if ((threadIdx.x & 63) == 0 && moved_total)
+        atomicAdd(reinterpret_cast<unsigned long long *>(stats + 1), moved_total);
+}
+
+// Pass 3: the move.  A member of degree t_l moves iff fewer than need_l such members of its partition come
+// before it by id: the count before its range, plus the ordered count inside the range (tiles of 256 vertices:
+// lanes of a wave with the same partition are matched with ballots, waves and tiles are added up in order).
+template <typename RowT>
+__global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int32_t k, int64_t rows_per_block,
+                                                                  uint64_t seed, const RowT *__restrict__ rowptr,
+                                                                  const uint8_t *__restrict__ vclass, int32_t class_id,
+                                                                  const BalPlan *__restrict__ plan,
+                                                                  const int32_t *__restrict__ tie,
+                                                                  int32_t *__restrict__ labels,
+                                                                  int64_t *__restrict__ stats) {
+    if (!plan->by_select) return;   // uniform over the grid
+    constexpr int kWavesPerBlock = kBlock / 64;
+    __shared__ long long cumf[256];
+    __shared__ long long need[256];
+    __shared__ int32_t tdeg[256];
+    __shared__ int32_t running[256];                 // degree-t members of every partition met so far (by id)
+    __shared__ int32_t wcnt[kWavesPerBlock][256];
+    const int t = threadIdx.x, wave = t >> 6;
+    const bool over = t < k && plan->m[t] > 0;
+    cumf[t] = t < k ? plan->cumf[t] : plan->F;
+    need[t] = over ? plan->need[t] : 0;
+    tdeg[t] = over ? plan->tdeg[t] : -1;
+    running[t] = t < k ? tie[(int64_t)blockIdx.x * k + t] : 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) wcnt[w][t] = 0;
+    __syncthreads();
+    const uint64_t F = (uint64_t)plan->F;
+    const uint32_t round = (uint32_t)plan->round;
+    const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
+    unsigned long long moved_total = 0;
+    for (int64_t tile = b; tile < e; tile += kBlock) {
+        const int64_t v = tile + t;
+        int32_t l = -1;
+        int64_t deg = 0;
+        if (v < e && (!vclass || vclass[v] == class_id)) {
+            const int32_t lab = labels[v];
+            if (lab >= 0 && lab < k && tdeg[lab] >= 0) {
+                l = lab;
+                deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
+            }
+        }
+        const bool at_threshold = l >= 0 && deg == (int64_t)tdeg[l];
+        // lanes of this wave at the threshold of the same partition
+        const int key = at_threshold ? l : 0;
+        uint64_t peers = __ballot(at_threshold);
+        for (int bit = 0; bit < 8; ++bit) {
+            const uint64_t m = __ballot((key >> bit) & 1);
+            peers &= ((key >> bit) & 1) ? m : ~m;
+        }
+        const unsigned lane = t & 63;
+        const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+        const int rank_in_wave = __popcll(peers & below);
+        if (at_threshold && rank_in_wave == 0) wcnt[wave][key] = __popcll(peers);
+        __syncthreads();
+        bool move = l >= 0 && deg < (int64_t)tdeg[l];
+        if (at_threshold) {
+            long long before = running[l] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) before += wcnt[w][l];
+            move = before < need[l];
+        }
+        if (move) {
+            const uint64_t r = draw64(seed, round, v) % F;
             int lo = 0, hi = k - 1;               // first partition whose running sum exceeds r
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
                 if ((uint64_t)cumf[mid] > r) hi = mid; else lo = mid + 1;
             }
             labels[v] = lo;
-            moved = 1;
         }
+        const unsigned long long mb = __ballot(move);
+        if (lane == 0) moved_total += (unsigned long long)__popcll(mb);
+        __syncthreads();
+        int32_t add = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) { add += wcnt[w][t]; wcnt[w][t] = 0; }
+        running[t] += add;
+        __syncthreads();
     }
-    const unsigned long long b = __ballot(moved);
-    if ((threadIdx.x & 63) == 0 && b) atomicAdd(reinterpret_cast<unsigned long long *>(stats + 1), (unsigned long long)__popcll(b));
+    if ((t & 63) == 0 && moved_total) atomicAdd(reinterpret_cast<unsigned long long *>(stats + 1), moved_total);
 }
 
 }  // namespace
@@ -162,6 +367,8 @@ BalanceWs carve_balance_ws(int64_t n, void *ws) {
     w.order = c.take<int32_t>((size_t)n);
     w.tmp = c.take<int32_t>((size_t)n);
     w.sort_hist = c.take<int32_t>(sort_hist_elems());
+    w.degree_hist = c.take<uint32_t>(kHistCounters);
+    w.tie = c.take<int32_t>((size_t)kSelBlocksMax * 256);
     w.bytes = align_up(c.used, 256);
     return w;
 }
@@ -171,26 +378,52 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
                    const BalanceWs &w, hipStream_t s) {
     if (k > kPartMax) return EP_EUNSUPPORTED;
     BalPlan *plan = reinterpret_cast<BalPlan *>(w.plan);
-    const unsigned per_vertex = (unsigned)ceil_div(n, kBlock);
+    const unsigned per_vertex = (unsigned)std::min<int64_t>(ceil_div(n, kBlock), 4096);   // grid-stride kernels
     const unsigned count_blocks = (unsigned)std::min<int64_t>(2048, ceil_div(n, kBlock * 8));
+    const int bins = degree_bins(k), cells = k * bins;
+    int64_t rows_per_block = std::max<int64_t>(ceil_div(n, kSelBlocksMax), 4 * kBlock);
+    rows_per_block = ceil_div(rows_per_block, kBlock) * kBlock;
+    const int sel_blocks = (int)ceil_div(n, rows_per_block);
+    auto by_width = [&](auto &&f) {
+        return i64 ? f(static_cast<const int64_t *>(rowptr)) : f(static_cast<const int32_t *>(rowptr));
+    };
     for (int32_t r = 0; r <= max_rounds; ++r) {
-        bal_reset_kernel<<<1, 256, 0, s>>>(plan, stats, r == 0);
+        if (r == 0) {
+            bal_reset_kernel<<<(unsigned)ceil_div(std::max(cells, 256), kBlock), kBlock, 0, s>>>(plan, stats, 1, cells,
+                                                                                              w.degree_hist);
+            EP_LAUNCH_CHECK();
+        }
+        by_width([&](auto *rp) {
+            bal_count_kernel<<<count_blocks, kBlock, 0, s>>>(n, k, bins, rp, vclass, class_id, labels, plan, w.degree_hist);
+            return 0;
+        });
         EP_LAUNCH_CHECK();
-        bal_count_kernel<<<count_blocks, kBlock, 0, s>>>(n, k, vclass, class_id, labels, plan);
-        EP_LAUNCH_CHECK();
-        bal_plan_kernel<<<1, 64, 0, s>>>(k, beta, r < max_rounds, plan, stats);
+        bal_plan_kernel<<<1, 256, 0, s>>>(k, bins, beta, r < max_rounds, plan, w.degree_hist, stats);
         EP_LAUNCH_CHECK();
         if (r == max_rounds) break;   // the closing evaluation only reports what is still overloaded
-        if (i64)
-            bal_keys_kernel<int64_t><<<per_vertex, kBlock, 0, s>>>(n, k, static_cast<const int64_t *>(rowptr), vclass,
-                                                                   class_id, labels, plan, w.keys);
-        else
-            bal_keys_kernel<int32_t><<<per_vertex, kBlock, 0, s>>>(n, k, static_cast<const int32_t *>(rowptr), vclass,
-                                                                   class_id, labels, plan, w.keys);
+        // selection (the usual way) ...
+        by_width([&](auto *rp) {
+            bal_tie_count_kernel<<<sel_blocks, kBlock, 0, s>>>(n, k, rows_per_block, rp, vclass, class_id, labels, plan, w.tie);
+            return 0;
+        });
         EP_LAUNCH_CHECK();
-        int rc = launch_sort_by_key(n, 4, w.keys, nullptr, w.order, w.tmp, w.sort_hist, &plan->active, s);
+        bal_tie_scan_kernel<<<1, 256, 0, s>>>(k, sel_blocks, plan, w.tie);
+        EP_LAUNCH_CHECK();
+        by_width([&](auto *rp) {
+            bal_select_move_kernel<<<sel_blocks, kBlock, 0, s>>>(n, k, rows_per_block, seed, rp, vclass, class_id, plan,
+                                                                 w.tie, labels, stats);
+            return 0;
+        });
+        EP_LAUNCH_CHECK();
+        // ... or, if a threshold degree fell into the last histogram bin, the sort (every kernel reads by_sort)
+        by_width([&](auto *rp) {
+            bal_keys_kernel<<<per_vertex, kBlock, 0, s>>>(n, k, rp, vclass, class_id, labels, plan, w.keys);
+            return 0;
+        });
+        EP_LAUNCH_CHECK();
+        int rc = launch_sort_by_key(n, 4, w.keys, nullptr, w.order, w.tmp, w.sort_hist, &plan->by_sort, s);
         if (rc != EP_OK) return rc;
-        bal_segments_kernel<<<(unsigned)ceil_div(n + 1, kBlock), kBlock, 0, s>>>(n, w.keys, w.order, plan);
+        bal_segments_kernel<<<(unsigned)std::min<int64_t>(ceil_div(n + 1, kBlock), 4096), kBlock, 0, s>>>(n, w.keys, w.order, plan);
         EP_LAUNCH_CHECK();
         bal_move_kernel<<<per_vertex, kBlock, 0, s>>>(n, k, seed, w.keys, w.order, plan, labels, stats);
         EP_LAUNCH_CHECK();

@@ -31,7 +31,6 @@ namespace ep {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kWaves = kBlock / 64;
 // Atomics on one cache line queue up behind each other: every bucket's cursor has a 128-byte line of its own.
 constexpr int kCursorStride = 16;
 constexpr int kAlign = 16;                 // records per 64-byte block: every write to the record buffer is whole blocks

@@ -216,6 +216,8 @@ struct BalanceWs {
     int32_t *order;       // [n]
     int32_t *tmp;         // [n]
     int32_t *sort_hist;
+    uint32_t *degree_hist;   // [k * bins] class members per partition and degree
+    int32_t *tie;            // per vertex range and partition: members at the threshold degree
     size_t bytes;
 };
 BalanceWs carve_balance_ws(int64_t n, void *ws);

@@ -48,6 +48,24 @@ def test_balance_equals_oracle(n, k, beta, rounds, i64):
         assert st[2] == 0
 
 
+@pytest.mark.parametrize("n,k,lo,hi", [(30_011, 200, 90, 400), (20_000, 8, 250, 3_000), (25_000, 64, 0, 600),
+                                      (6_000, 3, 100_000, 2_000_000)])
+def test_balance_with_large_degrees_equals_oracle(n, k, lo, hi):
+    """Degrees beyond the degree histogram of the selection (its last bin holds everything from min(256,
+    16384 / k) - 1 up): the rounds whose threshold degree lies there take the sorting path, the others the
+    selection; both must pick the oracle's movers.  (Degrees stay below 2^24, beyond which the device treats
+    them as equal.)"""
+    rng = np.random.default_rng(n + k)
+    deg = rng.integers(lo, hi, n).astype(np.int64)
+    deg[rng.random(n) < 0.3] = rng.integers(0, 30, n)[: int((rng.random(n) < 0.3).sum())][0]   # and a block of small ones
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    labels = _skewed_labels(n, k, n + 1)
+    want, st_or = oracle.balance(rowptr, labels, k, 1.05, seed=n, max_rounds=12)
+    got, st = _device_balance(rowptr, labels, k, 1.05, n, 12)
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(st, st_or)
+
+
 def test_three_classes_in_sequence_on_a_benchmark_graph():
     """Alg. 3 as a whole on the arxiv-like workload: K-Means labels, then the three loops (training,
     validation, remaining vertices) one after the other on the same label vector."""
