@@ -243,6 +243,16 @@ __device__ __forceinline__ uint64_t draw64(uint64_t seed, uint32_t round, int64_
     return z ^ (z >> 31);
 }
 
+// x mod F without a 64-bit division per draw: with magic = floor((2^64 - 1) / F), q = high half of x * magic
+// is the quotient or up to two less, so at most two subtractions finish the remainder (exact for every x).
+__device__ __forceinline__ uint64_t magic_of(uint64_t F) { return F ? ~0ull / F : 0; }
+__device__ __forceinline__ uint64_t mod_by(uint64_t x, uint64_t F, uint64_t magic) {
+    uint64_t r = x - __umul64hi(x, magic) * F;
+    if (r >= F) r -= F;
+    if (r >= F) r -= F;
+    return r;
+}
+
 __global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, uint64_t seed,
                                                            const int32_t *__restrict__ keys,
                                                            const int32_t *__restrict__ order,
@@ -252,6 +262,7 @@ __global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, 
     __shared__ long long cumf[256];
     cumf[threadIdx.x] = (int)threadIdx.x < k ? plan->cumf[threadIdx.x] : plan->F;
     __syncthreads();
+    const uint64_t F = (uint64_t)plan->F, magic = magic_of(F);
     unsigned long long moved_total = 0;
     const int64_t padded = (n + kBlock - 1) / kBlock * kBlock;   // every lane of a wave takes the same number of turns
     for (int64_t pos = (int64_t)blockIdx.x * kBlock + threadIdx.x; pos < padded; pos += (int64_t)gridDim.x * kBlock) {
@@ -260,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, 
             const int32_t v = order[pos];
             const uint32_t part = (uint32_t)keys[v] >> 24;
             if (part < (uint32_t)k && pos - plan->seg[part] < plan->m[part]) {
-                const uint64_t r = draw64(seed, (uint32_t)plan->round, v) % (uint64_t)plan->F;
+                const uint64_t r = mod_by(draw64(seed, (uint32_t)plan->round, v), F, magic);
                 int lo = 0, hi = k - 1;               // first partition whose running sum exceeds r
                 while (lo < hi) {
                     const int mid = (lo + hi) >> 1;
@@ -303,7 +314,7 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
     running[t] = t < k ? tie[(int64_t)blockIdx.x * k + t] : 0;
     for (int w = 0; w < kWavesPerBlock; ++w) wcnt[w][t] = 0;
     __syncthreads();
-    const uint64_t F = (uint64_t)plan->F;
+    const uint64_t F = (uint64_t)plan->F, magic = magic_of(F);
     const uint32_t round = (uint32_t)plan->round;
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
     unsigned long long moved_total = 0;
@@ -338,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
             move = before < need[l];
         }
         if (move) {
-            const uint64_t r = draw64(seed, round, v) % F;
+            const uint64_t r = mod_by(draw64(seed, round, v), F, magic);
             int lo = 0, hi = k - 1;               // first partition whose running sum exceeds r
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
@@ -355,6 +366,278 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
         __syncthreads();
     }
     if ((t & 63) == 0 && moved_total) atomicAdd(reinterpret_cast<unsigned long long *>(stats + 1), moved_total);
+}
+
+
+// ---- small graphs: all rounds of a call in one launch ---------------------------------------------
+// Up to kSmallN vertices the work of a round is microseconds and the ~20 launches per round of the chain
+// above are all the time there is (about 1,000 launches for three classes and 16 rounds each).  One
+// workgroup of 1,024 threads then runs the whole call: per round the loads and degree counts, the plan,
+// the threshold degree of every overloaded partition, the ordered selection of its movers (every wave
+// over a contiguous range of vertices, the members at the threshold before its range counted first) and
+// their moves, and it stops at the first round that finds nothing overloaded.  The threshold degree is found by
+// selection at any size: if it lies beyond the exact bins, the range that holds it is counted again with
+// narrower bins until the bins are one degree wide (at most five passes up to degree 2^24 - 1, the value
+// degrees are clamped to here as in the sort keys above).  Same movers and same draws as the chain above.
+__device__ __forceinline__ void wave_lds_fence_() {   // orders a wave's own LDS accesses
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+constexpr int kSmallN = 1 << 18;
+constexpr int kSmBlock = 1024;
+constexpr int kSmWaves = kSmBlock / 64;
+constexpr int kSmPer = 8;             // vertices per thread and turn: their loads are in flight together
+constexpr int kSmCounters = 8192;      // LDS counters of the degree histogram (32 KB)
+constexpr int kDegreeLimit = 1 << 24;  // degrees are clamped to kDegreeLimit - 1
+
+template <typename RowT>
+__global__ __launch_bounds__(kSmBlock) void bal_small_kernel(int32_t n, int32_t k, const RowT *__restrict__ rowptr,
+                                                              const uint8_t *__restrict__ vclass, int32_t class_id,
+                                                              double beta, uint64_t seed, int32_t max_rounds,
+                                                              int32_t *__restrict__ labels, int64_t *__restrict__ stats) {
+    // n <= 2^18, so every count fits 32 bits
+    __shared__ unsigned int hist[kSmCounters];
+    __shared__ int32_t running[kSmWaves][256];   // degree-t members of a partition before a wave's place (by id)
+    __shared__ int32_t load_of[256], m_of[256], cumf[256], need[256], below[256];
+    __shared__ int32_t lo[256], hi[256], width[256], tdeg[256], refining[256];
+    __shared__ int32_t arrived[256];             // movers that landed in a partition this round
+    __shared__ int32_t cap_s, F_s, over_s, refine_any;
+    __shared__ unsigned int moved_s;
+    const int t = threadIdx.x, wave = t >> 6;
+    const unsigned lane = t & 63;
+    const int bins = min(256, kSmCounters / k), cells = k * bins;
+    if (t == 0) moved_s = 0;
+    int32_t rounds_run = 0;
+    // every wave owns a contiguous range of vertices (a multiple of 64 long), the ranges in wave order
+    const int per_wave = (n + 64 * kSmWaves - 1) / (64 * kSmWaves) * 64;
+    const int wave_begin = min(n, wave * per_wave), wave_end = min(n, wave_begin + per_wave);
+
+    // Partition and clamped degree of kSmPer vertices v0 + stride q; -1 for a vertex that is not a member of the
+    // class (or past the end).  All loads are issued before anything is looked at: one memory round trip.
+    auto fetch = [&](int v0, int stride, int end, int32_t(&l)[kSmPer], int32_t(&deg)[kSmPer]) {
+        int32_t cls[kSmPer], lab[kSmPer];
+        RowT r0[kSmPer], r1[kSmPer];
+#pragma unroll
+        for (int q = 0; q < kSmPer; ++q) {
+            const int v = v0 + q * stride;
+            const bool in = v < end;
+            const unsigned vs = in ? (unsigned)v : 0u;   // unsigned 32-bit offsets from a uniform base
+            cls[q] = vclass ? (int32_t)vclass[vs] : class_id;
+            lab[q] = labels[vs];
+            r0[q] = rowptr[vs];
+            r1[q] = rowptr[vs + 1];
+            if (!in) cls[q] = class_id + 1;
+        }
+#pragma unroll
+        for (int q = 0; q < kSmPer; ++q) {
+            const bool member = cls[q] == class_id && lab[q] >= 0 && lab[q] < k;
+            l[q] = member ? lab[q] : -1;
+            const int64_t d = (int64_t)(r1[q] - r0[q]);
+            deg[q] = (int32_t)min(max(d, (int64_t)0), (int64_t)kDegreeLimit - 1);
+        }
+    };
+
+    for (int32_t round = 0;; ++round) {
+        // ---- loads of the class per partition and the exact degree bins 0 .. bins - 2 (+ "bins - 1 or more") ----
+        for (int i = t; i < cells; i += kSmBlock) hist[i] = 0;
+        __syncthreads();
+        for (int v0 = t; v0 < n; v0 += kSmPer * kSmBlock) {
+            int32_t l[kSmPer], deg[kSmPer];
+            fetch(v0, kSmBlock, n, l, deg);
+#pragma unroll
+            for (int q = 0; q < kSmPer; ++q)
+                if (l[q] >= 0) atomicAdd(&hist[l[q] * bins + min(deg[q], bins - 1)], 1u);
+        }
+        __syncthreads();
+        if (t < 256) {
+            int32_t L = 0;
+            if (t < k)
+                for (int b = 0; b < bins; ++b) L += (int32_t)hist[t * bins + b];
+            load_of[t] = L;
+        }
+        __syncthreads();
+        if (t == 0) {
+            long long total = 0;
+            for (int j = 0; j < k; ++j) total += load_of[j];
+            long long cap = (long long)floor(beta * (double)total / (double)k);
+            const long long reach = (total + k - 1) / k;
+            if (cap < reach) cap = reach;
+            long long F = 0;
+            int32_t over = 0;
+            for (int j = 0; j < k; ++j) {
+                const long long Lj = load_of[j];
+                if (Lj < cap) F += cap - Lj;
+                cumf[j] = (int32_t)min(F, (long long)0x7fffffff);   // with something overloaded, F <= k n < 2^26
+                if (Lj > cap) ++over;
+            }
+            cap_s = (int32_t)min(cap, (long long)0x7fffffff);   // a capacity beyond n is never reached
+            F_s = (int32_t)min(F, (long long)0x7fffffff);
+            over_s = over;
+            refine_any = 0;
+        }
+        __syncthreads();
+        if (over_s == 0 || round >= max_rounds) {   // uniform: balanced, or the closing evaluation
+            if (t == 0) {
+                stats[0] = rounds_run;
+                stats[1] = (int64_t)moved_s;
+                stats[2] = over_s;
+            }
+            return;
+        }
+        rounds_run = round + 1;
+
+        // ---- threshold degree t_i of every overloaded partition: where its m_i-th smallest member sits ----
+        if (t < 256) {
+            const int32_t m = t < k && load_of[t] > cap_s ? load_of[t] - cap_s : 0;
+            m_of[t] = m;
+            tdeg[t] = -1;
+            need[t] = 0;
+            refining[t] = 0;
+            if (m > 0) {
+                int32_t seen = 0;
+                int b = 0;
+                for (; b < bins - 1; ++b) {
+                    const int32_t c = (int32_t)hist[t * bins + b];
+                    if (seen + c >= m) break;
+                    seen += c;
+                }
+                if (b < bins - 1) {
+                    tdeg[t] = b;
+                    need[t] = m - seen;
+                } else {   // beyond the exact bins: narrow the range [bins - 1, 2^24) down
+                    below[t] = seen;
+                    lo[t] = bins - 1;
+                    hi[t] = kDegreeLimit;
+                    refining[t] = 1;
+                    refine_any = 1;
+                }
+            }
+        }
+        __syncthreads();
+        int again = refine_any;
+        __syncthreads();
+        while (again) {   // uniform
+            for (int i = t; i < cells; i += kSmBlock) hist[i] = 0;
+            if (t < 256 && refining[t]) width[t] = (hi[t] - lo[t] + bins - 1) / bins;
+            if (t == 0) refine_any = 0;
+            __syncthreads();
+            for (int v0 = t; v0 < n; v0 += kSmPer * kSmBlock) {
+                int32_t l[kSmPer], deg[kSmPer];
+                fetch(v0, kSmBlock, n, l, deg);
+#pragma unroll
+                for (int q = 0; q < kSmPer; ++q)
+                    if (l[q] >= 0 && refining[l[q]] && deg[q] >= lo[l[q]] && deg[q] < hi[l[q]])
+                        atomicAdd(&hist[l[q] * bins + (deg[q] - lo[l[q]]) / width[l[q]]], 1u);
+            }
+            __syncthreads();
+            if (t < 256 && refining[t]) {
+                int32_t seen = below[t];
+                int b = 0;
+                for (; b < bins - 1; ++b) {   // the m-th smallest lies in the range, so the last bin ends the search
+                    const int32_t c = (int32_t)hist[t * bins + b];
+                    if (seen + c >= m_of[t]) break;
+                    seen += c;
+                }
+                below[t] = seen;
+                lo[t] += b * width[t];
+                hi[t] = min(hi[t], lo[t] + width[t]);
+                if (width[t] == 1) {
+                    tdeg[t] = lo[t];
+                    need[t] = m_of[t] - seen;
+                    refining[t] = 0;
+                } else {
+                    refine_any = 1;
+                }
+            }
+            __syncthreads();
+            again = refine_any;
+            __syncthreads();
+        }
+
+        // ---- members at the threshold before every wave's range: counts per range, then a scan over the ranges ----
+        for (int w = 0; w < kSmWaves; ++w)
+            if (t < 256) running[w][t] = 0;
+        if (t < 256) arrived[t] = 0;
+        __syncthreads();
+        for (int v0 = wave_begin + (int)lane; v0 < wave_end; v0 += kSmPer * 64) {
+            int32_t l[kSmPer], deg[kSmPer];
+            fetch(v0, 64, wave_end, l, deg);
+#pragma unroll
+            for (int q = 0; q < kSmPer; ++q)
+                if (l[q] >= 0 && m_of[l[q]] > 0 && deg[q] == tdeg[l[q]]) atomicAdd(&running[wave][l[q]], 1);
+        }
+        __syncthreads();
+        if (t < 256) {
+            int32_t run = 0;
+            for (int w = 0; w < kSmWaves; ++w) {
+                const int32_t c = running[w][t];
+                running[w][t] = run;
+                run += c;
+            }
+        }
+        __syncthreads();
+
+        // ---- the movers, every wave over its range in id order: below the threshold, or at it among the first need_i ----
+        const uint64_t F = (uint64_t)F_s, magic = magic_of(F);
+        unsigned int moved_here = 0;
+        for (int base = wave_begin; base < wave_end; base += kSmPer * 64) {   // uniform in the wave
+            const int v0 = base + (int)lane;
+            int32_t l[kSmPer], deg[kSmPer];
+            fetch(v0, 64, wave_end, l, deg);
+#pragma unroll
+            for (int q = 0; q < kSmPer; ++q) {
+                const int v = v0 + 64 * q;
+                const bool cand = l[q] >= 0 && m_of[l[q]] > 0;
+                const bool at_threshold = cand && deg[q] == tdeg[l[q]];
+                const int key = at_threshold ? l[q] : 0;
+                uint64_t peers = __ballot(at_threshold);   // lanes at the threshold of the same partition
+                for (int bit = 0; bit < 8; ++bit) {
+                    const uint64_t mb = __ballot((key >> bit) & 1);
+                    peers &= ((key >> bit) & 1) ? mb : ~mb;
+                }
+                const uint64_t lanes_before = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+                const int rank_in_wave = __popcll(peers & lanes_before);
+                bool move = cand && deg[q] < tdeg[l[q]];
+                if (at_threshold) {
+                    move = running[wave][key] + rank_in_wave < need[key];
+                }
+                wave_lds_fence_();
+                if (at_threshold && rank_in_wave == 0) running[wave][key] += __popcll(peers);
+                wave_lds_fence_();
+                if (move) {
+                    const uint64_t r = mod_by(draw64(seed, (uint32_t)round, v), F, magic);
+                    int a = 0, b = k - 1;               // first partition whose running sum exceeds r
+                    while (a < b) {
+                        const int mid = (a + b) >> 1;
+                        if ((uint64_t)cumf[mid] > r) b = mid; else a = mid + 1;
+                    }
+                    labels[v] = a;
+                    atomicAdd(&arrived[a], 1);   // integer: order does not matter
+                }
+                moved_here += (unsigned int)__popcll(__ballot(move));
+            }
+        }
+        if (lane == 0 && moved_here) atomicAdd(&moved_s, moved_here);
+        __syncthreads();   // the labels written above are read by the next round's count
+        // The loads after this round are known without counting again: every overloaded partition is down to the
+        // capacity and the others got their arrivals; the capacity itself (a function of the class size) stays.
+        // If nothing exceeds it, the next round's evaluation would find the same and end the call.
+        if (t == 0) {
+            int over = 0;
+            for (int j = 0; j < k; ++j) over += load_of[j] - m_of[j] + arrived[j] > cap_s;
+            over_s = over;
+        }
+        __syncthreads();
+        if (over_s == 0) {   // uniform
+            if (t == 0) {
+                stats[0] = rounds_run;
+                stats[1] = (int64_t)moved_s;
+                stats[2] = 0;
+            }
+            return;
+        }
+    }
 }
 
 }  // namespace
@@ -377,6 +660,16 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
                    double beta, uint64_t seed, int32_t max_rounds, int32_t *labels, int64_t *stats,
                    const BalanceWs &w, hipStream_t s) {
     if (k > kPartMax) return EP_EUNSUPPORTED;
+    if (n <= kSmallN) {   // small graph: the whole call in one launch
+        if (i64)
+            bal_small_kernel<<<1, kSmBlock, 0, s>>>((int32_t)n, k, static_cast<const int64_t *>(rowptr), vclass, class_id, beta, seed,
+                                                    max_rounds, labels, stats);
+        else
+            bal_small_kernel<<<1, kSmBlock, 0, s>>>((int32_t)n, k, static_cast<const int32_t *>(rowptr), vclass, class_id, beta, seed,
+                                                    max_rounds, labels, stats);
+        EP_LAUNCH_CHECK();
+        return EP_OK;
+    }
     BalPlan *plan = reinterpret_cast<BalPlan *>(w.plan);
     const unsigned per_vertex = (unsigned)std::min<int64_t>(ceil_div(n, kBlock), 4096);   // grid-stride kernels
     const unsigned count_blocks = (unsigned)std::min<int64_t>(2048, ceil_div(n, kBlock * 8));

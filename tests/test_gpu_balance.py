@@ -34,6 +34,8 @@ def _skewed_labels(n, k, seed):
 @pytest.mark.parametrize("n,k,beta,rounds,i64", [
     (1, 1, 1.0, 4, False), (257, 2, 1.0, 8, False), (5_003, 8, 1.05, 16, False), (20_011, 64, 1.2, 16, True),
     (70_001, 255, 1.05, 32, True), (40_000, 5, 1.0, 1, False), (40_000, 5, 1.0, 0, False),
+    # beyond 2^18 vertices the rounds run as a chain of launches instead of one
+    (300_007, 16, 1.05, 16, True), (280_001, 6, 1.1, 8, False), (262_144, 40, 1.05, 16, False), (262_145, 40, 1.05, 16, False),
 ])
 def test_balance_equals_oracle(n, k, beta, rounds, i64):
     rng = np.random.default_rng(n + k)
@@ -49,12 +51,12 @@ def test_balance_equals_oracle(n, k, beta, rounds, i64):
 
 
 @pytest.mark.parametrize("n,k,lo,hi", [(30_011, 200, 90, 400), (20_000, 8, 250, 3_000), (25_000, 64, 0, 600),
-                                      (6_000, 3, 100_000, 2_000_000)])
+                                      (6_000, 3, 100_000, 2_000_000), (270_000, 8, 250, 3_000), (300_000, 200, 60, 400)])
 def test_balance_with_large_degrees_equals_oracle(n, k, lo, hi):
-    """Degrees beyond the degree histogram of the selection (its last bin holds everything from min(256,
-    16384 / k) - 1 up): the rounds whose threshold degree lies there take the sorting path, the others the
-    selection; both must pick the oracle's movers.  (Degrees stay below 2^24, beyond which the device treats
-    them as equal.)"""
+    """Degrees beyond the exact bins of the degree histogram.  Up to 2^18 vertices the range that holds the
+    threshold degree is counted again with narrower bins; beyond, the rounds whose threshold degree lies in the
+    last bin (min(256, 16384 / k) - 1 and up) take the sorting path, the others the selection.  All must pick
+    the oracle's movers.  (Degrees stay below 2^24, beyond which the device treats them as equal.)"""
     rng = np.random.default_rng(n + k)
     deg = rng.integers(lo, hi, n).astype(np.int64)
     deg[rng.random(n) < 0.3] = rng.integers(0, 30, n)[: int((rng.random(n) < 0.3).sum())][0]   # and a block of small ones
