@@ -34,7 +34,7 @@ constexpr int kBlock = 256;
 // Atomics on one cache line queue up behind each other: every bucket's cursor has a 128-byte line of its own.
 constexpr int kCursorStride = 16;
 constexpr int kAlign = 16;                 // records per 64-byte block: every write to the record buffer is whole blocks
-constexpr int kScatterGridMax = 256 * 2;   // workgroups of the scatter pass (two per compute unit)
+constexpr int kScatterGridMax = 256;       // workgroups of the scatter pass (one per compute unit)
 constexpr int kSliceShift = 17;            // label piece held in LDS: 2^17 bytes
 constexpr int kSweepBlock = 1024;
 constexpr int kSweepPerThread = 64;
@@ -107,7 +107,7 @@ __global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long
 //   phase B  the counters are scanned (start of every bucket's run inside the tile) and thread b reserves the
 //            run of bucket b in the record buffer
 //   phase C  the records go to their sorted place in LDS, then every run leaves as one contiguous stream
-constexpr int kScatterBlock = 512;
+constexpr int kScatterBlock = 1024;
 constexpr int kScatterWaves = kScatterBlock / 64;
 constexpr int kTileSteps = 4;
 constexpr int kTile = kScatterWaves * kTileSteps * 256;
@@ -122,7 +122,6 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                                                                         uint32_t *__restrict__ records,
                                                                         unsigned long long *__restrict__ dropped) {
     static_assert(kBucketsMax <= kScatterBlock, "one thread per bucket in the scan of a tile");
-    __shared__ uint32_t sorted[kTile];
     __shared__ int32_t tile_cnt[kBucketsMax];        // entries of the tile per bucket
     __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
     __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
@@ -133,7 +132,9 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     // Records of earlier tiles that did not fill a whole 64-byte block of their bucket wait here for the next
     // tile, so that every write to the record buffer is a run of whole blocks at a block-aligned place (a
     // partial block costs the memory a read-modify-write).
-    extern __shared__ __attribute__((aligned(16))) uint32_t resid[];   // nb * (kAlign - 1) records
+    extern __shared__ __attribute__((aligned(16))) uint32_t scatter_lds[];
+    uint32_t *sorted = scatter_lds;           // kTile records, sorted by bucket
+    uint32_t *resid = scatter_lds + kTile;    // nb * (kAlign - 1) records
     __shared__ int32_t resid_cnt[kBucketsMax];
     __shared__ int32_t run_out[kBucketsMax];         // records of (waiting + run) that leave with this tile
     const int lane = threadIdx.x & 63;
@@ -271,22 +272,28 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         for (int i = 0; i < kTileSteps * 4; ++i)
             if (where[i] != 0xffffffffu) sorted[run_start[where[i] & 511u] + (int)(where[i] >> 9)] = rec[i];
         __syncthreads();
-        for (int b = wave; b < nb; b += kScatterWaves) {
+        // Four buckets per wave and turn, 16 lanes each: a run of this size is one or two 64-byte blocks, and a
+        // whole wave per bucket spent most of its instructions on lanes with nothing to write.
+        for (int b0 = 4 * wave; b0 < nb; b0 += 4 * kScatterWaves) {
+            const int b = b0 + (lane >> 4), li = lane & 15;
+            const bool valid = b < nb;
             // the bucket's stream = the records that waited, then this tile's run; `out` of them leave
-            const int first = run_start[b], cnt = run_start[b + 1] - first;
-            const int waiting = resid_cnt[b], out = run_out[b];
-            const int64_t dest = run_dest[b];
-            uint32_t *wait_b = resid + b * (kAlign - 1);
+            const int first = valid ? run_start[b] : 0, cnt = valid ? run_start[b + 1] - first : 0;
+            const int waiting = valid ? resid_cnt[b] : 0, out = valid ? run_out[b] : 0;
+            const int64_t dest = valid ? run_dest[b] : -1;
+            uint32_t *wait_b = resid + (valid ? b : 0) * (kAlign - 1);
             if (dest >= 0)
-                for (int i = lane; i < out; i += 64) records[dest + i] = i < waiting ? wait_b[i] : sorted[first + i - waiting];
+                for (int i = li; i < out; i += 16) records[dest + i] = i < waiting ? wait_b[i] : sorted[first + i - waiting];
             const int keep = waiting + cnt - out;   // < kAlign
             wave_fence();
-            if (out == 0) {                          // nothing left: the run joins the waiting records
-                if (lane < cnt) wait_b[waiting + lane] = sorted[first + lane];
-            } else if (lane < keep) {                // out >= kAlign > waiting: the tail of the run waits
-                wait_b[lane] = sorted[first + out - waiting + lane];
+            if (valid) {
+                if (out == 0) {                          // nothing left: the run joins the waiting records
+                    if (li < cnt) wait_b[waiting + li] = sorted[first + li];
+                } else if (li < keep) {                  // out >= kAlign > waiting: the tail of the run waits
+                    wait_b[li] = sorted[first + out - waiting + li];
+                }
+                if (li == 0) resid_cnt[b] = keep;
             }
-            if (lane == 0) resid_cnt[b] = keep;
         }
         __syncthreads();
         for (int b = threadIdx.x; b < nb; b += kScatterBlock) tile_cnt[b] = 0;
@@ -379,7 +386,7 @@ __global__ __launch_bounds__(kSweepBlock) void bucket_sweep_kernel(int64_t n, in
 // Dynamic LDS beyond 64 KB has to be allowed per kernel: done once per kernel and device (`done`: one word per
 // kernel of this file, one bit per device).
 int set_big_lds(const void *kern, std::atomic<uint64_t> &done, int bytes) {
-    if (bytes <= 64 * 1024) return EP_OK;
+    if (bytes + 16 * 1024 <= 64 * 1024) return EP_OK;   // room for the static LDS beside it
     int dev = 0;
     EP_HIP_TRY(hipGetDevice(&dev));
     const uint64_t bit = 1ull << (dev & 63);
@@ -389,7 +396,7 @@ int set_big_lds(const void *kern, std::atomic<uint64_t> &done, int bytes) {
     }
     return EP_OK;
 }
-std::atomic<uint64_t> g_sweep_lds{0};
+std::atomic<uint64_t> g_sweep_lds{0}, g_scatter_lds64{0}, g_scatter_lds32{0};
 
 }  // namespace
 
@@ -419,18 +426,24 @@ int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void
     bucket_scan_kernel<<<1, 64, 0, s>>>(pl.nb, (int)sgrid, hist, w.bucket_base, cursor, w.bucket_items);
     EP_LAUNCH_CHECK();
     {
-        const int resid_bytes = pl.nb * (kAlign - 1) * 4;   // <= 30 KB
+        // the tile (64 KB) and the waiting records (<= 30 KB) in dynamic LDS
+        const int scatter_bytes = (kTile + pl.nb * (kAlign - 1)) * 4;
+        constexpr int kScatterLdsMax = (kTile + kBucketsMax * (kAlign - 1)) * 4;
         if (i64) {
-            bucket_scatter_kernel<int64_t><<<sgrid, kScatterBlock, resid_bytes, s>>>(
+            int rc = set_big_lds(reinterpret_cast<const void *>(bucket_scatter_kernel<int64_t>), g_scatter_lds64, kScatterLdsMax);
+            if (rc != EP_OK) return rc;
+            bucket_scatter_kernel<int64_t><<<sgrid, kScatterBlock, scatter_bytes, s>>>(
                 n, nnz, pl.shift, pl.nb, static_cast<const int64_t *>(rowptr), colidx, w.label8, w.bucket_base, cursor,
                 w.bucket_records, dropped);
         } else {
-            bucket_scatter_kernel<int32_t><<<sgrid, kScatterBlock, resid_bytes, s>>>(
+            int rc = set_big_lds(reinterpret_cast<const void *>(bucket_scatter_kernel<int32_t>), g_scatter_lds32, kScatterLdsMax);
+            if (rc != EP_OK) return rc;
+            bucket_scatter_kernel<int32_t><<<sgrid, kScatterBlock, scatter_bytes, s>>>(
                 n, nnz, pl.shift, pl.nb, static_cast<const int32_t *>(rowptr), colidx, w.label8, w.bucket_base, cursor,
                 w.bucket_records, dropped);
         }
         EP_LAUNCH_CHECK();
-        int rc = set_big_lds(reinterpret_cast<const void *>(bucket_sweep_kernel), g_sweep_lds, 1 << kSliceShift);
+        const int rc = set_big_lds(reinterpret_cast<const void *>(bucket_sweep_kernel), g_sweep_lds, 1 << kSliceShift);
         if (rc != EP_OK) return rc;
         bucket_sweep_kernel<<<kSweepGrid, kSweepBlock, 1 << kSliceShift, s>>>(n, pl.shift, pl.nb, w.label8, cursor,
                                                                               w.bucket_base, w.bucket_items,
