@@ -16,7 +16,7 @@
 //                          the entry's bucket: a workgroup sorts a tile of 8,192 entries by bucket in LDS and
 //                          every bucket's run leaves as a contiguous stream of whole 64-byte blocks, its place
 //                          reserved with one integer atomic per bucket and tile
-//   bucket_sweep_kernel    a workgroup takes 64 K records of one bucket into registers, walks the bucket's
+//   bucket_sweep_kernel    a workgroup takes 96 K records of one bucket into registers, walks the bucket's
 //                          label slice through LDS 128 KB at a time and compares each record against the
 //                          piece that holds its v
 // Traffic: colidx twice, the records once out and once in, 4 bytes each: 16 bytes per entry in streams
@@ -37,7 +37,7 @@ constexpr int kAlign = 16;                 // records per 64-byte block: every w
 constexpr int kScatterGridMax = 256;       // workgroups of the scatter pass (one per compute unit)
 constexpr int kSliceShift = 17;            // label piece held in LDS: 2^17 bytes
 constexpr int kSweepBlock = 1024;
-constexpr int kSweepPerThread = 64;
+constexpr int kSweepPerThread = 96;
 constexpr int kChunk = kSweepBlock * kSweepPerThread;   // records per work item of the last pass
 constexpr int kSweepGrid = 1024;
 
