@@ -398,23 +398,29 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
                 for (int mt = 0; mt < KT; ++mt) acc[mt] = mfma_bf16_k32(a, ch[mt][s], acc[mt]);
             }
         } else {
+            // The operands of K-step s + 1 are split between the instruction groups of K-step s (as in
+            // lloyd_small_kernel): a wave cannot issue past a matrix instruction that waits for the pipe, so 24
+            // of them back to back would leave the vector pipe idle for as long as the matrix pipe is busy.
+            u32x4 xh[2], xm[2], xl[2];
+            auto split_pair = [&](int s, int pr) {
+                const f32x4 &v = x[2 * s + (pr >> 1)];
+                const Split3 t = split3_pair(v[2 * (pr & 1)], v[2 * (pr & 1) + 1]);
+                xh[s & 1][pr] = t.h, xm[s & 1][pr] = t.m, xl[s & 1][pr] = t.l;
+            };
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) split_pair(0, pr);
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                u32x4 xh, xm, xl;
-#pragma unroll
-                for (int pr = 0; pr < 4; ++pr) {
-                    const f32x4 &v = x[2 * s + (pr >> 1)];
-                    const Split3 t = split3_pair(v[2 * (pr & 1)], v[2 * (pr & 1) + 1]);
-                    xh[pr] = t.h, xm[pr] = t.m, xl[pr] = t.l;
-                }
 #pragma unroll
                 for (int pp = 0; pp < 6; ++pp) {   // xh.cl, xl.ch, xm.cm, xh.cm, xm.ch, xh.ch
-                    const u32x4 &a = pp == 1 ? xl : (pp == 2 || pp == 4) ? xm : xh;
+                    const u32x4 &a = pp == 1 ? xl[s & 1] : (pp == 2 || pp == 4) ? xm[s & 1] : xh[s & 1];
 #pragma unroll
                     for (int mt = 0; mt < KT; ++mt) {
                         const u32x4 &b = pp == 0 ? cl[mt][s] : (pp == 2 || pp == 3) ? cm[mt][s] : ch[mt][s];
                         acc[mt] = mfma_bf16_k32(a, b, acc[mt]);
                     }
+                    if (pp < 4 && s + 1 < KS) split_pair(s + 1, pp);
+                    __builtin_amdgcn_sched_barrier(0);   // pin the interleaving
                 }
             }
         }
