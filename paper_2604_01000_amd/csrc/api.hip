@@ -128,17 +128,19 @@ int run_rounds_bounded(const ep_problem &p, const void *X, int32_t iters, float 
     }
     for (int32_t t = kBoundsWarmRounds; t < iters; ++t) {
         const bool all_points = t == kBoundsWarmRounds;
-        if (all_points) rc = launch_record_searched(p.n, b.searched + t, s);
-        else rc = launch_bounds_pass(p, labels, b, b.searched + t, s);
-        if (rc != EP_OK) return rc;
-        if ((rc = launch_keep_centroids(p, C, b, s)) != EP_OK) return rc;
-        if ((rc = launch_bounds_round(p, X, C, w, b, all_points, labels, s)) != EP_OK) return rc;
-        if ((rc = launch_small_finalize_parts(p, bounds_round_parts(p), C, counts, w, add, s)) != EP_OK) return rc;
-        if ((rc = launch_accumulate_counts(p.k, add, s)) != EP_OK) return rc;
-        if (objective_hist &&
-            (rc = launch_objective_from_sums(p, w, b, small_xsq_total(w), objective_hist + t, s)) != EP_OK)
+        if (all_points) {   // later rounds find the centroids of their assignment kept by the round before
+            if ((rc = launch_record_searched(p.n, b.searched + t, s)) != EP_OK) return rc;
+            if ((rc = launch_keep_centroids(p, C, b, s)) != EP_OK) return rc;
+        } else if ((rc = launch_bounds_pass(p, labels, b, b.searched + t, s)) != EP_OK) {
             return rc;
-        if (t + 1 < iters && (rc = launch_drift(p, C, b, s)) != EP_OK) return rc;
+        }
+        if ((rc = launch_bounds_round(p, X, C, w, b, all_points, labels, s)) != EP_OK) return rc;
+        if ((rc = launch_small_finalize_parts(p, bounds_round_parts(p), all_points ? nullptr : b.n_active, C, counts, w,
+                                              add, s)) != EP_OK)
+            return rc;
+        if ((rc = launch_bounds_tail(p, C, w, b, small_xsq_total(w), objective_hist ? objective_hist + t : nullptr,
+                                     t + 1 < iters, s)) != EP_OK)
+            return rc;
     }
     return EP_OK;
 }

@@ -30,6 +30,14 @@ constexpr int kUpdateKeep = 4;   // internal: a finalizing call also leaves the 
 inline UpdateAcc whole_update() { return UpdateAcc{nullptr, nullptr, nullptr, EP_UPDATE_FINALIZE}; }
 
 #ifdef __HIPCC__
+// Workgroups of the bounded search (4 waves, 16 rows per wave and step, steps dealt to the waves in order) that
+// get any row of a list of `len` rows (clamped to [0, n]) on a grid of `parts`: the first so many.
+__device__ __forceinline__ int list_parts(int64_t len, int64_t n, int parts) {
+    len = len < 0 ? 0 : (len > n ? n : len);
+    const int64_t with_rows = (len + 63) / 64;
+    return with_rows < parts ? (int)with_rows : parts;
+}
+
 // Last step of every update kernel for element `at` = j * d + column of centroid j, given this call's
 // sum `tot` and count `cnt` for it: add what earlier chunks left, then either form the mean (an empty
 // cluster keeps its previous centroid) or leave the running sum for the next chunk.  Every element is
@@ -116,9 +124,10 @@ int launch_small_round(const ep_problem &p, const void *X, float *C, const Kmean
                        int64_t *counts, double *objective, bool first_round, hipStream_t s,
                        const UpdateAcc &acc = whole_update());
 // Second pass over `parts` per-workgroup partials that another kernel left in w.psum / w.pcnt (the bounded
-// rounds): C <- means in place, no objective.
-int launch_small_finalize_parts(const ep_problem &p, int parts, float *C, int64_t *counts, const KmeansWs &w,
-                                const UpdateAcc &acc, hipStream_t s);
+// rounds): C <- means in place, no objective.  With list_len (device), only the first
+// list_parts(*list_len, p.n, parts) partials were written and are read.
+int launch_small_finalize_parts(const ep_problem &p, int parts, const int64_t *list_len, float *C, int64_t *counts,
+                                const KmeansWs &w, const UpdateAcc &acc, hipStream_t s);
 // Where the fused rounds keep sum ||x||^2 between the rounds of a run.
 double *small_xsq_total(const KmeansWs &w);
 
@@ -128,7 +137,6 @@ struct BoundsWs {
     float *lb;               // [n] lower bound on the distance to every other centroid
     int32_t *active_idx;     // [n] rows to search this round, ascending
     int32_t *block_counts;   // per-workgroup counts of the bounds pass
-    int64_t *block_offsets;  // their exclusive scan
     int64_t *n_active;       // [1] rows to search this round
     int64_t *searched;       // [iters] rows searched per round of the run
     float *delta;            // [k] centroid movement of the last update
@@ -142,9 +150,11 @@ int bounds_round_parts(const ep_problem &p);
 int launch_record_searched(int64_t value, int64_t *slot, hipStream_t s);
 int launch_copy_searched(int32_t iters, const BoundsWs &w, int64_t *out, hipStream_t s);
 int launch_keep_centroids(const ep_problem &p, const float *C, const BoundsWs &w, hipStream_t s);
-int launch_drift(const ep_problem &p, const float *C_new, const BoundsWs &w, hipStream_t s);
-int launch_objective_from_sums(const ep_problem &p, const KmeansWs &kw, const BoundsWs &w, const double *xsq_total,
-                               double *objective, hipStream_t s);
+// After the means of a bounded round: the kept counts take the round's changes, the round's objective is formed
+// from the kept sums (objective may be null), and with want_drift the centroid movements are left for the next
+// round's bounds pass and w.C_old becomes C_new.
+int launch_bounds_tail(const ep_problem &p, const float *C_new, const KmeansWs &kw, const BoundsWs &w,
+                       const double *xsq_total, double *objective, bool want_drift, hipStream_t s);
 // Applies the last drift to every point's bounds and lists the rows whose bounds no longer separate.
 int launch_bounds_pass(const ep_problem &p, const int32_t *labels, const BoundsWs &w, int64_t *searched_slot,
                        hipStream_t s);

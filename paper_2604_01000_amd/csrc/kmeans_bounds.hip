@@ -19,13 +19,14 @@
 // Kernels of one bounded round:
 //   bounds_update_kernel    streams (label, u, l), 12 bytes per point, applies the drift, marks and counts
 //                           the points that must be searched (per workgroup)
-//   bounds_scan_kernel      exclusive scan of those counts (one workgroup)
-//   bounds_compact_kernel   writes the indices of the points to search, in ascending order
+//   bounds_compact_kernel   writes the indices of the points to search, in ascending order (a workgroup adds
+//                           up the counts of the workgroups before it)
 //   bounds_round_kernel     the search of those points (matrix cores), new bounds, label changes, and
 //                           per-workgroup partial sums of the rows that changed side (+x new, -x old)
 //   lloyd_small_finalize_kernel (kmeans_small.hip) adds the partials to the kept sums and forms the means
-//   objective_from_sums_kernel  the round's objective from the sums: sum ||x||^2 - 2 sum_j c_j.s_j + sum_j n_j ||c_j||^2
-//   drift_kernel            delta_j, its two largest values, max ||c||^2
+//   bounds_tail_kernel      one workgroup: brings the kept counts up to date, forms the round's objective from
+//                           the sums (sum ||x||^2 - 2 sum_j c_j.s_j + sum_j n_j ||c_j||^2), then delta_j, its two
+//                           largest values and max ||c||^2, and keeps the new centroids for the next round
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
@@ -100,51 +101,30 @@ __global__ __launch_bounds__(kBlock) void bounds_update_kernel(int64_t n, int64_
     if (threadIdx.x == 0) block_counts[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
 }
 
-// Exclusive scan of the per-workgroup counts (at most kBoundsBlocksMax of them) by one workgroup of 1024
-// threads; the total goes to *n_active and to the run's per-round record.
-__global__ __launch_bounds__(1024) void bounds_scan_kernel(int blocks, const int32_t *__restrict__ block_counts,
-                                                            int64_t *__restrict__ block_offsets,
-                                                            int64_t *__restrict__ n_active,
-                                                            int64_t *__restrict__ searched_slot) {
-    __shared__ int64_t part[1024];
-    const int t = threadIdx.x;
-    constexpr int kPer = kBoundsBlocksMax / 1024;
-    int64_t v[kPer], sum = 0;
-#pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-        const int i = t * kPer + q;
-        v[q] = i < blocks ? block_counts[i] : 0;
-        sum += v[q];
-    }
-    part[t] = sum;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-        const int64_t add = t >= off ? part[t - off] : 0;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
-    }
-    int64_t run = part[t] - sum;
-#pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-        const int i = t * kPer + q;
-        if (i < blocks) block_offsets[i] = run;
-        run += v[q];
-    }
-    if (t == 1023) {
-        *n_active = part[t];
-        *searched_slot = part[t];
-    }
-}
-
+// Writes the indices of the marked points in ascending order.  A workgroup's first position is the sum of the
+// counts of the workgroups before it (at most kBoundsBlocksMax of them, added up here in integers); the last
+// workgroup also records the total.
 __global__ __launch_bounds__(kBlock) void bounds_compact_kernel(int64_t n, int64_t rows_per_block,
                                                                  const float *__restrict__ ub,
-                                                                 const int64_t *__restrict__ block_offsets,
-                                                                 int32_t *__restrict__ active_idx) {
+                                                                 const int32_t *__restrict__ block_counts,
+                                                                 int32_t *__restrict__ active_idx,
+                                                                 int64_t *__restrict__ n_active,
+                                                                 int64_t *__restrict__ searched_slot) {
     __shared__ int32_t wave_cnt[kWaves];
+    __shared__ int64_t wave_before[kWaves];
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
     const int wave = threadIdx.x >> 6;
-    int64_t running = block_offsets[blockIdx.x];
+    int64_t before = 0;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kBlock) before += block_counts[i];
+    for (int off = 32; off > 0; off >>= 1) before += __shfl_down(before, off, 64);
+    if ((threadIdx.x & 63) == 0) wave_before[wave] = before;
+    __syncthreads();
+    int64_t running = wave_before[0] + wave_before[1] + wave_before[2] + wave_before[3];
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int64_t total = running + block_counts[blockIdx.x];
+        *n_active = total;
+        *searched_slot = total;
+    }
     for (int64_t tile = b; tile < e; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
         const bool active = i < e && (__float_as_uint(ub[i]) >> 31) != 0;   // marked by bounds_update_kernel
@@ -179,14 +159,43 @@ __device__ __forceinline__ double centroid_used(float c) {
     return BF16 ? (double)bf16_to_f32(f32_to_bf16_rne(c)) : (double)c;
 }
 
-// delta_j = ||c_new_j - c_old_j|| of the centroids as the distances use them, its two largest values and
-// max_j ||c_new_j||^2.  One workgroup; wave w takes the centroids w, w + 4, ...
+// What follows the means of a bounded round, in one workgroup:
+//   the kept counts take the round's changes (cnt += chunk_cnt);
+//   objective (if asked for) of the round whose assignment used C_old (as the distances use it) and left the sums
+//   and counts: sum ||x||^2 - 2 sum_j c_j . s_j + sum_j n_j ||c_j||^2, in fp64 and a fixed order;
+//   drift (if another round follows): delta_j = ||c_new_j - c_old_j|| of the centroids as the distances use them,
+//   its two largest values and max_j ||c_new_j||^2 (wave w takes the centroids w, w + 4, ...), after which C_old
+//   becomes C_new for that round.
 template <bool BF16>
-__global__ __launch_bounds__(kBlock) void drift_kernel(int32_t k, int32_t d, const float *__restrict__ C_new,
-                                                        const float *__restrict__ C_old, float *__restrict__ delta,
-                                                        DriftTop *__restrict__ top) {
+__global__ __launch_bounds__(kBlock) void bounds_tail_kernel(int32_t k, int32_t d, const float *__restrict__ C_new,
+                                                              float *__restrict__ C_old,
+                                                              const double *__restrict__ sum, int64_t *__restrict__ cnt,
+                                                              const int64_t *__restrict__ chunk_cnt,
+                                                              const double *__restrict__ xsq_total,
+                                                              double *__restrict__ objective, int want_drift,
+                                                              float *__restrict__ delta, DriftTop *__restrict__ top) {
+    __shared__ double wave_part[kWaves];
+    __shared__ int64_t cnt_lds[64];
     __shared__ float delta_lds[64], norm_lds[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if ((int)threadIdx.x < k) {
+        const int64_t all = cnt[threadIdx.x] + chunk_cnt[threadIdx.x];
+        cnt[threadIdx.x] = all;
+        cnt_lds[threadIdx.x] = all;
+    }
+    __syncthreads();
+    if (objective) {
+        double part = 0.0;
+        for (int e = threadIdx.x; e < k * d; e += kBlock) {
+            const double c = centroid_used<BF16>(C_old[e]);
+            part += c * ((double)cnt_lds[e / d] * c - 2.0 * sum[e]);
+        }
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+        if (lane == 0) wave_part[wave] = part;
+        __syncthreads();
+        if (threadIdx.x == 0) *objective = *xsq_total + (wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3]);
+    }
+    if (!want_drift) return;
     for (int j = wave; j < k; j += kWaves) {
         double moved = 0.0, norm = 0.0;
         for (int m = lane; m < d; m += 64) {
@@ -204,7 +213,8 @@ __global__ __launch_bounds__(kBlock) void drift_kernel(int32_t k, int32_t d, con
             norm_lds[j] = (float)norm * kUp;
         }
     }
-    __syncthreads();
+    __syncthreads();   // every read of C_old is done
+    for (int e = threadIdx.x; e < k * d; e += kBlock) C_old[e] = C_new[e];
     if ((int)threadIdx.x < k) delta[threadIdx.x] = delta_lds[threadIdx.x];
     if (threadIdx.x == 0) {
         DriftTop t{0.f, 0.f, 0.f, -1};
@@ -216,27 +226,6 @@ __global__ __launch_bounds__(kBlock) void drift_kernel(int32_t k, int32_t d, con
         }
         *top = t;
     }
-}
-
-// objective of the round whose assignment used C_used_from (as the distances use it) and left the sums
-// and counts: sum ||x||^2 - 2 sum_j c_j . s_j + sum_j n_j ||c_j||^2, in fp64 and a fixed order.
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void objective_from_sums_kernel(int32_t k, int32_t d,
-                                                                      const float *__restrict__ C_assign,
-                                                                      const double *__restrict__ sum,
-                                                                      const int64_t *__restrict__ cnt,
-                                                                      const double *__restrict__ xsq_total,
-                                                                      double *__restrict__ out) {
-    __shared__ double wave_part[kWaves];
-    double part = 0.0;
-    for (int e = threadIdx.x; e < k * d; e += kBlock) {
-        const double c = centroid_used<BF16>(C_assign[e]);
-        part += c * ((double)cnt[e / d] * c - 2.0 * sum[e]);
-    }
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
-    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = part;
-    __syncthreads();
-    if (threadIdx.x == 0) *out = *xsq_total + (wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3]);
 }
 
 // ---- the search of the points whose bounds no longer separate ------------------------------------
@@ -266,6 +255,9 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     float *lds = reinterpret_cast<float *>(dyn_lds);
     __shared__ int32_t cnt_lds[16 * KT];
 
+    // a workgroup that gets no row of the list leaves no partial (the second pass knows which ones do)
+    static_assert(kSub * kWaves == 64, "list_parts counts workgroups of 64 rows per step");
+    if (n_active_ptr && (int)blockIdx.x >= list_parts(*n_active_ptr, n, (int)gridDim.x)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, c = lane & 15;
@@ -555,7 +547,6 @@ BoundsWs carve_bounds_ws(const ep_problem &p, int32_t iters, void *ws) {
     w.lb = c.take<float>((size_t)p.n);
     w.active_idx = c.take<int32_t>((size_t)p.n);
     w.block_counts = c.take<int32_t>(kBoundsBlocksMax);
-    w.block_offsets = c.take<int64_t>(kBoundsBlocksMax);
     w.n_active = c.take<int64_t>(1);
     w.searched = c.take<int64_t>((size_t)std::max(iters, 1));
     w.delta = c.take<float>((size_t)p.k);
@@ -584,20 +575,15 @@ int launch_keep_centroids(const ep_problem &p, const float *C, const BoundsWs &w
     return EP_OK;
 }
 
-int launch_drift(const ep_problem &p, const float *C_new, const BoundsWs &w, hipStream_t s) {
+int launch_bounds_tail(const ep_problem &p, const float *C_new, const KmeansWs &kw, const BoundsWs &w,
+                       const double *xsq_total, double *objective, bool want_drift, hipStream_t s) {
     DriftTop *top = reinterpret_cast<DriftTop *>(w.top);
-    if (p.dtype == EP_BF16) drift_kernel<true><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, w.delta, top);
-    else drift_kernel<false><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, w.delta, top);
-    EP_LAUNCH_CHECK();
-    return EP_OK;
-}
-
-int launch_objective_from_sums(const ep_problem &p, const KmeansWs &kw, const BoundsWs &w, const double *xsq_total,
-                               double *objective, hipStream_t s) {
     if (p.dtype == EP_BF16)
-        objective_from_sums_kernel<true><<<1, kBlock, 0, s>>>(p.k, p.d, w.C_old, kw.acc_sum, kw.acc_cnt, xsq_total, objective);
+        bounds_tail_kernel<true><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, kw.acc_sum, kw.acc_cnt, kw.chunk_cnt,
+                                                      xsq_total, objective, want_drift ? 1 : 0, w.delta, top);
     else
-        objective_from_sums_kernel<false><<<1, kBlock, 0, s>>>(p.k, p.d, w.C_old, kw.acc_sum, kw.acc_cnt, xsq_total, objective);
+        bounds_tail_kernel<false><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, kw.acc_sum, kw.acc_cnt, kw.chunk_cnt,
+                                                       xsq_total, objective, want_drift ? 1 : 0, w.delta, top);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
@@ -609,9 +595,8 @@ int launch_bounds_pass(const ep_problem &p, const int32_t *labels, const BoundsW
     bounds_update_kernel<<<geo.blocks, kBlock, 0, s>>>(p.n, geo.rows_per_block, p.k, labels, w.ub, w.lb, w.delta, top,
                                                        w.block_counts);
     EP_LAUNCH_CHECK();
-    bounds_scan_kernel<<<1, 1024, 0, s>>>(geo.blocks, w.block_counts, w.block_offsets, w.n_active, searched_slot);
-    EP_LAUNCH_CHECK();
-    bounds_compact_kernel<<<geo.blocks, kBlock, 0, s>>>(p.n, geo.rows_per_block, w.ub, w.block_offsets, w.active_idx);
+    bounds_compact_kernel<<<geo.blocks, kBlock, 0, s>>>(p.n, geo.rows_per_block, w.ub, w.block_counts, w.active_idx,
+                                                        w.n_active, searched_slot);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }

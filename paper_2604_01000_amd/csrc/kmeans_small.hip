@@ -792,9 +792,11 @@ __global__ __launch_bounds__(kFinBlock) void lloyd_small_finalize_kernel(
     int32_t d_pad, int32_t d, int32_t k, int parts, const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
     const double *__restrict__ s_part, const double *__restrict__ xsq_part, int fresh_xsq,
     double *__restrict__ xsq_total, const float *__restrict__ C_prev, float *__restrict__ C_out,
-    int64_t *__restrict__ counts, double *__restrict__ objective, UpdateAcc acc) {
+    int64_t *__restrict__ counts, double *__restrict__ objective, UpdateAcc acc, const int64_t *__restrict__ list_len,
+    int64_t n) {
     __shared__ double seg_sum[kFinSegs * kFinCols];
     __shared__ unsigned long long total_cnt;
+    if (list_len) parts = list_parts(*list_len, n, parts);   // the workgroups beyond wrote no partial
     const int slices = d_pad / kFinCols;   // the partial sums have d_pad columns, the centroids d <= d_pad
     const int j = blockIdx.x / slices, col0 = kFinCols * (blockIdx.x % slices), t = threadIdx.x;
     const int m4 = t % (kFinCols / 4), seg = t / (kFinCols / 4);
@@ -976,12 +978,12 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 
 static int launch_small_finalize(const ep_problem &p, const float *C_prev, float *C_out, int64_t *counts,
                                  const KmeansWs &w, double *objective, bool fresh_xsq, const UpdateAcc &acc,
-                                 hipStream_t s, int parts = 0) {
+                                 hipStream_t s, int parts = 0, const int64_t *list_len = nullptr) {
     if (parts == 0) parts = small_blocks(p);
     const int dpad = small_padded_d(p);
     lloyd_small_finalize_kernel<<<p.k * (dpad / kFinCols), kFinBlock, 0, s>>>(
         dpad, p.d, p.k, parts, w.psum, w.pcnt, s_part_of(w), xsq_part_of(w), fresh_xsq ? 1 : 0, xsq_total_of(w), C_prev,
-        C_out, counts, objective, acc);
+        C_out, counts, objective, acc, list_len, p.n);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
@@ -993,9 +995,9 @@ int launch_small_update(const ep_problem &p, const void *X, const int32_t *label
     return launch_small_finalize(p, C_prev, C_out, counts, w, nullptr, false, acc, s);
 }
 
-int launch_small_finalize_parts(const ep_problem &p, int parts, float *C, int64_t *counts, const KmeansWs &w,
-                                const UpdateAcc &acc, hipStream_t s) {
-    return launch_small_finalize(p, C, C, counts, w, nullptr, false, acc, s, parts);
+int launch_small_finalize_parts(const ep_problem &p, int parts, const int64_t *list_len, float *C, int64_t *counts,
+                                const KmeansWs &w, const UpdateAcc &acc, hipStream_t s) {
+    return launch_small_finalize(p, C, C, counts, w, nullptr, false, acc, s, parts, list_len);
 }
 
 double *small_xsq_total(const KmeansWs &w) { return xsq_total_of(w); }
