@@ -46,6 +46,29 @@ MORE_STEPS = {"tiny": (50, 5), "arxiv_like": (20, 3), "products_like": (10, 2), 
               "papers_like": (3, 1)}
 
 
+def mfma_alone(X, dev):
+    """Rate of back-to-back bf16 matrix instructions (library's benchmark aid) on zeros and on rows of X."""
+    import torch
+
+    from paper_2604_01000_amd import embedpart as ep
+
+    nval = ep.EP_BENCH_MFMA_OPERAND_BYTES // 2
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    out = dict(unit="TFLOP/s")
+    iters = 40000
+    for name, ops in (("zero_operands", torch.zeros(nval, dtype=torch.bfloat16, device=dev)),
+                      ("rows_of_X_as_operands", X.reshape(-1)[:nval].contiguous())):
+        ep.ep_bench_mfma_bf16(ops, iters, sink)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(3):
+            ep.ep_bench_mfma_bf16(ops, iters, sink)
+        b.record()
+        torch.cuda.synchronize()
+        out[name] = ep.EP_BENCH_MFMA_FLOP_PER_ITER * iters * 3 / (a.elapsed_time(b) * 1e-3) / 1e12
+    return out
+
+
 def profile_traffic(kernel: str, workload: str):
     """(bytes per launch, file) from the counter summary of `kernel` on `workload` under profiles/."""
     path = ROOT / "profiles" / f"{kernel}_{workload}_hbm_traffic.txt"
@@ -339,6 +362,9 @@ def run_workload(name: str, steps: int, warmup: int, cpu_seconds: float, variant
         main_kernel = "large_assign_kernel"
         roofline = dict(bound="mfma", achieved=flop / (kernel_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS,
                         unit="TFLOP/s", algorithmic_flop_per_launch=flop)
+        # What the matrix pipe sustains with nothing else going on, on all-zero operands and on rows of this
+        # workload: the chip is power-limited in this instruction and the power follows the operand values.
+        roofline["matrix_instruction_alone"] = mfma_alone(X, dev)
     else:         # streaming: X read once + one int32 label per point
         nbytes = w.n * (w.d * elem + 4)
         main_kernel = "lloyd_small_kernel"

@@ -38,6 +38,22 @@ int ep_profile_count(void);
  */
 int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Benchmark aid: the rate of the bf16 matrix instruction alone, on operand values of the caller's choice.
+ * 512 workgroups of 4 waves; every lane takes 16 operand registers (16 bytes each) from `operands`
+ * (device, 65,536 bytes, 16-byte aligned: piece s of thread t at byte (256 s + t) * 16, s < 16) and the wave
+ * issues 16 * iters v_mfma_f32_32x32x16_bf16 in two accumulation chains, nothing else:
+ * 512 * 4 * 16 * iters * 32,768 flop per call.  The chip is power-limited in this instruction and the power
+ * follows the operand values, so the rate on all-zero operands (the published peak) and the rate on rows of
+ * the workload differ; a benchmark quotes both next to the rate of the assignment kernel.
+ *   iters in [1, 2^22]; sink: 4 bytes of device memory, 4-byte aligned, written only by a lane whose sums
+ *   add up to one particular value (it keeps the arithmetic alive; its content means nothing).  EP_EINVAL
+ *   for a null or misaligned pointer or iters out of range.
+ */
+#define EP_BENCH_MFMA_OPERAND_BYTES 65536
+#define EP_BENCH_MFMA_FLOP_PER_ITER (512.0 * 4 * 16 * 32768)
+int ep_bench_mfma_bf16(const void *operands, int32_t iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

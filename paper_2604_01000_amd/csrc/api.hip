@@ -266,6 +266,12 @@ int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream) {
     return launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+int ep_bench_mfma_bf16(const void *operands, int32_t iters, float *sink, void *stream) {
+    if (!operands || !sink || !aligned(operands, 16) || !aligned(sink, 4) || iters < 1 || iters > (1 << 22))
+        return EP_EINVAL;
+    return launch_bench_mfma(operands, iters, sink, static_cast<hipStream_t>(stream));
+}
+
 int kmeans_init_indices(uint64_t seed, int64_t n, int32_t k, int64_t *idx_host) {
     if (!idx_host || n < 1 || k < 1 || (int64_t)k > n) return EP_EINVAL;
     uint64_t state = seed;

@@ -169,6 +169,8 @@ size_t large_record_bytes(const ep_problem &p);
 // Rounds C to bf16 (w.cq16), leaves -||c||^2/2 in w.cnorm, then labels / min_d2 / objective.
 int launch_large_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s);
+// Benchmark aid: 512 workgroups x 4 waves x 16 * iters v_mfma_f32_32x32x16_bf16 on 65,536 bytes of operands.
+int launch_bench_mfma(const void *operands, int32_t iters, float *sink, hipStream_t s);
 
 // ---- graph kernels (graph.hip) ---------------------------------------------------
 constexpr int kSortBlocksMax = 1024;  // workgroups of one radix-sort pass

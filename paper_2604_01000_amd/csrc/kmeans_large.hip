@@ -406,7 +406,39 @@ int launch_large(const ep_problem &p, const bf16_t *X, const float *C, const Kme
     return EP_OK;
 }
 
+// ---- benchmark aid: the matrix instruction alone -------------------------------------------------
+// 16 operand registers per lane from memory, then 16 * iters dependent-chain matrix instructions in two
+// accumulation chains and nothing else: what the pipe sustains on these operand values.
+constexpr int kMfmaBenchGrid = 512;
+__global__ __launch_bounds__(kBlock, 2) void mfma_rate_kernel(const u32x4 *__restrict__ operands, int32_t iters,
+                                                               float *__restrict__ sink) {
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        a[s] = __builtin_bit_cast(bf16x8, operands[s * kBlock + threadIdx.x]);
+        b[s] = __builtin_bit_cast(bf16x8, operands[(8 + s) * kBlock + threadIdx.x]);
+    }
+    f32x16 c0 = {}, c1 = {};
+#pragma unroll 1
+    for (int32_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], b[s], c0, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], b[7 - s], c1, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) r += c0[q] + c1[q];
+    if (r == 123.456f) *sink = r;   // keeps the chains alive
+}
+
 }  // namespace
+
+int launch_bench_mfma(const void *operands, int32_t iters, float *sink, hipStream_t s) {
+    mfma_rate_kernel<<<kMfmaBenchGrid, kBlock, 0, s>>>(static_cast<const u32x4 *>(operands), iters, sink);
+    EP_LAUNCH_CHECK();
+    return EP_OK;
+}
 
 bool large_path_supported(const ep_problem &p) {
     return p.dtype == EP_BF16 && (p.d == 64 || p.d == 128) && p.k > 64 && p.ld < ((int64_t)1 << 23);

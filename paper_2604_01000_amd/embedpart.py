@@ -30,7 +30,7 @@ SYMBOLS = (
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
     "balance_workspace_bytes", "partition_balance", "graph_reorder_workspace_bytes", "graph_reorder",
     "cluster_and_balance_workspace_bytes", "cluster_and_balance",
-    "ep_profile_arm", "ep_profile_count", "ep_bench_copy",
+    "ep_profile_arm", "ep_profile_count", "ep_bench_copy", "ep_bench_mfma_bf16",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
 
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
         L.graph_reorder.argtypes = [i64, i64, vp, C.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
         L.ep_bench_copy.argtypes = [vp, vp, sz, vp]
+        L.ep_bench_mfma_bf16.argtypes = [vp, i32, vp, vp]
         for name in SYMBOLS:
             if name not in ("ep_strerror",):
                 getattr(L, name).restype = C.c_int
@@ -290,3 +291,13 @@ def ep_bench_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().ep_bench_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "ep_bench_copy")
+
+
+EP_BENCH_MFMA_OPERAND_BYTES = 65536
+EP_BENCH_MFMA_FLOP_PER_ITER = 512.0 * 4 * 16 * 32768
+
+
+def ep_bench_mfma_bf16(operands, iters, sink):
+    """16 * iters bf16 matrix instructions per wave on 65,536 bytes of operands (device): the pipe's rate alone."""
+    assert operands.numel() * operands.element_size() >= EP_BENCH_MFMA_OPERAND_BYTES and operands.is_contiguous()
+    _check(lib().ep_bench_mfma_bf16(_ptr(operands), iters, _ptr(sink), _stream()), "ep_bench_mfma_bf16")
