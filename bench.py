@@ -20,7 +20,9 @@ Every line carries
                 thread, on a contiguous slice of the same rows sized for a few seconds each.
 `traffic` is the HBM byte count of the kernel from the rocprofv3 counter summary under
 profiles/ that `traffic_source` names (null when there is none): it is read from that file,
-not measured by this run.
+not measured by this run.  `frac` is against the published peak; `frac_of_measured` is the same
+rate against what this machine sustains in this run (`measured_peak`: a plain copy of X for the
+streaming kernels, the bf16 matrix instruction alone on rows of X for the matrix-core kernel).
 """
 from __future__ import annotations
 
