@@ -41,8 +41,9 @@ __device__ __forceinline__ int list_parts(int64_t len, int64_t n, int parts) {
 // Last step of every update kernel for element `at` = j * d + column of centroid j, given this call's
 // sum `tot` and count `cnt` for it: add what earlier chunks left, then either form the mean (an empty
 // cluster keeps its previous centroid) or leave the running sum for the next chunk.  Every element is
-// owned by one thread; the running counts are only read here and are brought up to date by
-// launch_accumulate_counts afterwards, so no thread reads what another writes.
+// owned by one thread; the running counts are only read here and are brought up to date by a later
+// launch (launch_accumulate_counts, or the tail kernel of a bounded round), so no thread reads what
+// another writes.
 __device__ __forceinline__ void finish_centroid_element(const UpdateAcc &a, int64_t at, int32_t j, bool first_column,
                                                         double tot, int64_t cnt, const float *__restrict__ C_prev,
                                                         float *__restrict__ C_out, int64_t *__restrict__ counts) {

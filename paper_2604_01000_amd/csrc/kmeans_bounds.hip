@@ -51,7 +51,7 @@ constexpr float kEvalSlack = 0x1p-13f;
 // room the test leaves for the rounding of the two scores it stands in for
 constexpr float kTestSlack = 0x1p-12f;
 
-// Written by drift_kernel, read by the bounds pass of the next round.
+// Written by bounds_tail_kernel, read by the bounds pass of the next round.
 struct DriftTop {
     float first, second;   // largest and second-largest centroid movement (rounded up)
     float cmax2;           // max_j ||c_j||^2 of the new centroids (rounded up)
