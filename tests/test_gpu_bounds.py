@@ -176,6 +176,23 @@ def test_duplicate_rows_and_exact_ties():
     np.testing.assert_array_equal(fast["labels"], ref["labels"])
 
 
+@pytest.mark.parametrize("n,d,k,dtype,iters", [(9_001, 128, 64, torch.float32, 8), (12_000, 128, 8, torch.bfloat16, 7),
+                                               (3_000, 64, 5, torch.float32, 4)])
+def test_bounded_run_without_objective_history(n, d, k, dtype, iters):
+    """The objective is optional: without it the run gives the same centroids, labels and counts bit for bit."""
+    X = _mixture(n, d, 12, seed=n + 3, relu=True, dtype=dtype)
+    idx = oracle.init_indices(n, n, k)
+    with_hist = Kmeans(X, k).init(idx).run(iters, B)
+    km = Kmeans(X, k).init(idx)
+    ws = ep.workspace(ep.kmeans_run_workspace_bytes(km.p, iters, B), X.device)
+    ws.fill_(0x5A)
+    ep.kmeans_run(km.p, X, iters, km.C, km.labels, km.counts, None, B, ws)
+    km._sync_and_check()
+    np.testing.assert_array_equal(km.labels.cpu().numpy(), with_hist["labels"])
+    np.testing.assert_array_equal(km.counts.cpu().numpy(), with_hist["counts"])
+    np.testing.assert_array_equal(km.C.cpu().numpy(), with_hist["C"])
+
+
 def test_final_reassign_with_bounds():
     X = _mixture(8_000, 128, 10, seed=4, relu=True)
     idx = oracle.init_indices(2, 8_000, 12)
