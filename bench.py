@@ -247,7 +247,8 @@ def run_workload(name: str, steps: int, warmup: int, cpu_seconds: float, variant
     # ---- the same Lloyd rounds with distance bounds and kept sums (EP_RUN_BOUNDS): points whose bounds show that
     # ---- their label cannot change are not read.  Timed beside the step (kmeans_init + kmeans_run only, with and
     # ---- without the flag); `searched` is the number of rows read in each round, bytes_read_per_round what that
-    # ---- amounts to (a searched row + its label, plus 12 bytes of bounds and label per row in a bounded round)
+    # ---- amounts to (a searched row + its label, plus 12 bytes of bounds and label per row in a bounded round;
+    # ---- the third round, which takes the bounds, writes 8 bytes per row more than a plain one)
     bounded = None
     if variants:
         flags = ep.EP_RUN_BOUNDS

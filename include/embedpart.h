@@ -188,8 +188,9 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
  * point keeps an upper bound on the distance to its own centroid and a lower bound on the distance
  * to all others; after an update the bounds are moved by how far the centroids moved, and a point
  * whose bounds still separate is not read at all in the next round.  The per-cluster sums are kept
- * in fp64 between rounds and only rows that change label are moved between them.  The first two
- * rounds are ordinary ones, the third searches every point to take the bounds.
+ * in fp64 between rounds and only rows that change label are moved between them.  The first three
+ * rounds are ordinary ones; the third also takes every point's bounds (from its best and second-best
+ * score) and keeps the sums.
  *   Results: a searched point goes through the score arithmetic of the plain rounds and the bounds
  *   leave room for its rounding, so from equal centroids a round gives the labels of the plain round
  *   bit for bit.  The centroids themselves agree with the plain run's to the order of the fp64
@@ -197,7 +198,7 @@ int kmeans_run(const ep_problem *p, const void *X, int32_t iters, float *C,
  *   the other way in a later round; every round still is an exact Lloyd round of its own centroids.
  *   A run of T1 rounds followed by one of T2 is therefore not bit-equal to T1 + T2 rounds in one run,
  *   as it is without the flag; the run itself is bit-reproducible.
- *   Shapes: k in [2, 64], d = 64 or 128, fp32 or bfloat16 rows, iters >= 3; for any other shape the
+ *   Shapes: k in [2, 64], d = 64 or 128, fp32, fp16 or bfloat16 rows, iters >= 4; for any other shape the
  *   flag is accepted and the rounds run in full.
  *   Workspace: kmeans_run_workspace_bytes(p, iters, flags), which grows by 12 bytes per row.
  * kmeans_run_workspace_bytes with flags without EP_RUN_BOUNDS equals kmeans_workspace_bytes.

@@ -95,7 +95,8 @@ int check_graph(int64_t n, int64_t nnz, const void *rowptr, const int32_t *colid
 }
 
 // Full rounds before the first bounded one: while the centroids still move far, no bound survives a round.
-constexpr int32_t kBoundsWarmRounds = 2;
+// The last of them also takes the first bounds.
+constexpr int32_t kBoundsWarmRounds = 3;
 
 bool bounds_in_use(const ep_problem &p, int32_t iters, int flags) {
     return (flags & EP_RUN_BOUNDS) && bounds_path_supported(p) && iters > kBoundsWarmRounds;
@@ -111,8 +112,8 @@ BoundsWs bounds_ws_of(const ep_problem &p, int32_t iters, void *ws) {
     return carve_bounds_ws(p, iters, static_cast<char *>(ws) + align_up(carve_kmeans_ws(p, nullptr).bytes, 256));
 }
 
-// `iters` rounds with EP_RUN_BOUNDS: kBoundsWarmRounds full rounds (the last one leaves its sums), one round
-// that searches every point to take the first bounds, then rounds that search only what the bounds let through.
+// `iters` rounds with EP_RUN_BOUNDS: kBoundsWarmRounds full rounds, the last of which keeps its sums in fp64
+// and leaves every point's bounds, then rounds that search only what the bounds let through.
 int run_rounds_bounded(const ep_problem &p, const void *X, int32_t iters, float *C, int32_t *labels, int64_t *counts,
                        double *objective_hist, const KmeansWs &w, const BoundsWs &b, hipStream_t s) {
     int rc = EP_OK;
@@ -121,24 +122,22 @@ int run_rounds_bounded(const ep_problem &p, const void *X, int32_t iters, float 
     for (int32_t t = 0; t < kBoundsWarmRounds; ++t) {
         const bool last_full = t == kBoundsWarmRounds - 1;
         double *obj = objective_hist ? objective_hist + t : nullptr;   // round 1 also forms sum ||x||^2, kept for later
-        if ((rc = launch_small_round(p, X, C, w, labels, counts, obj, t == 0, s, last_full ? keep : whole_update())) != EP_OK)
+        if (last_full && (rc = launch_keep_centroids(p, C, b, s)) != EP_OK) return rc;   // what the bounds refer to
+        if ((rc = launch_small_round(p, X, C, w, labels, counts, obj, t == 0, s, last_full ? keep : whole_update(),
+                                     last_full ? b.ub : nullptr, last_full ? b.lb : nullptr)) != EP_OK)
             return rc;
-        if (last_full && (rc = launch_accumulate_counts(p.k, keep, s)) != EP_OK) return rc;
+        if (last_full) {   // the kept counts are this round's; then the centroids' movement for the first bounds pass
+            if ((rc = launch_accumulate_counts(p.k, keep, s)) != EP_OK) return rc;
+            if ((rc = launch_bounds_tail(p, C, w, b, false, nullptr, nullptr, true, s)) != EP_OK) return rc;
+        }
         if ((rc = launch_record_searched(p.n, b.searched + t, s)) != EP_OK) return rc;
     }
     for (int32_t t = kBoundsWarmRounds; t < iters; ++t) {
-        const bool all_points = t == kBoundsWarmRounds;
-        if (all_points) {   // later rounds find the centroids of their assignment kept by the round before
-            if ((rc = launch_record_searched(p.n, b.searched + t, s)) != EP_OK) return rc;
-            if ((rc = launch_keep_centroids(p, C, b, s)) != EP_OK) return rc;
-        } else if ((rc = launch_bounds_pass(p, labels, b, b.searched + t, s)) != EP_OK) {
+        if ((rc = launch_bounds_pass(p, labels, b, b.searched + t, s)) != EP_OK) return rc;
+        if ((rc = launch_bounds_round(p, X, C, w, b, labels, s)) != EP_OK) return rc;
+        if ((rc = launch_small_finalize_parts(p, bounds_round_parts(p), b.n_active, C, counts, w, add, s)) != EP_OK)
             return rc;
-        }
-        if ((rc = launch_bounds_round(p, X, C, w, b, all_points, labels, s)) != EP_OK) return rc;
-        if ((rc = launch_small_finalize_parts(p, bounds_round_parts(p), all_points ? nullptr : b.n_active, C, counts, w,
-                                              add, s)) != EP_OK)
-            return rc;
-        if ((rc = launch_bounds_tail(p, C, w, b, small_xsq_total(w), objective_hist ? objective_hist + t : nullptr,
+        if ((rc = launch_bounds_tail(p, C, w, b, true, small_xsq_total(w), objective_hist ? objective_hist + t : nullptr,
                                      t + 1 < iters, s)) != EP_OK)
             return rc;
     }

@@ -121,9 +121,11 @@ int launch_small_assign_sliced(const ep_problem &p, const void *X, const float *
 // round's objective.
 // first_round: the data-only term of the objective (sum ||x||^2) is computed and kept in the
 // workspace; later rounds of the same kmeans_run reuse it.
+// ub, lb (both or neither; d = 64 or 128 exactly, not the first round): the round also leaves every point's
+// distance bounds against the centroids it was assigned with, which is what the bounded rounds start from.
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
                        int64_t *counts, double *objective, bool first_round, hipStream_t s,
-                       const UpdateAcc &acc = whole_update());
+                       const UpdateAcc &acc = whole_update(), float *ub = nullptr, float *lb = nullptr);
 // Second pass over `parts` per-workgroup partials that another kernel left in w.psum / w.pcnt (the bounded
 // rounds): C <- means in place, no objective.  With list_len (device), only the first
 // list_parts(*list_len, p.n, parts) partials were written and are read.
@@ -151,18 +153,18 @@ int bounds_round_parts(const ep_problem &p);
 int launch_record_searched(int64_t value, int64_t *slot, hipStream_t s);
 int launch_copy_searched(int32_t iters, const BoundsWs &w, int64_t *out, hipStream_t s);
 int launch_keep_centroids(const ep_problem &p, const float *C, const BoundsWs &w, hipStream_t s);
-// After the means of a bounded round: the kept counts take the round's changes, the round's objective is formed
-// from the kept sums (objective may be null), and with want_drift the centroid movements are left for the next
-// round's bounds pass and w.C_old becomes C_new.
+// After the means of a round whose assignment used w.C_old: with add_counts the kept counts take the round's
+// changes, the round's objective is formed from the kept sums (objective may be null), and with want_drift the
+// centroid movements are left for the next round's bounds pass and w.C_old becomes C_new.
 int launch_bounds_tail(const ep_problem &p, const float *C_new, const KmeansWs &kw, const BoundsWs &w,
-                       const double *xsq_total, double *objective, bool want_drift, hipStream_t s);
+                       bool add_counts, const double *xsq_total, double *objective, bool want_drift, hipStream_t s);
 // Applies the last drift to every point's bounds and lists the rows whose bounds no longer separate.
 int launch_bounds_pass(const ep_problem &p, const int32_t *labels, const BoundsWs &w, int64_t *searched_slot,
                        hipStream_t s);
-// Searches the listed rows (all rows with all_points), renews their bounds, updates labels in place and
-// leaves per-workgroup partial sums of the rows that changed label in kw.psum / kw.pcnt.
+// Searches the listed rows, renews their bounds, updates labels in place and leaves per-workgroup partial sums
+// of the rows that changed label in kw.psum / kw.pcnt.
 int launch_bounds_round(const ep_problem &p, const void *X, const float *C, const KmeansWs &kw, const BoundsWs &w,
-                        bool all_points, int32_t *labels, hipStream_t s);
+                        int32_t *labels, hipStream_t s);
 
 // ---- K-Means, k > 64, bf16, d in {64,128}: bf16 matrix-core assignment (kmeans_large.hip) -------
 bool large_path_supported(const ep_problem &p);

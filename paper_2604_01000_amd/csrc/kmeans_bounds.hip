@@ -16,6 +16,9 @@
 // down, and the test leaves room for the rounding of the scores themselves, so a skipped point is one
 // whose scores, had they been computed, would have named the same centroid.
 //
+// The first bounds come from the last full round: the fused kernel of kmeans_small.hip, built with its bounds
+// option, also tracks every point's second-best score and stores u and l next to the label.
+//
 // Kernels of one bounded round:
 //   bounds_update_kernel    streams (label, u, l), 12 bytes per point, applies the drift, marks and counts
 //                           the points that must be searched (per workgroup)
@@ -43,11 +46,6 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kSub = 16;              // points per sub-tile of the search
 constexpr int kBoundsBlocksMax = 2048;   // workgroups of the bounds pass (each a contiguous chunk of rows)
 
-constexpr float kUp = 1.0f + 0x1p-21f;      // pushes a non-negative value up past any fp32 rounding of one operation
-constexpr float kDown = 1.0f - 0x1p-21f;
-// |d^2 as computed from a score - true d^2| <= kEvalSlack * (||x||^2 + max ||c||^2): 768 fp32 additions of a
-// six-term split product bound the relative error of a score by 768 * 2^-24 < 2^-14 of |x| |c|; this is twice that.
-constexpr float kEvalSlack = 0x1p-13f;
 // room the test leaves for the rounding of the two scores it stands in for
 constexpr float kTestSlack = 0x1p-12f;
 
@@ -160,7 +158,7 @@ __device__ __forceinline__ double centroid_used(float c) {
 }
 
 // What follows the means of a bounded round, in one workgroup:
-//   the kept counts take the round's changes (cnt += chunk_cnt);
+//   the kept counts take the round's changes (cnt += chunk_cnt; not after a full round, whose counts are whole);
 //   objective (if asked for) of the round whose assignment used C_old (as the distances use it) and left the sums
 //   and counts: sum ||x||^2 - 2 sum_j c_j . s_j + sum_j n_j ||c_j||^2, in fp64 and a fixed order;
 //   drift (if another round follows): delta_j = ||c_new_j - c_old_j|| of the centroids as the distances use them,
@@ -170,7 +168,7 @@ template <bool BF16>
 __global__ __launch_bounds__(kBlock) void bounds_tail_kernel(int32_t k, int32_t d, const float *__restrict__ C_new,
                                                               float *__restrict__ C_old,
                                                               const double *__restrict__ sum, int64_t *__restrict__ cnt,
-                                                              const int64_t *__restrict__ chunk_cnt,
+                                                              const int64_t *__restrict__ chunk_cnt, int add_counts,
                                                               const double *__restrict__ xsq_total,
                                                               double *__restrict__ objective, int want_drift,
                                                               float *__restrict__ delta, DriftTop *__restrict__ top) {
@@ -179,8 +177,11 @@ __global__ __launch_bounds__(kBlock) void bounds_tail_kernel(int32_t k, int32_t 
     __shared__ float delta_lds[64], norm_lds[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if ((int)threadIdx.x < k) {
-        const int64_t all = cnt[threadIdx.x] + chunk_cnt[threadIdx.x];
-        cnt[threadIdx.x] = all;
+        int64_t all = cnt[threadIdx.x];
+        if (add_counts) {
+            all += chunk_cnt[threadIdx.x];
+            cnt[threadIdx.x] = all;
+        }
         cnt_lds[threadIdx.x] = all;
     }
     __syncthreads();
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
 
     // a workgroup that gets no row of the list leaves no partial (the second pass knows which ones do)
     static_assert(kSub * kWaves == 64, "list_parts counts workgroups of 64 rows per step");
-    if (n_active_ptr && (int)blockIdx.x >= list_parts(*n_active_ptr, n, (int)gridDim.x)) return;
+    if ((int)blockIdx.x >= list_parts(*n_active_ptr, n, (int)gridDim.x)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, c = lane & 15;
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     __syncthreads();
 
     // this wave's share of the sub-tiles of the list (a fixed function of the list's length and the grid)
-    const int64_t n_act = n_active_ptr ? min(max(*n_active_ptr, (int64_t)0), n) : n;
+    const int64_t n_act = min(max(*n_active_ptr, (int64_t)0), n);
     const int64_t total_sub = (n_act + kSub - 1) / kSub;
     const int64_t waves = (int64_t)gridDim.x * kWaves, wave_id = (int64_t)blockIdx.x * kWaves + wave;
     const int64_t per = total_sub / waves, extra = total_sub % waves;
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     auto fetch_row = [&](int64_t st) -> int64_t {
         const int64_t pos = st * kSub + c;
         if (st >= last || pos >= n_act) return -1;
-        const int64_t row = active_idx ? (int64_t)active_idx[pos] : pos;
+        const int64_t row = (int64_t)active_idx[pos];
         return row >= 0 && row < n ? row : -1;
     };
     auto load_x = [&](int64_t row, f32x4(&dst)[NX]) {
@@ -464,11 +465,10 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
         const int32_t own_old = __shfl(old_c, src, 64);
         const float own_xn = __shfl(xpart, src, 64);
         if (c < 4 && 4 * g + c < rows_here && own_row >= 0) {
-            const float slack = kEvalSlack * (own_xn + cmax2);
-            const float d2_best = fmaxf(own_xn - 2.f * s_best, 0.f) + slack;
-            const float d2_second = fmaxf(own_xn - 2.f * s_second - slack, 0.f);   // +inf when there is no other centroid
-            ub[own_row] = __fsqrt_rn(d2_best) * kUp;
-            lb[own_row] = __fsqrt_rn(d2_second) * kDown;
+            float u, l;
+            fresh_bounds(own_xn, s_best, s_second, cmax2, u, l);
+            ub[own_row] = u;
+            lb[own_row] = l;
             if (my_l != own_old) labels[own_row] = my_l;
         }
 
@@ -576,14 +576,16 @@ int launch_keep_centroids(const ep_problem &p, const float *C, const BoundsWs &w
 }
 
 int launch_bounds_tail(const ep_problem &p, const float *C_new, const KmeansWs &kw, const BoundsWs &w,
-                       const double *xsq_total, double *objective, bool want_drift, hipStream_t s) {
+                       bool add_counts, const double *xsq_total, double *objective, bool want_drift, hipStream_t s) {
     DriftTop *top = reinterpret_cast<DriftTop *>(w.top);
     if (p.dtype == EP_BF16)
         bounds_tail_kernel<true><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, kw.acc_sum, kw.acc_cnt, kw.chunk_cnt,
-                                                      xsq_total, objective, want_drift ? 1 : 0, w.delta, top);
+                                                      add_counts ? 1 : 0, xsq_total, objective, want_drift ? 1 : 0,
+                                                      w.delta, top);
     else
         bounds_tail_kernel<false><<<1, kBlock, 0, s>>>(p.k, p.d, C_new, w.C_old, kw.acc_sum, kw.acc_cnt, kw.chunk_cnt,
-                                                       xsq_total, objective, want_drift ? 1 : 0, w.delta, top);
+                                                       add_counts ? 1 : 0, xsq_total, objective, want_drift ? 1 : 0,
+                                                       w.delta, top);
     EP_LAUNCH_CHECK();
     return EP_OK;
 }
@@ -604,11 +606,11 @@ int launch_bounds_pass(const ep_problem &p, const int32_t *labels, const BoundsW
 int bounds_round_parts(const ep_problem &p) { return bounds_grid(p); }
 
 int launch_bounds_round(const ep_problem &p, const void *X, const float *C, const KmeansWs &kw, const BoundsWs &w,
-                        bool all_points, int32_t *labels, hipStream_t s) {
+                        int32_t *labels, hipStream_t s) {
     const int grid = bounds_grid(p);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
-    const int32_t *idx = all_points ? nullptr : w.active_idx;
-    const int64_t *n_act = all_points ? nullptr : w.n_active;
+    const int32_t *idx = w.active_idx;
+    const int64_t *n_act = w.n_active;
     ProfScope prof(EP_PROF_LLOYD_MAIN, s);
 #define EP_BOUNDS_LAUNCH(D_, KT_, XT_)                                                                          \
     do {                                                                                                        \

@@ -75,14 +75,19 @@ struct SmallLds {
 // PAD: the rows have d < D columns (d a multiple of 4, passed at run time); columns d .. D - 1 are
 // read as zeros (their loads are sent out of the buffer's range), which changes neither scores nor
 // sums, and only the first d columns of the centroids exist in memory.
-template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT, bool PAD>
+// BND (fused rounds only): also leave, per point, the distance bounds that the bounded rounds start from
+// (upper bound on the distance to the own centroid from the best score, lower bound on the distance to all
+// others from the second-best score; see kmeans_bounds.hip) in ub / lb.
+template <int D, int KT, int MODE, bool XSQ, bool STREAM, typename XT, bool PAD, bool BND = false>
 __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_small_kernel(
     int64_t n, int64_t ld, int32_t d, int32_t k, int64_t subtiles_per_wave, int64_t waves_with_one_more,
     const XT *__restrict__ X,
     const float *__restrict__ C, int32_t *__restrict__ labels_out,
     const int32_t *__restrict__ labels_in, float *__restrict__ min_d2, float *__restrict__ psum,
     int32_t *__restrict__ pcnt, double *__restrict__ s_part, double *__restrict__ xsq_part,
-    int32_t label_base, float *__restrict__ best_score) {
+    int32_t label_base, float *__restrict__ best_score, float *__restrict__ ub = nullptr,
+    float *__restrict__ lb = nullptr) {
+    static_assert(!BND || MODE == kFused, "bounds are taken in a fused round");
     constexpr int NJ = D / 16;       // 16-byte pieces per lane in the transposed layout; also column tiles
     constexpr int NH = D / 64;       // 16-byte pieces per lane and point in the load layout
     constexpr int STRIDE = D + 4;    // padded LDS row: consecutive rows start 4 banks apart
@@ -132,6 +137,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
     u32x4 ch[kSplit ? KT : 1][kSplit ? KS : 1], cm[kThreeTerms ? KT : 1][kThreeTerms ? KS : 1],
         cl[kThreeTerms ? KT : 1][kThreeTerms ? KS : 1];
     float hn[KT];   // -||c||^2 / 2 of centroid 16*mt + c: the value the score accumulators start from
+    float cmax2 = 0.f;   // BND: max ||c||^2 over the centroids (rounded up), the same in every lane
     // Called after the first sub-tile's loads have been issued, so that the two latencies overlap.
     auto load_centroids = [&]() {
         if (MODE != kUpdateOnly) {
@@ -168,7 +174,9 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
                 nacc += __shfl_xor(nacc, 16, 64);
                 nacc += __shfl_xor(nacc, 32, 64);
                 hn[mt] = real ? (float)(-0.5 * nacc) : -3.0e38f;
+                if (BND && real) cmax2 = fmaxf(cmax2, (float)nacc * kUp);
             }
+            if constexpr (BND) cmax2 = key_float(row16_max(float_key(cmax2)));
             if constexpr (kSplit) {
                 // The 3 * KT * KS operands are only ever read by matrix instructions: pin them to the
                 // accumulation registers, which those instructions read directly.  Left to itself the
@@ -327,6 +335,25 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
             }
     };
 
+    // BND: bounds of the 16 points of a sub-tile from the row maxima of their best (bk) and second-best (sk)
+    // scores and this lane's quarter of ||x_c||^2; lane c < 4 of every 16-lane row owns point 4 g + c.
+    auto store_bounds = [&](int bk0, int bk1, int bk2, int bk3, int sk0, int sk1, int sk2, int sk3, float xpart,
+                            int64_t row0, int rows) __attribute__((always_inline)) {
+        float xn = xpart;
+        xn += __shfl_xor(xn, 16, 64);
+        xn += __shfl_xor(xn, 32, 64);   // ||x||^2 of point c, in all four lanes that hold a quarter of it
+        const int sel = c & 3;
+        const float s_best = key_float(sel == 0 ? bk0 : sel == 1 ? bk1 : sel == 2 ? bk2 : bk3);
+        const float s_second = key_float(sel == 0 ? sk0 : sel == 1 ? sk1 : sel == 2 ? sk2 : sk3);
+        const float own_xn = __shfl(xn, 4 * g + sel, 64);
+        float u, l;
+        fresh_bounds(own_xn, s_best, s_second, cmax2, u, l);
+        if (c < 4 && 4 * g + c < rows) {
+            ub[row0 + 4 * g + c] = u;
+            lb[row0 + 4 * g + c] = l;
+        }
+    };
+
     auto process = [&](int64_t st, const f32x4(&x)[NX]) {
         const int64_t row0 = st * kSub;
         const int rows_here = (int)min((int64_t)kSub, n - row0);  // uniform
@@ -384,7 +411,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
             }
 
             float xpart = 0.f;
-            if (XSQ || min_d2) {
+            if (XSQ || BND || min_d2) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     xpart += x[j][0] * x[j][0] + x[j][1] * x[j][1] + x[j][2] * x[j][2] + x[j][3] * x[j][3];
@@ -393,21 +420,30 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
             // argmax over centroids: inside the lane over tiles (ascending index, strict >), then a
             // 16-lane butterfly on an order-preserving integer key: the maximum first, then the
             // lowest index among the lanes that hold it.
-            int bkey[4];
+            int bkey[4], skey[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float sc = acc0[0][v];
                 int idx = c;
+                float m1 = acc0[0][v], m2 = -3.4e38f;   // BND: the lane's largest and second-largest (equal values count twice)
 #pragma unroll
                 for (int mt = 1; mt < KT; ++mt) {
                     const float s2 = acc0[mt][v];
                     if (s2 > sc) { sc = s2; idx = 16 * mt + c; }
+                    if constexpr (BND) {
+                        if (s2 > m1) { m2 = m1; m1 = s2; }
+                        else if (s2 > m2) { m2 = s2; }
+                    }
                 }
                 const int key = float_key(sc);
                 bkey[v] = row16_max(key);
                 const int win = row16_min(key == bkey[v] ? idx : 0x7fffffff);
                 lab[v] = (4 * g + v < rows_here) ? win : -1;
+                // every lane offers its best, the winner's lane what is left without the winning entry
+                if constexpr (BND) skey[v] = row16_max(float_key(c == (win & 15) ? m2 : m1));
             }
+            if constexpr (BND)
+                store_bounds(bkey[0], bkey[1], bkey[2], bkey[3], skey[0], skey[1], skey[2], skey[3], xpart, row0, rows_here);
 
             // lane c < 4 of every group owns point 4g + c for the stores and the objective
             const int sel = c & 3;
@@ -501,7 +537,9 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         }
     };
 
-    if constexpr (kLdsSums && MODE == kFused && KT >= 4) {
+    // (with the bounds option at d = 128 the pipeline's three register sets no longer fit: that one round runs the
+    // plain loop)
+    if constexpr (kLdsSums && MODE == kFused && KT >= 4 && !(BND && D == 128)) {
         // k > 32, fused round.  With four centroid tiles the split centroid operand (192 registers) and
         // the sum tables (137 KB) leave room for one wave per SIMD only, so nothing else hides a wave's
         // latencies.  (Two tiles fit two waves per SIMD and run the plain loop below: measured
@@ -524,7 +562,8 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
         float *dummy = wsums + 16 * KT * STRIDE + 4 * g;   // the extra row idle lanes add to; never read
         f32x4 scp[KT];         // previous sub-tile: scores
         int prev_rows = 0;     // rows of the previous sub-tile
-        int bkeyp[4];
+        int bkeyp[4], skeyp[4];
+        int64_t prev_st = 0;   // the previous sub-tile
         int32_t labp[4];
         int32_t lab_c = -1;
         int rank = -1;
@@ -536,13 +575,21 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
                 const int v = b;
                 float sc = scp[0][v];
                 int idx = c;
+                float m1 = scp[0][v], m2 = -3.4e38f;   // BND: as in process()
 #pragma unroll
-                for (int mt = 1; mt < KT; ++mt)
-                    if (scp[mt][v] > sc) { sc = scp[mt][v]; idx = 16 * mt + c; }
+                for (int mt = 1; mt < KT; ++mt) {
+                    const float s2 = scp[mt][v];
+                    if (s2 > sc) { sc = s2; idx = 16 * mt + c; }
+                    if constexpr (BND) {
+                        if (s2 > m1) { m2 = m1; m1 = s2; }
+                        else if (s2 > m2) { m2 = s2; }
+                    }
+                }
                 const int key = float_key(sc);
                 bkeyp[v] = row16_max(key);
                 const int win = row16_min(key == bkeyp[v] ? idx : 0x7fffffff);
                 labp[v] = (4 * g + v < prev_rows) ? win : -1;
+                if constexpr (BND) skeyp[v] = row16_max(float_key(c == (win & 15) ? m2 : m1));
             } else if (b == 4) {   // labels to the LDS buffer, objective terms
                 // every lane of a 16-lane row holds the row's four results: lane c == 0 stores them,
                 // and every lane keeps the running sum of best scores (only lane c == 0's is used)
@@ -550,12 +597,15 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
                 *dst = i32x4{labp[0], labp[1], labp[2], labp[3]};
 #pragma unroll
                 for (int v = 0; v < 4; ++v) obj_s += (double)(4 * g + v < prev_rows ? key_float(bkeyp[v]) : 0.f);
-                if (XSQ) {
+                if (XSQ || BND) {
                     float xpart = 0.f;
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
                         xpart += xp[j][0] * xp[j][0] + xp[j][1] * xp[j][1] + xp[j][2] * xp[j][2] + xp[j][3] * xp[j][3];
-                    obj_x += (double)(c < prev_rows ? xpart : 0.f);
+                    if (XSQ) obj_x += (double)(c < prev_rows ? xpart : 0.f);
+                    if constexpr (BND)
+                        store_bounds(bkeyp[0], bkeyp[1], bkeyp[2], bkeyp[3], skeyp[0], skeyp[1], skeyp[2], skeyp[3], xpart,
+                                     prev_st * kSub, prev_rows);
                 }
                 wave_lds_fence();
             } else if (b == 5) {   // label of this lane's point; first half of its rank among earlier equal labels
@@ -619,6 +669,7 @@ __global__ __launch_bounds__(kBlock, (KT <= 2 && D <= 128) ? 2 : 1) void lloyd_s
             __builtin_amdgcn_sched_barrier(0);
             if (DEFERRED) finish_prev(xp);
             prev_rows = (int)min((int64_t)kSub, n - st * kSub);
+            prev_st = st;
         };
         auto drain = [&](const f32x4(&xp)[NX]) {   // the last sub-tile's deferred work, no matrix work to hide in
 #pragma unroll
@@ -868,10 +919,11 @@ double *xsq_total_of(const KmeansWs &w) { return w.obj_part + 2 * kSmallMaxBlock
 
 // label_base / best_score: assignment over one 64-centroid slice of a larger k (see
 // launch_small_assign_sliced); 0 / nullptr otherwise.
-template <int MODE, bool XSQ>
+// BND: the fused round also leaves the distance bounds of every point in ub / lb (exact d = 64 or 128 only).
+template <int MODE, bool XSQ, bool BND = false>
 int launch_mode(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels_out,
                 const int32_t *labels_in, float *min_d2, bool want_obj, hipStream_t s, int32_t label_base = 0,
-                float *best_score = nullptr) {
+                float *best_score = nullptr, float *ub = nullptr, float *lb = nullptr) {
     const Geometry geo = geometry(p.n);
     const int kt = p.k <= 16 ? 1 : p.k <= 32 ? 2 : 4;
     const bool stream_x = (double)p.n * (double)p.ld * (double)elem_bytes(p.dtype) > kLastLevelCacheBytes;
@@ -879,10 +931,12 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
     ProfScope prof(MODE == kUpdateOnly ? EP_PROF_UPDATE_SUMS : EP_PROF_LLOYD_MAIN, s, true);
 #define EP_SMALL_LAUNCH_P(D_, KT_, XT_, PAD_)                                                                 \
     do {                                                                                                      \
+        if constexpr (BND && (PAD_ || D_ == 256)) return EP_EUNSUPPORTED;   /* not instantiated */           \
+        else {                                                                                                \
         constexpr int lds_bytes = SmallLds<D_, KT_>::kBytes;                                                  \
         const XT_ *Xt = static_cast<const XT_ *>(X);                                                          \
-        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_, PAD_>                        \
-                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_, PAD_>;                      \
+        auto kern = stream_x ? lloyd_small_kernel<D_, KT_, MODE, XSQ, true, XT_, PAD_, BND>                   \
+                             : lloyd_small_kernel<D_, KT_, MODE, XSQ, false, XT_, PAD_, BND>;                 \
         if (lds_bytes > 64 * 1024) {   /* once per kernel variant and device */                              \
             static std::atomic<uint64_t> attr_set[2];   /* one bit per device, per STREAM variant */          \
             int dev_ = 0;                                                                                     \
@@ -898,12 +952,13 @@ int launch_mode(const ep_problem &p, const void *X, const float *C, const Kmeans
             hipExtLaunchKernelGGL(kern, dim3(geo.blocks), dim3(kBlock), lds_bytes, s, prof.start_, prof.stop_, 0,  \
                                   p.n, p.ld, p.d, p.k, geo.subtiles_per_wave, geo.waves_with_one_more, Xt, C,  \
                                   labels_out, labels_in, min_d2,                                              \
-                                  w.psum, w.pcnt, sp, xsq_part_of(w), label_base, best_score);                \
+                                  w.psum, w.pcnt, sp, xsq_part_of(w), label_base, best_score, ub, lb);        \
         else                                                                                                  \
             kern<<<geo.blocks, kBlock, lds_bytes, s>>>(p.n, p.ld, p.d, p.k, geo.subtiles_per_wave,            \
                                                        geo.waves_with_one_more, Xt, C, labels_out, labels_in, \
                                                        min_d2, w.psum, w.pcnt, sp, xsq_part_of(w),            \
-                                                       label_base, best_score);                               \
+                                                       label_base, best_score, ub, lb);                       \
+        }                                                                                                     \
     } while (0)
 #define EP_SMALL_LAUNCH_T(D_, KT_, XT_)                                                                       \
     do {                                                                                                      \
@@ -1003,9 +1058,13 @@ int launch_small_finalize_parts(const ep_problem &p, int parts, const int64_t *l
 double *small_xsq_total(const KmeansWs &w) { return xsq_total_of(w); }
 
 int launch_small_round(const ep_problem &p, const void *X, float *C, const KmeansWs &w, int32_t *labels,
-                       int64_t *counts, double *objective, bool first_round, hipStream_t s, const UpdateAcc &acc) {
+                       int64_t *counts, double *objective, bool first_round, hipStream_t s, const UpdateAcc &acc,
+                       float *ub, float *lb) {
     const bool fresh = objective && first_round;  // sum ||x||^2 is computed in the first round and kept
-    int rc = fresh ? launch_mode<kFused, true>(p, X, C, w, labels, nullptr, nullptr, true, s)
+    if (ub && (fresh || !lb)) return EP_EINVAL;   // bounds are taken in a later round
+    int rc = ub ? launch_mode<kFused, false, true>(p, X, C, w, labels, nullptr, nullptr, objective != nullptr, s, 0,
+                                                   nullptr, ub, lb)
+           : fresh ? launch_mode<kFused, true>(p, X, C, w, labels, nullptr, nullptr, true, s)
                    : launch_mode<kFused, false>(p, X, C, w, labels, nullptr, nullptr, objective != nullptr, s);
     if (rc != EP_OK) return rc;
     return launch_small_finalize(p, C, C, counts, w, objective, fresh, acc, s);

@@ -74,6 +74,24 @@ __device__ __forceinline__ f32x4 mfma_bf16_k32(const u32x4 &a, const u32x4 &b, c
                                                    acc, 0, 0, 0);
 }
 
+// Distance bounds of the bounded rounds, kept on the safe side of fp32 rounding: an upper bound is rounded up, a
+// lower bound down.
+constexpr float kUp = 1.0f + 0x1p-21f;      // pushes a non-negative value up past any fp32 rounding of one operation
+constexpr float kDown = 1.0f - 0x1p-21f;
+// |d^2 as computed from a score - true d^2| <= kEvalSlack * (||x||^2 + max ||c||^2): 768 fp32 additions of a
+// six-term split product bound the relative error of a score by 768 * 2^-24 < 2^-14 of |x| |c|; this is twice that.
+constexpr float kEvalSlack = 0x1p-13f;
+// Fresh bounds of a point from its best and second-best score (score = x.c - ||c||^2 / 2, so
+// d^2 = ||x||^2 - 2 score): u >= the distance to the own centroid, l <= the distance to every other one
+// (+infinity when there is no other centroid: the padding score is -3e38).
+__device__ __forceinline__ void fresh_bounds(float xn, float s_best, float s_second, float cmax2, float &u, float &l) {
+    const float slack = kEvalSlack * (xn + cmax2);
+    const float d2_best = fmaxf(xn - 2.f * s_best, 0.f) + slack;
+    const float d2_second = fmaxf(xn - 2.f * s_second - slack, 0.f);
+    u = __fsqrt_rn(d2_best) * kUp;
+    l = __fsqrt_rn(d2_second) * kDown;
+}
+
 // sums[label of point c][:] += x_c for the 16 points of a sub-tile, in LDS, without atomics and in
 // a fixed order.  Lane (g, c) holds a quarter of point c's row (columns 16 j + 4 g .. + 3).  Points
 // of the sub-tile that share a label must not update the same row at once, so every point gets

@@ -202,7 +202,7 @@ def test_final_reassign_with_bounds():
 
 def test_flag_without_effect_and_workspace_rules():
     X = _mixture(3_000, 128, 8, seed=6, relu=True)
-    for k, iters in ((100, 5), (8, 2)):                        # a shape without bounded kernels; too few rounds
+    for k, iters in ((100, 5), (8, 2), (8, 3)):                # a shape without bounded kernels; too few rounds
         idx = oracle.init_indices(3, 3_000, k)
         plain, fast = Kmeans(X, k).init(idx).run(iters), Kmeans(X, k).init(idx).run(iters, B)
         for key in ("C", "labels", "counts"):
