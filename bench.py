@@ -72,6 +72,35 @@ def mfma_alone(X, dev):
     return out
 
 
+def probe_fold() -> dict:
+    """The library's fold probe (include/embedpart_bench.h) at the shapes of the two small workloads: what a Lloyd
+    round's second pass costs as a launch of its own and as work of the last workgroup to arrive."""
+    import torch
+
+    from paper_2604_01000_amd import embedpart as ep
+
+    dev, reps, res = "cuda:0", 2000, []
+    for name, parts, elems in (("tiny", 313, 4 * 64), ("arxiv_like", 512, 8 * 128)):
+        partials = torch.empty(parts * elems, dtype=torch.float32, device=dev)
+        out = torch.empty(elems, dtype=torch.float32, device=dev)
+        ticket = torch.zeros(1, dtype=torch.int32, device=dev)
+        us = {}
+        for mode, key in ((0, "producer_alone_us"), (2, "producer_and_second_launch_us"), (1, "producer_with_fold_us")):
+            for _ in range(20):
+                ep.ep_bench_fold(partials, parts, elems, mode, ticket, out)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                ep.ep_bench_fold(partials, parts, elems, mode, ticket, out)
+            b.record()
+            torch.cuda.synchronize()
+            us[key] = a.elapsed_time(b) * 1e3 / reps
+        res.append(dict(shape_of=name, partials=parts, floats_per_partial=elems, **us,
+                        second_launch_costs_us=us["producer_and_second_launch_us"] - us["producer_alone_us"],
+                        fold_costs_us=us["producer_with_fold_us"] - us["producer_alone_us"]))
+    return dict(probe="fold of the second pass into the round kernel", launches_per_figure=reps, results=res)
+
+
 def profile_traffic(kernel: str, workload: str):
     """(bytes per launch, file) from the counter summary of `kernel` on `workload` under profiles/."""
     path = ROOT / "profiles" / f"{kernel}_{workload}_hbm_traffic.txt"
@@ -450,6 +479,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the sample-trained, balancing and graph-rewrite legs (for profiles of the step's kernels alone)")
+    ap.add_argument("--probe", default=None, choices=["fold"],
+                    help="run one of the library's benchmark probes instead of the workloads and print its figures")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -457,6 +488,9 @@ def main() -> int:
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    if args.probe == "fold":
+        print(json.dumps(probe_fold()))
+        return 0
     cpu_seconds = 0.0 if args.no_cpu_baseline else args.cpu_seconds
     also = OTHERS if args.also is None else args.also
     out = run_workload(args.workload, args.steps, args.warmup, cpu_seconds, not args.no_variants)

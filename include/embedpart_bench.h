@@ -54,6 +54,21 @@ int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
 #define EP_BENCH_MFMA_FLOP_PER_ITER (512.0 * 4 * 16 * 32768)
 int ep_bench_mfma_bf16(const void *operands, int32_t iters, float *sink, void *stream);
 
+/*
+ * Benchmark aid: the price of folding the second pass of a Lloyd round into its first kernel.  `parts`
+ * workgroups each write `elems` floats of partial sums to `partials`; then
+ *   mode 0  nothing more (the producer alone);
+ *   mode 1  every workgroup passes a device-scope fence and takes an integer ticket, and the last one to arrive
+ *           adds all partials in fp64 and writes `out` ("the last workgroup reduces": one launch);
+ *   mode 2  a second launch of elems / 8 workgroups adds the partials and writes `out` (what the library's
+ *           rounds do).
+ * No workgroup waits for another in any mode.
+ *   partials  parts * elems floats, device, written;  out  elems floats, device, written (modes 1, 2);
+ *   ticket    4 bytes, device, zero before the first call (mode 1 leaves it zero again);
+ *   parts in [1, 2048], elems a multiple of 8 in [8, 8192]; EP_EINVAL otherwise or for a null pointer.
+ */
+int ep_bench_fold(float *partials, int32_t parts, int32_t elems, int mode, uint32_t *ticket, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -265,6 +265,12 @@ int ep_bench_copy(void *dst, const void *src, size_t bytes, void *stream) {
     return launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+int ep_bench_fold(float *partials, int32_t parts, int32_t elems, int mode, uint32_t *ticket, float *out, void *stream) {
+    if (!partials || !ticket || !out || !aligned(partials, 4) || !aligned(ticket, 4) || !aligned(out, 4)) return EP_EINVAL;
+    if (parts < 1 || parts > 2048 || elems < 8 || elems > 8192 || elems % 8 != 0 || mode < 0 || mode > 2) return EP_EINVAL;
+    return launch_bench_fold(partials, parts, elems, mode, ticket, out, static_cast<hipStream_t>(stream));
+}
+
 int ep_bench_mfma_bf16(const void *operands, int32_t iters, float *sink, void *stream) {
     if (!operands || !sink || !aligned(operands, 16) || !aligned(sink, 4) || iters < 1 || iters > (1 << 22))
         return EP_EINVAL;

@@ -172,6 +172,10 @@ size_t large_record_bytes(const ep_problem &p);
 // Rounds C to bf16 (w.cq16), leaves -||c||^2/2 in w.cnorm, then labels / min_d2 / objective.
 int launch_large_assign(const ep_problem &p, const void *X, const float *C, const KmeansWs &w, int32_t *labels,
                         float *min_d2, double *objective, hipStream_t s);
+// Benchmark aid (bench_probe.hip): `parts` workgroups write `elems` partials each; mode 0 nothing more, 1 the last
+// workgroup to arrive adds them up behind a ticket, 2 a second launch adds them up.
+int launch_bench_fold(float *partials, int32_t parts, int32_t elems, int mode, unsigned *ticket, float *out,
+                      hipStream_t s);
 // Benchmark aid: 512 workgroups x 4 waves x 16 * iters v_mfma_f32_32x32x16_bf16 on 65,536 bytes of operands.
 int launch_bench_mfma(const void *operands, int32_t iters, float *sink, hipStream_t s);
 

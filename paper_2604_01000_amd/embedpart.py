@@ -30,7 +30,7 @@ SYMBOLS = (
     "partition_quality", "partition_permutation", "edge_gap_sum", "vertex_bandwidth_sum",
     "balance_workspace_bytes", "partition_balance", "graph_reorder_workspace_bytes", "graph_reorder",
     "cluster_and_balance_workspace_bytes", "cluster_and_balance",
-    "ep_profile_arm", "ep_profile_count", "ep_bench_copy", "ep_bench_mfma_bf16",
+    "ep_profile_arm", "ep_profile_count", "ep_bench_copy", "ep_bench_mfma_bf16", "ep_bench_fold",
 )
 EP_PROF_LLOYD_MAIN, EP_PROF_UPDATE_SUMS, EP_PROF_EDGE_SWEEP = 1, 2, 3
 
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
         L.ep_profile_arm.argtypes = [vp, C.c_int, C.c_int]
         L.ep_bench_copy.argtypes = [vp, vp, sz, vp]
         L.ep_bench_mfma_bf16.argtypes = [vp, i32, vp, vp]
+        L.ep_bench_fold.argtypes = [vp, i32, i32, C.c_int, vp, vp, vp]
         for name in SYMBOLS:
             if name not in ("ep_strerror",):
                 getattr(L, name).restype = C.c_int
@@ -291,6 +292,13 @@ def ep_bench_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().ep_bench_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "ep_bench_copy")
+
+
+def ep_bench_fold(partials, parts, elems, mode, ticket, out):
+    """`parts` workgroups write `elems` partials each; mode 0 nothing more, 1 the last workgroup to arrive adds them
+    up behind a ticket, 2 a second launch adds them up."""
+    assert partials.numel() >= parts * elems and out.numel() >= elems and ticket.numel() >= 1
+    _check(lib().ep_bench_fold(_ptr(partials), parts, elems, mode, _ptr(ticket), _ptr(out), _stream()), "ep_bench_fold")
 
 
 EP_BENCH_MFMA_OPERAND_BYTES = 65536

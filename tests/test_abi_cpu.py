@@ -96,6 +96,11 @@ def test_null_pointers_workspace_and_flags():
     assert L.ep_validate_labels(10, 4, fake, C.c_void_p(0x1004), None) == ep.EP_EINVAL
     assert L.kmeans_run(C.byref(p), fake, -1, fake, fake, fake, None, 0, ws, need, None) == ep.EP_EINVAL
     assert L.kmeans_run(C.byref(p), fake, 1, fake, fake, fake, None, 8, ws, need, None) == ep.EP_EINVAL
+    assert L.ep_bench_fold(None, 8, 64, 0, fake, fake, None) == ep.EP_EINVAL
+    assert L.ep_bench_fold(fake, 0, 64, 0, fake, fake, None) == ep.EP_EINVAL
+    assert L.ep_bench_fold(fake, 8, 60, 0, fake, fake, None) == ep.EP_EINVAL      # not a multiple of 8
+    assert L.ep_bench_fold(fake, 8, 64, 3, fake, fake, None) == ep.EP_EINVAL
+    assert L.ep_bench_fold(fake, 4096, 64, 1, fake, fake, None) == ep.EP_EINVAL
     assert L.ep_bench_mfma_bf16(None, 1, fake, None) == ep.EP_EINVAL
     assert L.ep_bench_mfma_bf16(fake, 0, fake, None) == ep.EP_EINVAL
     assert L.ep_bench_mfma_bf16(fake, (1 << 22) + 1, fake, None) == ep.EP_EINVAL
