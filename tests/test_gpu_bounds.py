@@ -81,6 +81,7 @@ SHAPES = [  # n, d, k, dtype, iters, components
     (12_000, 128, 8, torch.bfloat16, 12, 10), (5_000, 64, 50, torch.bfloat16, 8, 30), (6_001, 128, 24, torch.bfloat16, 9, 16),
     (4_099, 64, 4, torch.float32, 15, 8), (37, 128, 5, torch.float32, 6, 3), (500, 128, 64, torch.float32, 7, 5),
     (3_000, 128, 2, torch.float32, 8, 6), (8_000, 128, 40, torch.float16, 9, 25), (6_000, 64, 12, torch.float16, 10, 9),
+    (6_007, 64, 48, torch.float32, 9, 20),   # d = 64, k > 32: the bounds are taken inside the pipelined loop
 ]
 
 
