@@ -145,6 +145,7 @@ struct BoundsWs {
     float *delta;            // [k] centroid movement of the last update
     unsigned char *top;      // its two largest values, the centroid that moved most, max ||c||^2
     float *C_old;            // [k*d] the centroids the round's assignment used
+    int32_t *scrap;          // four words per thread of the search grid: where lanes without a point store
     size_t bytes;
 };
 bool bounds_path_supported(const ep_problem &p);

@@ -243,7 +243,8 @@ template <int D, int KT, typename XT>
 __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     int64_t n, int64_t ld, int32_t k, const XT *__restrict__ X, const float *__restrict__ C,
     const int32_t *__restrict__ active_idx, const int64_t *__restrict__ n_active_ptr, int32_t *__restrict__ labels,
-    float *__restrict__ ub, float *__restrict__ lb, float *__restrict__ psum, int32_t *__restrict__ pcnt) {
+    float *__restrict__ ub, float *__restrict__ lb, float *__restrict__ psum, int32_t *__restrict__ pcnt,
+    int32_t *__restrict__ scrap) {
     constexpr int NJ = D / 16;
     constexpr int NX = NJ;
     constexpr int STRIDE = D + 4;
@@ -275,12 +276,19 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     const int64_t first = wave_id * per + min(wave_id, extra);
     const int64_t last = first + per + (wave_id < extra ? 1 : 0);
 
-    // row of this lane's point in sub-tile st (-1: none)
-    auto fetch_row = [&](int64_t st) -> int64_t {
+    // Row of this lane's point in sub-tile st, in two steps.  The list entry is loaded unconditionally (from a
+    // position clamped into the list) and not looked at; it is checked one sub-tile later, where it is used.
+    // A value that is tested right after its load makes the wave wait for that load, and on this chip that wait
+    // is for every older and, when a branch stands in between, every younger access too: the row loads of the
+    // next sub-tile, issued just before, would be waited for at once.  The same holds for the old labels and is
+    // why the stores below have no branch.
+    auto fetch_raw = [&](int64_t st) -> int32_t {
         const int64_t pos = st * kSub + c;
-        if (st >= last || pos >= n_act) return -1;
-        const int64_t row = (int64_t)active_idx[pos];
-        return row >= 0 && row < n ? row : -1;
+        return active_idx[pos < n_act ? pos : n_act - 1];   // n_act >= 1: a workgroup without rows has left
+    };
+    auto resolve_row = [&](int32_t raw, int64_t st) -> int64_t {   // -1: none
+        const int64_t pos = st * kSub + c;
+        return (st < last && pos < n_act && raw >= 0 && (int64_t)raw < n) ? (int64_t)raw : -1;
     };
     auto load_x = [&](int64_t row, f32x4(&dst)[NX]) {
         const XT *ptr = X + (row < 0 ? 0 : row) * ld + 4 * g;
@@ -297,11 +305,7 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
             }
         }
     };
-    auto load_old = [&](int64_t row) -> int32_t {
-        if (row < 0) return -1;
-        const int32_t a = labels[row];
-        return (uint32_t)a < (uint32_t)k ? a : -1;
-    };
+    auto load_old_raw = [&](int64_t row) -> int32_t { return labels[row < 0 ? 0 : row]; };   // checked in process()
 
     // ---- centroid operand (as in lloyd_small_kernel) ----
     f32x4 creg[kSplit ? 1 : KT][kSplit ? 1 : NJ];
@@ -419,8 +423,9 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
         }
     };
 
-    auto process = [&](int64_t st, const f32x4(&x)[NX], int64_t row_c, int32_t old_c) {
+    auto process = [&](int64_t st, const f32x4(&x)[NX], int64_t row_c, int32_t old_raw) {
         const int rows_here = (int)min((int64_t)kSub, n_act - st * kSub);   // uniform, >= 1
+        const int32_t old_c = (row_c >= 0 && (uint32_t)old_raw < (uint32_t)k) ? old_raw : -1;
         f32x4 acc[KT];
         scores(x, acc);
 
@@ -462,14 +467,19 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
         const int32_t my_l = sel == 0 ? lab[0] : sel == 1 ? lab[1] : sel == 2 ? lab[2] : lab[3];
         const int src = 4 * g + sel;   // a lane that holds point 4 g + c's row index, old label and norm
         const int64_t own_row = __shfl(row_c, src, 64);
-        const int32_t own_old = __shfl(old_c, src, 64);
         const float own_xn = __shfl(xpart, src, 64);
-        if (c < 4 && 4 * g + c < rows_here && own_row >= 0) {
+        {   // every lane stores, without a branch: a lane that owns no point writes its three scrap words, and an
+            // owner writes its label whether it changed or not
+            const bool owner = c < 4 && 4 * g + c < rows_here && own_row >= 0;
             float u, l;
             fresh_bounds(own_xn, s_best, s_second, cmax2, u, l);
-            ub[own_row] = u;
-            lb[own_row] = l;
-            if (my_l != own_old) labels[own_row] = my_l;
+            int32_t *mine = scrap + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+            float *pu = owner ? ub + own_row : reinterpret_cast<float *>(mine);
+            float *pl = owner ? lb + own_row : reinterpret_cast<float *>(mine + 1);
+            int32_t *pa = owner ? labels + own_row : mine + 2;
+            *pu = u;
+            *pl = l;
+            *pa = my_l;
         }
 
         // the rows that change side: + x into the new label's sum, - x out of the old one's
@@ -487,27 +497,28 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     // Two register sets in ping-pong; the row indices run one sub-tile further ahead than the rows.
     f32x4 xa[NX], xb[NX];
     int64_t st = first;
-    int64_t row_a = fetch_row(st), row_b = fetch_row(st + 1), row_n;
-    int32_t old_a = load_old(row_a), old_b;
+    int64_t row_a = resolve_row(fetch_raw(st), st), row_b;
+    int32_t raw_n = fetch_raw(st + 1);   // the list entry of the sub-tile after the one whose rows are in flight
+    int32_t old_a = load_old_raw(row_a), old_b;
     load_x(row_a, xa);
     __builtin_amdgcn_sched_barrier(0);
     load_centroids();
     while (st < last) {
+        row_b = resolve_row(raw_n, st + 1);
         load_x(row_b, xb);
-        old_b = load_old(row_b);
-        row_n = fetch_row(st + 2);
+        old_b = load_old_raw(row_b);
+        raw_n = fetch_raw(st + 2);
         __builtin_amdgcn_sched_barrier(0);
         process(st, xa, row_a, old_a);
         ++st;
         if (st >= last) break;
-        row_a = row_n;
+        row_a = resolve_row(raw_n, st + 1);
         load_x(row_a, xa);
-        old_a = load_old(row_a);
-        row_n = fetch_row(st + 2);
+        old_a = load_old_raw(row_a);
+        raw_n = fetch_raw(st + 2);
         __builtin_amdgcn_sched_barrier(0);
         process(st, xb, row_b, old_b);
         ++st;
-        row_b = row_n;
     }
 
     // ---- partial sums of this workgroup: the waves' tables added in wave order ----
@@ -522,7 +533,8 @@ __global__ __launch_bounds__(kBlock, KT <= 2 ? 2 : 1) void bounds_round_kernel(
     if ((int)threadIdx.x < k) pcnt[(int64_t)blockIdx.x * k + threadIdx.x] = cnt_lds[threadIdx.x];
 }
 
-int bounds_grid(const ep_problem &p) { return p.k <= 32 ? 512 : 256; }
+constexpr int kBoundsGridMax = 512;
+int bounds_grid(const ep_problem &p) { return p.k <= 32 ? kBoundsGridMax : 256; }
 
 struct PassGeometry {
     int blocks;
@@ -552,6 +564,7 @@ BoundsWs carve_bounds_ws(const ep_problem &p, int32_t iters, void *ws) {
     w.delta = c.take<float>((size_t)p.k);
     w.top = c.take<unsigned char>(sizeof(DriftTop));
     w.C_old = c.take<float>((size_t)p.k * p.d);
+    w.scrap = c.take<int32_t>((size_t)kBoundsGridMax * kBlock * 4);
     w.bytes = align_up(c.used, 256);
     return w;
 }
@@ -628,7 +641,7 @@ int launch_bounds_round(const ep_problem &p, const void *X, const float *C, cons
             }                                                                                                   \
         }                                                                                                       \
         kern<<<grid, kBlock, lds_bytes, s>>>(p.n, p.ld, p.k, static_cast<const XT_ *>(X), C, idx, n_act, labels, \
-                                             w.ub, w.lb, kw.psum, kw.pcnt);                                     \
+                                             w.ub, w.lb, kw.psum, kw.pcnt, w.scrap);                            \
     } while (0)
 #define EP_BOUNDS_LAUNCH_T(D_, KT_)                                                                             \
     do {                                                                                                        \
