@@ -153,17 +153,37 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     // this wave's position in its stream of entries
     int64_t rb = (int64_t)blockIdx.x * kScatterWaves + wave - rb_stride;   // current row block (none yet)
     int64_t p0 = 0, e_begin = 0, e_end = 0;   // next 256-entry step of the block, the block's entry range
-    i32x4 ahead = {-1, -1, -1, -1};           // this lane's four entries of the step at p0, loaded one step early
+    i32x4 ahead = {0, 0, 0, 0};               // this lane's four entries of the step at p0, loaded one step early
     unsigned long long lost = 0;
 
-    auto load4 = [&](int64_t p) {
-        i32x4 c = {-1, -1, -1, -1};
-        if (p < e_end) {
-            if (p + 3 < nnz) c = *reinterpret_cast<const i32x4 *>(colidx + p);
-            else for (int t = 0; t < 4; ++t) if (p + t < nnz) c[t] = colidx[p + t];
-        }
-        return c;
+    // Every load of the stream is unconditional and branch-free, so that the compiler can count the accesses in
+    // flight exactly: a wait for the entries loaded one step ago then leaves the step just issued in flight.  (Behind
+    // a load under a branch every later wait is for all outstanding accesses, and the read-ahead is waited for as
+    // soon as it is issued.)  The 256 entries of the step at p come through a buffer descriptor that ends at the
+    // block's last entry: lanes past it get zeros, which no test below looks at (such an entry is not live).
+    auto uniform64 = [](int64_t v) -> int64_t {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+        return (int64_t)(((uint64_t)hi << 32) | lo);
     };
+    auto load4 = [&](int64_t pstep) {   // pstep: first entry of the step, the same in every lane, a multiple of 4
+        const int64_t ps = uniform64(pstep), pe = uniform64(min(e_end, nnz));
+        const int64_t left = pe - ps;
+        const int bytes = left <= 0 ? 0 : (int)(min(left, (int64_t)256) * 4);
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int32_t *>(colidx + (left <= 0 ? 0 : ps)), 0, bytes, 0x00020000);
+        return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, 16 * lane, 0, 0));
+    };
+    // The offsets and labels of the wave's next row block are fetched one block ahead, into registers.
+    int64_t nrp = 0, nrp_end = 0;
+    int32_t nau = 255;
+    auto fetch_block = [&](int64_t b) {   // unconditional: rows past the graph read the last offset / a valid label
+        const int64_t r0 = min(b, row_blocks) * 64;
+        nrp = (int64_t)rowptr[min(r0 + lane, n)];
+        nrp_end = (int64_t)rowptr[min(r0 + 64, n)];
+        nau = (int32_t)label8[min(r0 + lane, n - 1)];
+    };
+    fetch_block(rb + rb_stride);
     // the next row block of this wave that has entries; false when the wave has none left
     auto next_block = [&]() -> bool {
         for (;;) {
@@ -174,16 +194,19 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
             }
             const int64_t r0 = rb * 64;
             wave_fence();   // the window of the previous block is no longer read
-            const int64_t r = min(r0 + lane, n);
-            rp[lane] = min(max((int64_t)rowptr[r], (int64_t)0), nnz);
-            if (lane == 0) rp[64] = min(max((int64_t)rowptr[min(r0 + 64, n)], (int64_t)0), nnz);
-            aus[lane] = r0 + lane < n ? (int32_t)label8[r0 + lane] : 255;
+            rp[lane] = min(max(nrp, (int64_t)0), nnz);
+            if (lane == 0) rp[64] = min(max(nrp_end, (int64_t)0), nnz);
+            aus[lane] = r0 + lane < n ? nau : 255;
+            // (the old values are used up before the new loads are issued: loaded into other registers first, they
+            // would have to be copied, and a copy waits for its load)
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_block(rb + rb_stride);
             wave_fence();
             e_begin = rp[0];
             e_end = rp[64];
             p0 = e_begin & ~(int64_t)3;
             if (e_end > e_begin) {
-                ahead = load4(p0 + 4 * lane);
+                ahead = load4(p0);
                 return true;
             }
         }
@@ -203,7 +226,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 worked = true;
                 const int64_t p = p0 + 4 * lane;
                 const i32x4 c = ahead;
-                ahead = load4(p + 256);   // the next step of this block, in flight while this one is ranked
+                ahead = load4(p0 + 256);   // the next step of this block, in flight while this one is ranked
                 int j = 0;
                 {
                     const int64_t q = max(p, e_begin);
