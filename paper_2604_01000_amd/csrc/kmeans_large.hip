@@ -320,23 +320,31 @@ __global__ __launch_bounds__(kBlock) void large_refine_kernel(int64_t n, int64_t
     const int64_t group = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 5;
     const int64_t groups = ((int64_t)gridDim.x * kBlock) >> 5;
     double obj = 0.0;
+    // The code and the row piece of the next point are loaded (unconditionally, from a clamped index) before this
+    // point's candidate rows are waited for, and no load of the loop stands under a branch, so the compiler's wait
+    // counts stay exact: the loop exposes one memory latency per point instead of two.
+    int64_t i = group;
+    int code_raw = best_code[i < n ? i : 0];
+    uint4 xc = *reinterpret_cast<const uint4 *>(X + (i < n ? i : 0) * ld + 8 * chunk);
     for (int64_t i0 = 0; i0 < n; i0 += groups) {   // uniform trip count: the lane exchanges need every lane
-        const int64_t i = i0 + group;
         const bool valid = i < n;
-        const int code = valid ? best_code[i] : 0;
-        const uint4 xc = *reinterpret_cast<const uint4 *>(X + (valid ? i : 0) * ld + 8 * chunk);
+        const int64_t i_next = i + groups;
+        const int code_next = best_code[i_next < n ? i_next : 0];
+        const uint4 xc_next = *reinterpret_cast<const uint4 *>(X + (i_next < n ? i_next : 0) * ld + 8 * chunk);
+        const int code = valid ? code_raw : 0;
         // candidates: rows 8 group + 4 half .. + 3 of tile code / 8
         const int64_t first_row = (int64_t)(code >> 3) * kTile + 8 * ((code >> 1) & 3) + 4 * (code & 1);
-        const uint4 *base = reinterpret_cast<const uint4 *>(cq16 + first_row * D);
         float best = kNever;
         int bidx = 0x7fffffff;
 #pragma unroll
         for (int q = 0; q < (CAND + ROWS - 1) / ROWS; ++q) {
             const int row = q * ROWS + sub;
             const bool real = row < CAND && first_row + row < k;   // rows of the padded last tile are never read
-            const uint4 cc = real ? base[q * 32 + r] : uint4{0, 0, 0, 0};
+            const int64_t at = real ? first_row + row : 0;          // (a lane without a row reads row 0 and ignores it)
+            const uint4 cc = *reinterpret_cast<const uint4 *>(cq16 + at * D + 8 * chunk);
+            const float bias = hneg[at];
             const float dot = group_sum<CH>(dot8(xc, cc, 0.f));
-            const float score = real ? dot + hneg[first_row + row] : kNever;
+            const float score = real ? dot + bias : kNever;
             if (score > best) { best = score; bidx = (int)(first_row + row); }
         }
 #pragma unroll
@@ -352,6 +360,9 @@ __global__ __launch_bounds__(kBlock) void large_refine_kernel(int64_t n, int64_t
             if (min_d2) min_d2[i] = d2;
             obj += (double)d2;
         }
+        i = i_next;
+        code_raw = code_next;
+        xc = xc_next;
     }
     if (obj_part) {
         for (int off = 32; off > 0; off >>= 1) obj += __shfl_down(obj, off, 64);
