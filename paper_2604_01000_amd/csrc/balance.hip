@@ -83,12 +83,30 @@ __global__ __launch_bounds__(kBlock) void bal_count_kernel(int64_t n, int32_t k,
     const int cells = k * bins;
     for (int i = threadIdx.x; i < cells; i += kBlock) h[i] = 0;
     __syncthreads();
-    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n; v += (int64_t)gridDim.x * kBlock) {
-        if (vclass && vclass[v] != class_id) continue;
-        const int32_t l = labels[v];
-        if (l < 0 || l >= k) continue;
-        const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
-        atomicAdd(&h[l * bins + (int)std::min<int64_t>(std::max<int64_t>(deg, 0), bins - 1)], 1u);
+    // Class, label and the two offsets of four vertices per thread are loaded at once and unconditionally (a vertex
+    // past the end reads the last one and is ignored): tested one after the other, each under the branch of the test
+    // before, they were three memory latencies in a row per vertex, at two workgroups per compute unit.
+    constexpr int kPer = 4;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const uint8_t *cls = vclass ? vclass : reinterpret_cast<const uint8_t *>(labels);   // without classes: read, not used
+    for (int64_t v0 = (int64_t)blockIdx.x * kBlock + threadIdx.x; v0 < n; v0 += kPer * stride) {
+        uint8_t c[kPer];
+        int32_t l[kPer];
+        RowT lo[kPer], hi[kPer];
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int64_t v = std::min<int64_t>(v0 + q * stride, n - 1);
+            c[q] = cls[v];
+            l[q] = labels[v];
+            lo[q] = rowptr[v];
+            hi[q] = rowptr[v + 1];
+        }
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const bool mine = v0 + q * stride < n && (!vclass || c[q] == class_id) && l[q] >= 0 && l[q] < k;
+            const int64_t deg = (int64_t)(hi[q] - lo[q]);
+            if (mine) atomicAdd(&h[l[q] * bins + (int)std::min<int64_t>(std::max<int64_t>(deg, 0), bins - 1)], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < cells; i += kBlock)
@@ -181,11 +199,25 @@ __global__ __launch_bounds__(kBlock) void bal_tie_count_kernel(int64_t n, int32_
     tdeg[threadIdx.x] = (int)threadIdx.x < k && plan->m[threadIdx.x] > 0 ? plan->tdeg[threadIdx.x] : -1;
     __syncthreads();
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
-    for (int64_t v = b + threadIdx.x; v < e; v += kBlock) {
-        if (vclass && vclass[v] != class_id) continue;
-        const int32_t l = labels[v];
-        if (l < 0 || l >= k) continue;
-        if ((int64_t)(rowptr[v + 1] - rowptr[v]) == (int64_t)tdeg[l]) atomicAdd(&cnt[l], 1);
+    constexpr int kPer = 4;   // loads of four vertices per thread at once, unconditionally (as in bal_count_kernel)
+    const uint8_t *cls = vclass ? vclass : reinterpret_cast<const uint8_t *>(labels);
+    for (int64_t v0 = b + threadIdx.x; v0 < e; v0 += kPer * kBlock) {
+        uint8_t c[kPer];
+        int32_t l[kPer];
+        RowT lo[kPer], hi[kPer];
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int64_t v = std::min<int64_t>(v0 + q * kBlock, n - 1);
+            c[q] = cls[v];
+            l[q] = labels[v];
+            lo[q] = rowptr[v];
+            hi[q] = rowptr[v + 1];
+        }
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const bool mine = v0 + q * kBlock < e && (!vclass || c[q] == class_id) && l[q] >= 0 && l[q] < k;
+            if (mine && (int64_t)(hi[q] - lo[q]) == (int64_t)tdeg[l[q]]) atomicAdd(&cnt[l[q]], 1);
+        }
     }
     __syncthreads();
     if ((int)threadIdx.x < k) tie[(int64_t)blockIdx.x * k + threadIdx.x] = cnt[threadIdx.x];
@@ -318,15 +350,19 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
     const uint32_t round = (uint32_t)plan->round;
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
     unsigned long long moved_total = 0;
+    const uint8_t *cls = vclass ? vclass : reinterpret_cast<const uint8_t *>(labels);
     for (int64_t tile = b; tile < e; tile += kBlock) {
         const int64_t v = tile + t;
         int32_t l = -1;
         int64_t deg = 0;
-        if (v < e && (!vclass || vclass[v] == class_id)) {
-            const int32_t lab = labels[v];
-            if (lab >= 0 && lab < k && tdeg[lab] >= 0) {
+        {   // the four values of the vertex are loaded together and unconditionally, then tested
+            const int64_t vq = std::min<int64_t>(v, n - 1);
+            const uint8_t cq = cls[vq];
+            const int32_t lab = labels[vq];
+            const RowT lo = rowptr[vq], hi = rowptr[vq + 1];
+            if (v < e && (!vclass || cq == class_id) && lab >= 0 && lab < k && tdeg[lab] >= 0) {
                 l = lab;
-                deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
+                deg = (int64_t)(hi - lo);
             }
         }
         const bool at_threshold = l >= 0 && deg == (int64_t)tdeg[l];
