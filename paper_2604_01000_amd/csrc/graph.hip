@@ -62,14 +62,35 @@ __global__ __launch_bounds__(kBlock) void label_prep_kernel(int64_t n, int32_t k
         for (int j = threadIdx.x; j < k; j += kBlock) hist[j] = 0;
         __syncthreads();
     }
+    // four consecutive labels per thread: one 16-byte load and one 4-byte store of the byte copy (both arrays are
+    // 16-byte aligned allocations; the last, partial group goes element by element)
     const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+    const int64_t groups = n / 4;
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const bool vec = (reinterpret_cast<uintptr_t>(labels) & 15) == 0 && (reinterpret_cast<uintptr_t>(label8) & 3) == 0;
+    auto count = [&](int32_t l) {
+        if (in_lds) atomicAdd(&hist[l], 1);
+        else atomicAdd(reinterpret_cast<unsigned long long *>(&sizes[l]), 1ull);
+    };
+    const int64_t first_single = vec ? 4 * groups : 0;
+    if (vec) {
+        for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < groups; g += stride) {
+            const i32x4 l4 = *reinterpret_cast<const i32x4 *>(labels + 4 * g);
+            uint32_t packed = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool ok = l4[q] >= 0 && l4[q] < k;
+                packed |= (ok ? (uint32_t)l4[q] & 0xffu : 255u) << (8 * q);
+                if (ok) count(l4[q]);
+            }
+            if (label8) *reinterpret_cast<uint32_t *>(label8 + 4 * g) = packed;
+        }
+    }
+    for (int64_t i = first_single + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
         const int32_t l = labels[i];
         const bool ok = l >= 0 && l < k;
         if (label8) label8[i] = ok ? (uint8_t)l : (uint8_t)255;
-        if (!ok) continue;
-        if (in_lds) atomicAdd(&hist[l], 1);
-        else atomicAdd(reinterpret_cast<unsigned long long *>(&sizes[l]), 1ull);
+        if (ok) count(l);
     }
     if (in_lds) {
         __syncthreads();
