@@ -230,10 +230,18 @@ __global__ __launch_bounds__(256) void bal_tie_scan_kernel(int32_t k, int blocks
     const int l = threadIdx.x;
     if (l >= k) return;
     int32_t run = 0;
-    for (int b = 0; b < blocks; ++b) {
-        const int32_t c = tie[(int64_t)b * k + l];
-        tie[(int64_t)b * k + l] = run;
-        run += c;
+    constexpr int kBatch = 16;   // loads in flight per thread (one at a time, each waited for, before)
+    for (int b0 = 0; b0 < blocks; b0 += kBatch) {
+        int32_t c[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) c[q] = tie[(int64_t)std::min(b0 + q, blocks - 1) * k + l];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (b0 + q < blocks) {
+                tie[(int64_t)(b0 + q) * k + l] = run;
+                run += c[q];
+            }
+        }
     }
 }
 
@@ -351,20 +359,29 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
     const int64_t b = (int64_t)blockIdx.x * rows_per_block, e = min(n, b + rows_per_block);
     unsigned long long moved_total = 0;
     const uint8_t *cls = vclass ? vclass : reinterpret_cast<const uint8_t *>(labels);
+    // The four values of a vertex are loaded together and unconditionally, one tile ahead: the tile's three
+    // barriers pass while the next tile's loads are in flight.  (A tile only writes the labels of its own vertices,
+    // so the labels read ahead are not changed by it.)
+    uint8_t cq;
+    int32_t lab;
+    RowT lo, hi;
+    auto fetch = [&](int64_t v) {
+        const int64_t vq = std::min<int64_t>(v, n - 1);
+        cq = cls[vq];
+        lab = labels[vq];
+        lo = rowptr[vq];
+        hi = rowptr[vq + 1];
+    };
+    fetch(b + t);
     for (int64_t tile = b; tile < e; tile += kBlock) {
         const int64_t v = tile + t;
         int32_t l = -1;
         int64_t deg = 0;
-        {   // the four values of the vertex are loaded together and unconditionally, then tested
-            const int64_t vq = std::min<int64_t>(v, n - 1);
-            const uint8_t cq = cls[vq];
-            const int32_t lab = labels[vq];
-            const RowT lo = rowptr[vq], hi = rowptr[vq + 1];
-            if (v < e && (!vclass || cq == class_id) && lab >= 0 && lab < k && tdeg[lab] >= 0) {
-                l = lab;
-                deg = (int64_t)(hi - lo);
-            }
+        if (v < e && (!vclass || cq == class_id) && lab >= 0 && lab < k && tdeg[lab] >= 0) {
+            l = lab;
+            deg = (int64_t)(hi - lo);
         }
+        fetch(v + kBlock);
         const bool at_threshold = l >= 0 && deg == (int64_t)tdeg[l];
         // lanes of this wave at the threshold of the same partition
         const int key = at_threshold ? l : 0;
