@@ -17,10 +17,11 @@
 //      workgroups and an ordered count inside the workgroup;
 //   4. the destination of a mover v is the partition whose interval of the running sum holds
 //      (mix(seed, round, v) mod F).
-//   Only if some t_i falls into the last histogram bin (more movers than members below degree B-1) the
-//   round falls back to sorting: key (partition << 24) | min(degree, 2^24 - 1), stable 4-pass radix
-//   sort of the vertex ids, the first m_i of every partition's run move.  Both ways pick the same
-//   vertices (ascending degree, equal degrees by ascending id).
+//   If some t_i falls into the last histogram bin (more movers than members below degree B-1), the range that
+//   holds it is counted again with B bins of equal width and narrowed to the bin with the need_i-th member, level
+//   by level until the bins are one degree wide (two or three more counting passes; degrees enter as
+//   min(degree, 2^24 - 1)); then step 3 runs as always.  Nothing is sorted; the movers are the first m_i members
+//   by ascending degree, equal degrees by ascending id.
 // The draw is a function of (seed, round, v) only, so the result does not depend on the order in
 // which threads get to the vertices.  Rounds whose plan finds nothing overloaded do nothing (every
 // kernel after the plan reads its flags and returns, and once a plan has found nothing overloaded even
@@ -36,19 +37,19 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kPartMax = 255;                 // partition ids fit the top byte of a key, 255 = "stays"
-constexpr uint32_t kStay = 0xFFFFFFFFu;
 constexpr uint32_t kDegreeMask = 0x00FFFFFFu;
 
 struct BalPlan {
     unsigned long long L[256];    // loads of the class per partition (this round)
     long long m[256];             // vertices to move out (0 unless overloaded)
     long long cumf[256];          // running sum of the free capacities, partitions in index order
-    long long seg[257];           // first sorted position of every partition's run
+    int ref_lo[256];              // refinement: first degree of the range a partition's threshold is known to lie in
+    int refining[256];            // refinement: the partition's threshold degree is not yet pinned to one degree
     long long F;                  // total free capacity
     int active;                   // this round moves vertices
     int round;                    // rounds completed before this one (enters the draw)
-    int by_sort;                  // ... by the sorting fallback (a threshold degree in the last bin)
-    int by_select;                // ... by selection
+    int refine;                   // a threshold degree fell into the last histogram bin: the refinement passes run
+    int by_select;                // this round moves vertices (selection of the smallest (degree, id) members)
     int finished;                 // a plan found nothing overloaded: later rounds do nothing
     int tdeg[256];                // threshold degree t_i of the overloaded partitions
     long long need[256];          // members of degree t_i that move (the smallest ids)
@@ -120,13 +121,13 @@ __global__ __launch_bounds__(256) void bal_plan_kernel(int32_t k, int bins, doub
     if (plan->finished) return;
     __shared__ long long load_lds[256];
     __shared__ long long cap_lds;
-    __shared__ int sort_lds;
+    __shared__ int refine_lds;
     const int i = threadIdx.x;
     long long L = 0;
     if (i < k)
         for (int b = 0; b < bins; ++b) L += dhist[i * bins + b];
     load_lds[i] = L;
-    if (i == 0) sort_lds = 0;
+    if (i == 0) refine_lds = 0;
     __syncthreads();
     if (i == 0) {
         long long total = 0;
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(256) void bal_plan_kernel(int32_t k, int bins, doub
     __syncthreads();
     const long long cap = cap_lds;
     long long m = 0, need = 0;
-    int tdeg = 0;
+    int tdeg = 0, refining = 0;
     if (i < k) {
         plan->L[i] = (unsigned long long)L;
         m = L > cap ? L - cap : 0;
@@ -167,19 +168,113 @@ __global__ __launch_bounds__(256) void bal_plan_kernel(int32_t k, int bins, doub
             }
             tdeg = b;
             need = m - below;
-            if (b == bins - 1) sort_lds = 1;   // the last bin holds several degrees: this round sorts
+            if (b == bins - 1) {   // the last bin holds every degree from bins - 1 up: narrowed down by the refinement
+                refine_lds = 1;
+                refining = 1;
+            }
         }
         plan->m[i] = m;
         plan->tdeg[i] = tdeg;
         plan->need[i] = need;
+        plan->ref_lo[i] = bins - 1;
+        plan->refining[i] = refining;
     }
     __syncthreads();
     if (i == 0) {
-        plan->by_sort = plan->active && sort_lds;
-        plan->by_select = plan->active && !sort_lds;
+        plan->refine = plan->active && refine_lds;
+        plan->by_select = plan->active;
     }
     if (i < k)   // the next round's count starts from zero
         for (int b = 0; b < bins; ++b) dhist[i * bins + b] = 0;
+}
+
+// ---- refinement of a threshold degree that fell into the last bin ------------------------------------------
+// The last bin of the first histogram holds every degree from bins - 1 up (degrees enter at most as
+// kDegreeMask).  A partition whose threshold lies there is counted again over the range it is known to lie in,
+// ref_lo .. ref_lo + bins * width, with `bins` bins of `width` degrees, and the range is narrowed to the bin that
+// holds the need-th member; the widths of the levels (a function of `bins` only, so the host launches a fixed
+// number of them) end at 1, where the threshold degree and the number of members to take at it are known.
+// Nothing is sorted.  Without a refining partition the kernels return at once.
+__host__ __device__ inline int64_t refine_width(int bins, int level) {   // level 1, 2, ...: bins of this many degrees
+    int64_t w = ((int64_t)kDegreeMask + 1 - (bins - 1) + bins - 1) / bins;
+    for (int j = 1; j < level; ++j) w = (w + bins - 1) / bins;
+    return w;
+}
+inline int refine_levels(int bins) {
+    int level = 1;
+    while (refine_width(bins, level) > 1) ++level;
+    return level;
+}
+
+template <typename RowT>
+__global__ __launch_bounds__(kBlock) void bal_refine_count_kernel(int64_t n, int32_t k, int bins, int64_t width,
+                                                                   const RowT *__restrict__ rowptr,
+                                                                   const uint8_t *__restrict__ vclass, int32_t class_id,
+                                                                   const int32_t *__restrict__ labels,
+                                                                   const BalPlan *__restrict__ plan,
+                                                                   unsigned int *__restrict__ dhist) {
+    if (!plan->refine) return;   // uniform over the grid
+    __shared__ unsigned int h[kHistCounters];
+    __shared__ int lo_lds[256];
+    const int cells = k * bins;
+    for (int i = threadIdx.x; i < cells; i += kBlock) h[i] = 0;
+    lo_lds[threadIdx.x] = (int)threadIdx.x < k && plan->refining[threadIdx.x] ? plan->ref_lo[threadIdx.x] : -1;
+    __syncthreads();
+    constexpr int kPer = 4;   // as in bal_count_kernel
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const uint8_t *cls = vclass ? vclass : reinterpret_cast<const uint8_t *>(labels);
+    for (int64_t v0 = (int64_t)blockIdx.x * kBlock + threadIdx.x; v0 < n; v0 += kPer * stride) {
+        uint8_t c[kPer];
+        int32_t l[kPer];
+        RowT lo[kPer], hi[kPer];
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int64_t v = std::min<int64_t>(v0 + q * stride, n - 1);
+            c[q] = cls[v];
+            l[q] = labels[v];
+            lo[q] = rowptr[v];
+            hi[q] = rowptr[v + 1];
+        }
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const bool mine = v0 + q * stride < n && (!vclass || c[q] == class_id) && l[q] >= 0 && l[q] < k;
+            if (!mine) continue;
+            const int first = lo_lds[l[q]];
+            if (first < 0) continue;
+            const int64_t deg = std::min<int64_t>(std::max<int64_t>((int64_t)(hi[q] - lo[q]), 0), (int64_t)kDegreeMask);
+            const int64_t off = deg - first;
+            if (off >= 0 && off < (int64_t)bins * width) atomicAdd(&h[l[q] * bins + (int)(off / width)], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < cells; i += kBlock)
+        if (h[i]) atomicAdd(&dhist[i], h[i]);   // integers: the order does not matter
+}
+
+// Thread i = partition i: the bin that holds its need-th member becomes its range; at width 1 that is the threshold.
+__global__ __launch_bounds__(256) void bal_refine_plan_kernel(int32_t k, int bins, int64_t width, BalPlan *plan,
+                                                               unsigned int *__restrict__ dhist) {
+    if (!plan->refine) return;
+    const int i = threadIdx.x;
+    if (i >= k) return;
+    if (plan->refining[i]) {
+        long long below = 0;
+        const long long need = plan->need[i];
+        int b = 0;
+        for (; b < bins - 1; ++b) {
+            const long long c = dhist[i * bins + b];
+            if (below + c >= need) break;
+            below += c;
+        }
+        const int first = plan->ref_lo[i] + (int)(b * width);
+        plan->ref_lo[i] = first;
+        plan->need[i] = need - below;
+        if (width == 1) {
+            plan->tdeg[i] = first;
+            plan->refining[i] = 0;
+        }
+    }
+    for (int b = 0; b < bins; ++b) dhist[i * bins + b] = 0;   // the next count starts from zero
 }
 
 // ---- selection: the movers are the members below the threshold degree and the first need_i (by id) at it ----
@@ -216,7 +311,8 @@ __global__ __launch_bounds__(kBlock) void bal_tie_count_kernel(int64_t n, int32_
 #pragma unroll
         for (int q = 0; q < kPer; ++q) {
             const bool mine = v0 + q * kBlock < e && (!vclass || c[q] == class_id) && l[q] >= 0 && l[q] < k;
-            if (mine && (int64_t)(hi[q] - lo[q]) == (int64_t)tdeg[l[q]]) atomicAdd(&cnt[l[q]], 1);
+            const int64_t deg = std::min<int64_t>((int64_t)(hi[q] - lo[q]), (int64_t)kDegreeMask);
+            if (mine && deg == (int64_t)tdeg[l[q]]) atomicAdd(&cnt[l[q]], 1);
         }
     }
     __syncthreads();
@@ -245,37 +341,6 @@ __global__ __launch_bounds__(256) void bal_tie_scan_kernel(int32_t k, int blocks
     }
 }
 
-template <typename RowT>
-__global__ __launch_bounds__(kBlock) void bal_keys_kernel(int64_t n, int32_t k, const RowT *__restrict__ rowptr,
-                                                           const uint8_t *__restrict__ vclass, int32_t class_id,
-                                                           const int32_t *__restrict__ labels,
-                                                           const BalPlan *__restrict__ plan,
-                                                           int32_t *__restrict__ keys) {
-    if (!plan->by_sort) return;   // uniform over the grid
-    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n; v += (int64_t)gridDim.x * kBlock) {
-        uint32_t key = kStay;
-        if (!vclass || vclass[v] == class_id) {
-            const int32_t l = labels[v];
-            if (l >= 0 && l < k && plan->m[l] > 0) {
-                const int64_t deg = (int64_t)(rowptr[v + 1] - rowptr[v]);
-                key = ((uint32_t)l << 24) | (uint32_t)std::min<int64_t>(deg, (int64_t)kDegreeMask);
-            }
-        }
-        keys[v] = (int32_t)key;
-    }
-}
-
-// seg[j] = first sorted position whose partition byte is >= j (j = 0 .. 256).
-__global__ void bal_segments_kernel(int64_t n, const int32_t *__restrict__ keys, const int32_t *__restrict__ order,
-                                    BalPlan *plan) {
-    if (!plan->by_sort) return;   // uniform over the grid
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i <= n; i += (int64_t)gridDim.x * blockDim.x) {
-        const int prev = i == 0 ? -1 : (int)((uint32_t)keys[order[i - 1]] >> 24);
-        const int cur = i == n ? 256 : (int)((uint32_t)keys[order[i]] >> 24);
-        for (int j = prev + 1; j <= cur; ++j) plan->seg[j] = i;
-    }
-}
-
 __device__ __forceinline__ uint64_t draw64(uint64_t seed, uint32_t round, int64_t v) {
     uint64_t z = seed + (((uint64_t)round << 32) + (uint64_t)v + 1ull) * 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -293,40 +358,6 @@ __device__ __forceinline__ uint64_t mod_by(uint64_t x, uint64_t F, uint64_t magi
     return r;
 }
 
-__global__ __launch_bounds__(kBlock) void bal_move_kernel(int64_t n, int32_t k, uint64_t seed,
-                                                           const int32_t *__restrict__ keys,
-                                                           const int32_t *__restrict__ order,
-                                                           const BalPlan *__restrict__ plan, int32_t *__restrict__ labels,
-                                                           int64_t *__restrict__ stats) {
-    if (!plan->by_sort) return;   // uniform over the grid
-    __shared__ long long cumf[256];
-    cumf[threadIdx.x] = (int)threadIdx.x < k ? plan->cumf[threadIdx.x] : plan->F;
-    __syncthreads();
-    const uint64_t F = (uint64_t)plan->F, magic = magic_of(F);
-    unsigned long long moved_total = 0;
-    const int64_t padded = (n + kBlock - 1) / kBlock * kBlock;   // every lane of a wave takes the same number of turns
-    for (int64_t pos = (int64_t)blockIdx.x * kBlock + threadIdx.x; pos < padded; pos += (int64_t)gridDim.x * kBlock) {
-        int moved = 0;
-        if (pos < n) {
-            const int32_t v = order[pos];
-            const uint32_t part = (uint32_t)keys[v] >> 24;
-            if (part < (uint32_t)k && pos - plan->seg[part] < plan->m[part]) {
-                const uint64_t r = mod_by(draw64(seed, (uint32_t)plan->round, v), F, magic);
-                int lo = 0, hi = k - 1;               // first partition whose running sum exceeds r
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if ((uint64_t)cumf[mid] > r) hi = mid; else lo = mid + 1;
-                }
-                labels[v] = lo;
-                moved = 1;
-            }
-        }
-        const unsigned long long b = __ballot(moved);
-        if ((threadIdx.x & 63) == 0) moved_total += (unsigned long long)__popcll(b);
-    }
-    if ((threadIdx.x & 63) == 0 && moved_total)
-        atomicAdd(reinterpret_cast<unsigned long long *>(stats + 1), moved_total);
-}
 
 // Pass 3: the move.  A member of degree t_l moves iff fewer than need_l such members of its partition come
 // before it by id: the count before its range, plus the ordered count inside the range (tiles of 256 vertices:
@@ -379,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
         int64_t deg = 0;
         if (v < e && (!vclass || cq == class_id) && lab >= 0 && lab < k && tdeg[lab] >= 0) {
             l = lab;
-            deg = (int64_t)(hi - lo);
+            deg = std::min<int64_t>((int64_t)(hi - lo), (int64_t)kDegreeMask);
         }
         fetch(v + kBlock);
         const bool at_threshold = l >= 0 && deg == (int64_t)tdeg[l];
@@ -431,7 +462,7 @@ __global__ __launch_bounds__(kBlock) void bal_select_move_kernel(int64_t n, int3
 // their moves, and it stops at the first round that finds nothing overloaded.  The threshold degree is found by
 // selection at any size: if it lies beyond the exact bins, the range that holds it is counted again with
 // narrower bins until the bins are one degree wide (at most five passes up to degree 2^24 - 1, the value
-// degrees are clamped to here as in the sort keys above).  Same movers and same draws as the chain above.
+// degrees are clamped to, as in the chain above).  Same movers and same draws as the chain above.
 __device__ __forceinline__ void wave_lds_fence_() {   // orders a wave's own LDS accesses
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -699,10 +730,6 @@ BalanceWs carve_balance_ws(int64_t n, void *ws) {
     Carver c(ws);
     BalanceWs w{};
     w.plan = c.take<unsigned char>(sizeof(BalPlan));
-    w.keys = c.take<int32_t>((size_t)n);
-    w.order = c.take<int32_t>((size_t)n);
-    w.tmp = c.take<int32_t>((size_t)n);
-    w.sort_hist = c.take<int32_t>(sort_hist_elems());
     w.degree_hist = c.take<uint32_t>(kHistCounters);
     w.tie = c.take<int32_t>((size_t)kSelBlocksMax * 256);
     w.bytes = align_up(c.used, 256);
@@ -724,9 +751,8 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
         return EP_OK;
     }
     BalPlan *plan = reinterpret_cast<BalPlan *>(w.plan);
-    const unsigned per_vertex = (unsigned)std::min<int64_t>(ceil_div(n, kBlock), 4096);   // grid-stride kernels
     const unsigned count_blocks = (unsigned)std::min<int64_t>(2048, ceil_div(n, kBlock * 8));
-    const int bins = degree_bins(k), cells = k * bins;
+    const int bins = degree_bins(k), cells = k * bins, levels = refine_levels(bins);
     int64_t rows_per_block = std::max<int64_t>(ceil_div(n, kSelBlocksMax), 4 * kBlock);
     rows_per_block = ceil_div(rows_per_block, kBlock) * kBlock;
     const int sel_blocks = (int)ceil_div(n, rows_per_block);
@@ -747,7 +773,19 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
         bal_plan_kernel<<<1, 256, 0, s>>>(k, bins, beta, r < max_rounds, plan, w.degree_hist, stats);
         EP_LAUNCH_CHECK();
         if (r == max_rounds) break;   // the closing evaluation only reports what is still overloaded
-        // selection (the usual way) ...
+        // a threshold degree in the last histogram bin is narrowed down first (no-ops otherwise)
+        for (int level = 1; level <= levels; ++level) {
+            const int64_t width = refine_width(bins, level);
+            by_width([&](auto *rp) {
+                bal_refine_count_kernel<<<count_blocks, kBlock, 0, s>>>(n, k, bins, width, rp, vclass, class_id, labels, plan,
+                                                                        w.degree_hist);
+                return 0;
+            });
+            EP_LAUNCH_CHECK();
+            bal_refine_plan_kernel<<<1, 256, 0, s>>>(k, bins, width, plan, w.degree_hist);
+            EP_LAUNCH_CHECK();
+        }
+        // selection: members below the threshold degree move, and the first need_i (by id) at it
         by_width([&](auto *rp) {
             bal_tie_count_kernel<<<sel_blocks, kBlock, 0, s>>>(n, k, rows_per_block, rp, vclass, class_id, labels, plan, w.tie);
             return 0;
@@ -760,18 +798,6 @@ int launch_balance(int64_t n, int32_t k, const void *rowptr, bool i64, const uin
                                                                  w.tie, labels, stats);
             return 0;
         });
-        EP_LAUNCH_CHECK();
-        // ... or, if a threshold degree fell into the last histogram bin, the sort (every kernel reads by_sort)
-        by_width([&](auto *rp) {
-            bal_keys_kernel<<<per_vertex, kBlock, 0, s>>>(n, k, rp, vclass, class_id, labels, plan, w.keys);
-            return 0;
-        });
-        EP_LAUNCH_CHECK();
-        int rc = launch_sort_by_key(n, 4, w.keys, nullptr, w.order, w.tmp, w.sort_hist, &plan->by_sort, s);
-        if (rc != EP_OK) return rc;
-        bal_segments_kernel<<<(unsigned)std::min<int64_t>(ceil_div(n + 1, kBlock), 4096), kBlock, 0, s>>>(n, w.keys, w.order, plan);
-        EP_LAUNCH_CHECK();
-        bal_move_kernel<<<per_vertex, kBlock, 0, s>>>(n, k, seed, w.keys, w.order, plan, labels, stats);
         EP_LAUNCH_CHECK();
     }
     return EP_OK;

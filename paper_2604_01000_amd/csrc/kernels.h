@@ -231,11 +231,7 @@ int launch_edge_gap(int64_t n, int64_t nnz, const void *rowptr, bool i64, const 
 
 // ---- balancing (balance.hip) -------------------------------------------------------
 struct BalanceWs {
-    unsigned char *plan;  // per-round plan (loads, moves, free capacities, segment starts)
-    int32_t *keys;        // [n]
-    int32_t *order;       // [n]
-    int32_t *tmp;         // [n]
-    int32_t *sort_hist;
+    unsigned char *plan;  // per-round plan (loads, moves, free capacities, threshold degrees)
     uint32_t *degree_hist;   // [k * bins] class members per partition and degree
     int32_t *tie;            // per vertex range and partition: members at the threshold degree
     size_t bytes;

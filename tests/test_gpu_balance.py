@@ -51,12 +51,13 @@ def test_balance_equals_oracle(n, k, beta, rounds, i64):
 
 
 @pytest.mark.parametrize("n,k,lo,hi", [(30_011, 200, 90, 400), (20_000, 8, 250, 3_000), (25_000, 64, 0, 600),
-                                      (6_000, 3, 100_000, 2_000_000), (270_000, 8, 250, 3_000), (300_000, 200, 60, 400)])
+                                      (6_000, 3, 100_000, 2_000_000), (270_000, 8, 250, 3_000), (300_000, 200, 60, 400),
+                                      (270_001, 3, 100_000, 2_000_000), (263_000, 64, 0, 16_000_000)])
 def test_balance_with_large_degrees_equals_oracle(n, k, lo, hi):
-    """Degrees beyond the exact bins of the degree histogram.  Up to 2^18 vertices the range that holds the
-    threshold degree is counted again with narrower bins; beyond, the rounds whose threshold degree lies in the
-    last bin (min(256, 16384 / k) - 1 and up) take the sorting path, the others the selection.  All must pick
-    the oracle's movers.  (Degrees stay below 2^24, beyond which the device treats them as equal.)"""
+    """Degrees beyond the exact bins of the degree histogram (min(256, 16384 / k) - 1 and up share the last bin):
+    the range that holds the threshold degree is counted again with narrower bins, inside the one launch of the
+    small graphs and as further launches of the chain beyond 2^18 vertices, until it is one degree wide.  All must
+    pick the oracle's movers.  (Degrees stay below 2^24, beyond which the device treats them as equal.)"""
     rng = np.random.default_rng(n + k)
     deg = rng.integers(lo, hi, n).astype(np.int64)
     deg[rng.random(n) < 0.3] = rng.integers(0, 30, n)[: int((rng.random(n) < 0.3).sum())][0]   # and a block of small ones
