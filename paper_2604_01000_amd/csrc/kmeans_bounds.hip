@@ -123,15 +123,30 @@ __global__ __launch_bounds__(kBlock) void bounds_compact_kernel(int64_t n, int64
         *n_active = total;
         *searched_slot = total;
     }
-    for (int64_t tile = b; tile < e; tile += kBlock) {
-        const int64_t i = tile + threadIdx.x;
-        const bool active = i < e && (__float_as_uint(ub[i]) >> 31) != 0;   // marked by bounds_update_kernel
-        const uint64_t mask = __ballot(active);
-        if ((threadIdx.x & 63) == 0) wave_cnt[wave] = __popcll(mask);
+    // Four consecutive points per thread (one 16-byte load; the range starts on a multiple of 256 points, and what
+    // a load reads past the last point lies inside the workspace and is not looked at): a quarter of the barriers.
+    for (int64_t tile = b; tile < e; tile += 4 * kBlock) {
+        const int64_t i0 = tile + 4 * threadIdx.x;
+        const u32x4 u4 = *reinterpret_cast<const u32x4 *>(ub + (i0 < e ? i0 : b));   // always a position of the range
+        bool active[4];
+        uint64_t mask[4];
+        int before_lanes = 0, mine = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            active[q] = i0 + q < e && (u4[q] >> 31) != 0;   // marked by bounds_update_kernel
+            mask[q] = __ballot(active[q]);
+            before_lanes += __popcll(mask[q] & lanes_below());
+        }
+        if ((threadIdx.x & 63) == 0)
+            wave_cnt[wave] = __popcll(mask[0]) + __popcll(mask[1]) + __popcll(mask[2]) + __popcll(mask[3]);
         __syncthreads();
-        int64_t pos = running + __popcll(mask & lanes_below());
+        int64_t pos = running + before_lanes;
         for (int w = 0; w < wave; ++w) pos += wave_cnt[w];
-        if (active) active_idx[pos] = (int32_t)i;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (active[q]) active_idx[pos + mine] = (int32_t)(i0 + q);
+            mine += active[q] ? 1 : 0;
+        }
         running += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
         __syncthreads();
     }
