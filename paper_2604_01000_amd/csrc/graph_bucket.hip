@@ -11,7 +11,7 @@
 // and, in two pieces, 128 KB (LDS):
 //   bucket_hist_kernel     entries per bucket (one streaming read of colidx)
 //   bucket_scan_kernel     bucket offsets (each bucket starts on a 128-byte line), work items of the last pass
-//   bucket_scatter_kernel  streams colidx with its rows' labels (64-row windows as in the plain sweep) and
+//   bucket_scatter_kernel  streams colidx with its rows' labels (128-row windows, otherwise as in the plain sweep) and
 //                          writes one 32-bit record per entry, (v - bucket start) | pid(u) << shift, to
 //                          the entry's bucket: a workgroup sorts a tile of 8,192 entries by bucket in LDS and
 //                          every bucket's run leaves as a contiguous stream of whole 64-byte blocks, its place
@@ -101,7 +101,7 @@ __global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long
 
 // A workgroup gathers a tile of up to kTile entries, sorts it by bucket in LDS and writes every bucket's run
 // to the bucket's next free slots, reserved with one integer atomic per bucket and tile.
-//   phase A  every wave streams its rows' entries (64-row windows as in edge_block_sweep_kernel, 256 entries
+//   phase A  every wave streams its rows' entries (128-row windows, otherwise as in edge_block_sweep_kernel, 256 entries
 //            per step, kTileSteps steps, the next step's entries in flight); an entry takes its rank inside
 //            its bucket from an LDS counter and stays in registers as (record, bucket | rank)
 //   phase B  the counters are scanned (start of every bucket's run inside the tile) and thread b reserves the
@@ -109,6 +109,7 @@ __global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long
 //   phase C  the records go to their sorted place in LDS, then every run leaves as one contiguous stream
 constexpr int kScatterBlock = 1024;
 constexpr int kScatterWaves = kScatterBlock / 64;
+constexpr int kWindowRows = 128;   // rows per window of a wave: two per lane (a new window costs two memory latencies)
 constexpr int kTileSteps = 4;
 constexpr int kTile = kScatterWaves * kTileSteps * 256;
 
@@ -125,8 +126,8 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     __shared__ int32_t tile_cnt[kBucketsMax];        // entries of the tile per bucket
     __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
     __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
-    __shared__ int64_t rp_lds[kScatterWaves][66];
-    __shared__ int32_t au_lds[kScatterWaves][64];
+    __shared__ int64_t rp_lds[kScatterWaves][kWindowRows + 2];
+    __shared__ int32_t au_lds[kScatterWaves][kWindowRows];
     __shared__ int32_t wave_total[kScatterWaves];
     __shared__ int32_t any_work;
     // Records of earlier tiles that did not fill a whole 64-byte block of their bucket wait here for the next
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int64_t *rp = rp_lds[wave];
     int32_t *aus = au_lds[wave];
-    const int64_t row_blocks = (n + 63) / 64;
+    const int64_t row_blocks = (n + kWindowRows - 1) / kWindowRows;
     const int64_t rb_stride = (int64_t)gridDim.x * kScatterWaves;
     for (int b = threadIdx.x; b < kBucketsMax; b += kScatterBlock) {
         tile_cnt[b] = 0;
@@ -175,13 +176,17 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, 16 * lane, 0, 0));
     };
     // The offsets and labels of the wave's next row block are fetched one block ahead, into registers.
-    int64_t nrp = 0, nrp_end = 0;
-    int32_t nau = 255;
+    constexpr int kPerLane = kWindowRows / 64;
+    int64_t nrp[kPerLane], nrp_end = 0;
+    int32_t nau[kPerLane];
     auto fetch_block = [&](int64_t b) {   // unconditional: rows past the graph read the last offset / a valid label
-        const int64_t r0 = min(b, row_blocks) * 64;
-        nrp = (int64_t)rowptr[min(r0 + lane, n)];
-        nrp_end = (int64_t)rowptr[min(r0 + 64, n)];
-        nau = (int32_t)label8[min(r0 + lane, n - 1)];
+        const int64_t r0 = min(b, row_blocks) * kWindowRows;
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q) {
+            nrp[q] = (int64_t)rowptr[min(r0 + 64 * q + lane, n)];
+            nau[q] = (int32_t)label8[min(r0 + 64 * q + lane, n - 1)];
+        }
+        nrp_end = (int64_t)rowptr[min(r0 + kWindowRows, n)];
     };
     fetch_block(rb + rb_stride);
     // the next row block of this wave that has entries; false when the wave has none left
@@ -192,18 +197,21 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 p0 = e_begin = e_end = 0;
                 return false;
             }
-            const int64_t r0 = rb * 64;
+            const int64_t r0 = rb * kWindowRows;
             wave_fence();   // the window of the previous block is no longer read
-            rp[lane] = min(max(nrp, (int64_t)0), nnz);
-            if (lane == 0) rp[64] = min(max(nrp_end, (int64_t)0), nnz);
-            aus[lane] = r0 + lane < n ? nau : 255;
+#pragma unroll
+            for (int q = 0; q < kPerLane; ++q) {
+                rp[64 * q + lane] = min(max(nrp[q], (int64_t)0), nnz);
+                aus[64 * q + lane] = r0 + 64 * q + lane < n ? nau[q] : 255;
+            }
+            if (lane == 0) rp[kWindowRows] = min(max(nrp_end, (int64_t)0), nnz);
             // (the old values are used up before the new loads are issued: loaded into other registers first, they
             // would have to be copied, and a copy waits for its load)
             __builtin_amdgcn_sched_barrier(0);
             fetch_block(rb + rb_stride);
             wave_fence();
             e_begin = rp[0];
-            e_end = rp[64];
+            e_end = rp[kWindowRows];
             p0 = e_begin & ~(int64_t)3;
             if (e_end > e_begin) {
                 ahead = load4(p0);
@@ -231,17 +239,17 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 {
                     const int64_t q = max(p, e_begin);
 #pragma unroll
-                    for (int step = 32; step > 0; step >>= 1)
+                    for (int step = kWindowRows / 2; step > 0; step >>= 1)
                         if (rp[j + step] <= q) j += step;
                 }
-                int64_t row_end = rp[min(j + 1, 64)];
-                uint32_t lu = (uint32_t)aus[min(j, 63)];
+                int64_t row_end = rp[min(j + 1, kWindowRows)];
+                uint32_t lu = (uint32_t)aus[min(j, kWindowRows - 1)];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int64_t pe = p + t;
                     const bool live = pe >= e_begin && pe < e_end;
                     if (live) {
-                        while (pe >= row_end) {   // ends: pe < e_end = rp[64]
+                        while (pe >= row_end) {   // ends: pe < e_end = rp[kWindowRows]
                             ++j;
                             row_end = rp[j + 1];
                             lu = (uint32_t)aus[j];
@@ -444,7 +452,7 @@ int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void
     const unsigned hgrid = (unsigned)std::min<int64_t>(ceil_div(nnz / 4 + 1, kBlock * 8), 256 * 8);
     bucket_hist_kernel<<<hgrid, kBlock, 0, s>>>(n, nnz, pl.shift, pl.nb, colidx, hist);
     EP_LAUNCH_CHECK();
-    const int64_t row_blocks = ceil_div(n, 64);
+    const int64_t row_blocks = ceil_div(n, kWindowRows);
     const unsigned sgrid = (unsigned)std::min<int64_t>(ceil_div(row_blocks, kScatterWaves), kScatterGridMax);
     bucket_scan_kernel<<<1, 64, 0, s>>>(pl.nb, (int)sgrid, hist, w.bucket_base, cursor, w.bucket_items);
     EP_LAUNCH_CHECK();
