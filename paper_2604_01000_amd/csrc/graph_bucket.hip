@@ -381,16 +381,28 @@ __global__ __launch_bounds__(kSweepBlock) void bucket_sweep_kernel(int64_t n, in
         for (int piece = 0; piece < pieces; ++piece) {
             __syncthreads();   // the previous piece is no longer read
             const int64_t p0 = v0 + ((int64_t)piece << kSliceShift);
-            for (int i = threadIdx.x; i < (1 << kSliceShift) / 16; i += kSweepBlock) {
-                const int64_t g = p0 + 16 * (int64_t)i;
-                u32x4 val = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
-                if (g + 15 < n) {
-                    val = *reinterpret_cast<const u32x4 *>(label8 + g);
-                } else {
-                    for (int e = 0; e < 16; ++e)
-                        if (g + e < n) reinterpret_cast<uint8_t *>(&val)[e] = label8[g + e];
+            {   // the piece's label bytes, two 16-byte loads of a thread in flight at a time, through a buffer descriptor
+                // that ends at the word holding the last vertex (the range check works on whole words: a word cut
+                // short would read as zero; the label array is followed by 256-byte aligned arrays of the same
+                // workspace, and no record names a vertex past the last; words beyond the end read as zeros)
+                constexpr int kLoads = (1 << kSliceShift) / 16 / kSweepBlock;
+                static_assert(kLoads * kSweepBlock * 16 == (1 << kSliceShift), "whole loads per thread");
+                const int64_t left = n - p0;
+                const int bytes = left <= 0 ? 0 : (int)min((left + 3) & ~(int64_t)3, (int64_t)1 << kSliceShift);
+                __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint8_t *>(label8 + (left <= 0 ? 0 : p0)), 0, bytes, 0x00020000);
+                constexpr int kBatch = 2;   // (more at once do not fit beside the 96 records of a thread)
+                static_assert(kLoads % kBatch == 0, "whole batches");
+#pragma unroll
+                for (int q0 = 0; q0 < kLoads; q0 += kBatch) {
+                    u32x4 val[kBatch];
+#pragma unroll
+                    for (int q = 0; q < kBatch; ++q)
+                        val[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, 16 * (int)(threadIdx.x + (q0 + q) * kSweepBlock), 0, 0);
+#pragma unroll
+                    for (int q = 0; q < kBatch; ++q)
+                        reinterpret_cast<u32x4 *>(slice)[threadIdx.x + (q0 + q) * kSweepBlock] = val[q];
                 }
-                reinterpret_cast<u32x4 *>(slice)[i] = val;
             }
             __syncthreads();
 #pragma unroll
