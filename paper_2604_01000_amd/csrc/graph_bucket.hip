@@ -189,6 +189,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         nrp_end = (int64_t)rowptr[min(r0 + kWindowRows, n)];
     };
     fetch_block(rb + rb_stride);
+    const int64_t my_limit = (int)threadIdx.x < nb ? base[threadIdx.x + 1] : 0;   // end of the bucket thread t reserves in
     // the next row block of this wave that has entries; false when the wave has none left
     auto next_block = [&]() -> bool {
         for (;;) {
@@ -270,8 +271,13 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         __syncthreads();
         if (!any_work) break;   // uniform over the workgroup: no wave had a step
         // ---- phase B: exclusive scan of tile_cnt[0 .. nb), one counter per thread; reservations ----
+        // The reservation of thread t's bucket is one integer atomic per bucket and tile; all of a tile's are in
+        // flight together, and their answers (a round trip to the memory side) are looked at only after the
+        // records have been sorted in LDS: the barriers in between wait for LDS traffic alone.
+        const int t = threadIdx.x;
+        unsigned long long pos = 0;
+        int my_out = 0;
         {
-            const int t = threadIdx.x;
             const int cnt = t < nb ? tile_cnt[t] : 0;
             int incl = cnt;
 #pragma unroll
@@ -280,20 +286,18 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 if (lane >= off) incl += up;
             }
             if (lane == 63) wave_total[wave] = incl;
-            const int out = t < nb ? ((resid_cnt[t] + cnt) & ~(kAlign - 1)) : 0;   // whole blocks of waiting + new records
-            int64_t dest = -1;
-            if (out > 0) {   // one integer atomic per bucket and tile; all of them in flight together
-                const unsigned long long pos = atomicAdd(&cursor[t * kCursorStride], (unsigned long long)out);
-                if ((int64_t)pos + out <= base[t + 1]) dest = (int64_t)pos;   // never write past a bucket
-                else lost += (unsigned long long)out;
-            }
+            my_out = t < nb ? ((resid_cnt[t] + cnt) & ~(kAlign - 1)) : 0;   // whole blocks of waiting + new records
+            if (my_out > 0) pos = atomicAdd(&cursor[t * kCursorStride], (unsigned long long)my_out);
             __syncthreads();
+            // every thread has read its counter and the flag: both start the next tile at zero (the barrier below
+            // orders this before any wave's next phase A)
+            if (t < kBucketsMax) tile_cnt[t] = 0;
+            if (t == 0) any_work = 0;
             int before = 0;
             for (int w = 0; w < wave; ++w) before += wave_total[w];
             if (t < nb) {
                 run_start[t] = before + incl - cnt;
-                run_dest[t] = dest;
-                run_out[t] = out;
+                run_out[t] = my_out;
             }
             if (t == kScatterBlock - 1) run_start[nb] = before + incl;   // nb <= kScatterBlock: the total
         }
@@ -302,6 +306,12 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 #pragma unroll
         for (int i = 0; i < kTileSteps * 4; ++i)
             if (where[i] != 0xffffffffu) sorted[run_start[where[i] & 511u] + (int)(where[i] >> 9)] = rec[i];
+        {   // (straight-line code: the one wait for the answer sits on every path, and the write-out below, whose
+            // stores must stay in flight from turn to turn, is not made to wait for it again)
+            const bool fits = (int64_t)pos + my_out <= my_limit;   // never write past a bucket
+            lost += (my_out > 0 && !fits) ? (unsigned long long)my_out : 0ull;
+            run_dest[min(t, kBucketsMax - 1)] = (my_out > 0 && fits) ? (int64_t)pos : (int64_t)-1;
+        }
         __syncthreads();
         // Four buckets per wave and turn, 16 lanes each: a run of this size is one or two 64-byte blocks, and a
         // whole wave per bucket spent most of its instructions on lanes with nothing to write.
@@ -326,10 +336,10 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 if (li == 0) resid_cnt[b] = keep;
             }
         }
-        __syncthreads();
-        for (int b = threadIdx.x; b < nb; b += kScatterBlock) tile_cnt[b] = 0;
-        if (threadIdx.x == 0) any_work = 0;
-        __syncthreads();
+        // No barrier here: a wave that is done writing goes on to gather its part of the next tile.  What the next
+        // tile shares with this write-out is touched only behind its first barrier (`sorted` and the run tables
+        // two and three barriers on, resid_cnt of another wave's buckets in phase B), which every wave reaches
+        // after its own write-out; the waiting records of a bucket stay with the same wave from tile to tile.
     }
     // what still waits leaves as one block per bucket, filled up with records that count for nothing
     for (int b = wave; b < nb; b += kScatterWaves) {
