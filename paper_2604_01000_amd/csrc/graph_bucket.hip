@@ -101,9 +101,10 @@ __global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long
 
 // A workgroup gathers a tile of up to kTile entries, sorts it by bucket in LDS and writes every bucket's run
 // to the bucket's next free slots, reserved with one integer atomic per bucket and tile.
-//   phase A  every wave streams its rows' entries (128-row windows, otherwise as in edge_block_sweep_kernel, 256 entries
-//            per step, kTileSteps steps, the next step's entries in flight); an entry takes its rank inside
-//            its bucket from an LDS counter and stays in registers as (record, bucket | rank)
+//   phase A  every wave streams its rows' entries (blocks of 128 rows, 256 entries per step, kTileSteps steps, the
+//            next step's entries and the next block's offsets and labels in flight); an entry finds its row through
+//            marks at the rows' first entries and a running maximum, takes its rank inside its bucket from an
+//            LDS counter and stays in registers as (record, bucket | rank)
 //   phase B  the counters are scanned (start of every bucket's run inside the tile) and thread b reserves the
 //            run of bucket b in the record buffer
 //   phase C  the records go to their sorted place in LDS, then every run leaves as one contiguous stream
@@ -122,11 +123,12 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                                                                         unsigned long long *__restrict__ cursor,
                                                                         uint32_t *__restrict__ records,
                                                                         unsigned long long *__restrict__ dropped) {
-    static_assert(kBucketsMax <= kScatterBlock, "one thread per bucket in the scan of a tile");
-    __shared__ int32_t tile_cnt[kBucketsMax];        // entries of the tile per bucket
+    static_assert(kBucketsMax + 64 <= kScatterBlock, "one thread per bucket in the scan of a tile");
+    __shared__ int32_t tile_cnt[kBucketsMax + 64];   // entries of the tile per bucket (+ one word per lane for entries
+                                                     // that count for nothing: their rank is asked for all the same)
     __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
     __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
-    __shared__ int64_t rp_lds[kScatterWaves][kWindowRows + 2];
+    __shared__ __attribute__((aligned(16))) int32_t mark_lds[kScatterWaves][256];   // per step: row number + 1 at a row's first entry
     __shared__ int32_t au_lds[kScatterWaves][kWindowRows];
     __shared__ int32_t wave_total[kScatterWaves];
     __shared__ int32_t any_work;
@@ -140,13 +142,13 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     __shared__ int32_t run_out[kBucketsMax];         // records of (waiting + run) that leave with this tile
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int64_t *rp = rp_lds[wave];
+    int32_t *mk = mark_lds[wave];
     int32_t *aus = au_lds[wave];
     const int64_t row_blocks = (n + kWindowRows - 1) / kWindowRows;
     const int64_t rb_stride = (int64_t)gridDim.x * kScatterWaves;
-    for (int b = threadIdx.x; b < kBucketsMax; b += kScatterBlock) {
+    for (int b = threadIdx.x; b < kBucketsMax + 64; b += kScatterBlock) {
         tile_cnt[b] = 0;
-        resid_cnt[b] = 0;
+        if (b < kBucketsMax) resid_cnt[b] = 0;
     }
     if (threadIdx.x == 0) any_work = 0;
     __syncthreads();
@@ -190,6 +192,12 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     };
     fetch_block(rb + rb_stride);
     const int64_t my_limit = (int)threadIdx.x < nb ? base[threadIdx.x + 1] : 0;   // end of the bucket thread t reserves in
+    // The current block: the first entry of this lane's rows (row 64 q + lane of the block), and the number + 1 of
+    // the last row that starts before the step at p0 (0: none yet).
+    int64_t crp[kPerLane];
+    uint32_t carry = 0;
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) crp[q] = 0;
     // the next row block of this wave that has entries; false when the wave has none left
     auto next_block = [&]() -> bool {
         for (;;) {
@@ -199,21 +207,22 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 return false;
             }
             const int64_t r0 = rb * kWindowRows;
-            wave_fence();   // the window of the previous block is no longer read
+            wave_fence();   // the labels of the previous block are no longer read
 #pragma unroll
             for (int q = 0; q < kPerLane; ++q) {
-                rp[64 * q + lane] = min(max(nrp[q], (int64_t)0), nnz);
+                crp[q] = min(max(nrp[q], (int64_t)0), nnz);
                 aus[64 * q + lane] = r0 + 64 * q + lane < n ? nau[q] : 255;
             }
-            if (lane == 0) rp[kWindowRows] = min(max(nrp_end, (int64_t)0), nnz);
+            const int64_t block_end = min(max(nrp_end, (int64_t)0), nnz);
             // (the old values are used up before the new loads are issued: loaded into other registers first, they
             // would have to be copied, and a copy waits for its load)
             __builtin_amdgcn_sched_barrier(0);
             fetch_block(rb + rb_stride);
             wave_fence();
-            e_begin = rp[0];
-            e_end = rp[kWindowRows];
+            e_begin = uniform64(crp[0]);   // lane 0 holds the block's first row
+            e_end = uniform64(block_end);
             p0 = e_begin & ~(int64_t)3;
+            carry = 0;
             if (e_end > e_begin) {
                 ahead = load4(p0);
                 return true;
@@ -236,33 +245,47 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 const int64_t p = p0 + 4 * lane;
                 const i32x4 c = ahead;
                 ahead = load4(p0 + 256);   // the next step of this block, in flight while this one is ranked
-                int j = 0;
-                {
-                    const int64_t q = max(p, e_begin);
+                // The row of every entry without a search: rows that start inside the step leave their number + 1
+                // at their first entry's place (of several rows at one place, all but the last are empty: the
+                // largest number wins), and a running maximum over the step's 256 places, carried on from the
+                // steps before, is the number + 1 of the last row that starts at or before a place.
+                wave_fence();   // the previous step's marks have been read
+                *reinterpret_cast<i32x4 *>(&mk[4 * lane]) = i32x4{0, 0, 0, 0};
+                wave_fence();
 #pragma unroll
-                    for (int step = kWindowRows / 2; step > 0; step >>= 1)
-                        if (rp[j + step] <= q) j += step;
+                for (int q = 0; q < kPerLane; ++q) {
+                    const int64_t s = crp[q] - p0;
+                    if (s >= 0 && s < 256) atomicMax(&mk[(int)s], 64 * q + lane + 1);   // integer, LDS
                 }
-                int64_t row_end = rp[min(j + 1, kWindowRows)];
-                uint32_t lu = (uint32_t)aus[min(j, kWindowRows - 1)];
+                wave_fence();
+                const i32x4 m = *reinterpret_cast<const i32x4 *>(&mk[4 * lane]);
+                uint32_t upto[4];   // running maximum inside the lane's four places
+                upto[0] = (uint32_t)m[0];
+#pragma unroll
+                for (int t = 1; t < 4; ++t) upto[t] = max(upto[t - 1], (uint32_t)m[t]);
+                const uint32_t incl = wave_inclusive_max(upto[3]);
+                uint32_t before = (uint32_t)__shfl_up((int)incl, 1, 64);   // the lanes before this one
+                before = max(lane == 0 ? 0u : before, carry);
+                carry = max(carry, (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
+                uint32_t lu[4];
+                int bucket[4];
+                bool ok[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
+                    const int row = (int)max(before, upto[t]) - 1;   // -1 only before the block's first entry
+                    lu[t] = (uint32_t)aus[min(max(row, 0), kWindowRows - 1)];
                     const int64_t pe = p + t;
-                    const bool live = pe >= e_begin && pe < e_end;
-                    if (live) {
-                        while (pe >= row_end) {   // ends: pe < e_end = rp[kWindowRows]
-                            ++j;
-                            row_end = rp[j + 1];
-                            lu = (uint32_t)aus[j];
-                        }
-                    }
                     const int32_t v = c[t];
-                    if (live && v >= 0 && v < n) {
-                        const int b = v >> shift;
-                        const int rank = atomicAdd(&tile_cnt[b], 1);   // integer, LDS: the order inside a run is free
-                        rec[4 * st + t] = ((uint32_t)v & ((1u << shift) - 1u)) | (lu << shift);
-                        where[4 * st + t] = (uint32_t)b | ((uint32_t)rank << 9);
-                    }
+                    ok[t] = pe >= e_begin && pe < e_end && v >= 0 && v < n;
+                    bucket[t] = ok[t] ? (int)(v >> shift) : kBucketsMax + lane;
+                }
+                int rank[4];   // all four asked for at once (integer, LDS: the order inside a run is free)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) rank[t] = atomicAdd(&tile_cnt[bucket[t]], 1);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    rec[4 * st + t] = ((uint32_t)c[t] & ((1u << shift) - 1u)) | (lu[t] << shift);
+                    where[4 * st + t] = ok[t] ? ((uint32_t)bucket[t] | ((uint32_t)rank[t] << 9)) : 0xffffffffu;
                 }
                 p0 += 256;
             }
@@ -291,7 +314,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
             __syncthreads();
             // every thread has read its counter and the flag: both start the next tile at zero (the barrier below
             // orders this before any wave's next phase A)
-            if (t < kBucketsMax) tile_cnt[t] = 0;
+            if (t < kBucketsMax + 64) tile_cnt[t] = 0;
             if (t == 0) any_work = 0;
             int before = 0;
             for (int w = 0; w < wave; ++w) before += wave_total[w];

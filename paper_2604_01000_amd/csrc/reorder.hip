@@ -223,20 +223,6 @@ __global__ __launch_bounds__(kBlock) void reorder_window_rows_kernel(int64_t n, 
     window_rows[b] = pos >= nnz ? n : first_row_at_or_after(new_rowptr, n, pos);
 }
 
-// Inclusive running maximum over the 64 lanes, on the data-parallel-primitive paths (no LDS):
-// shifts by 1, 2, 4, 8 inside rows of 16 lanes, then the last lane of row 0 / 2 into rows 1 / 3 and
-// the last lane of row 1 into rows 2 and 3.  Lanes without a source see 0 (the values are unsigned).
-__device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v) {
-    auto fold = [&](uint32_t other) { v = other > v ? other : v; };
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true));    // row_shr:1
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true));    // row_shr:2
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true));    // row_shr:4
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true));    // row_shr:8
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false));   // row_bcast:15 into rows 1, 3
-    fold((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false));   // row_bcast:31 into rows 2, 3
-    return v;
-}
-
 // ---- all short rows of a window sorted at once -------------------------------------------------
 // Every row gets a region of 2^p slots, p = ceil(log2(length)), filled up with +infinity.  The
 // regions are laid out by descending p, so every region is aligned to its own size and the slots
