@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
     __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
     __shared__ __attribute__((aligned(16))) int32_t mark_lds[kScatterWaves][256];   // per step: row number + 1 at a row's first entry
-    __shared__ int32_t au_lds[kScatterWaves][kWindowRows];
+    __shared__ int32_t au_lds[kScatterWaves][kWindowRows + 1];   // [0]: for places before the block's first entry
     __shared__ int32_t wave_total[kScatterWaves];
     __shared__ int32_t any_work;
     // Records of earlier tiles that did not fill a whole 64-byte block of their bucket wait here for the next
@@ -144,6 +144,9 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int32_t *mk = mark_lds[wave];
     int32_t *aus = au_lds[wave];
+    const uint32_t n_ids = (uint32_t)min(n, (int64_t)1 << 31);          // a column c is a vertex iff (uint32_t)c < n_ids
+    const uint32_t scrap_v = (uint32_t)(kBucketsMax + lane) << shift;   // "vertex" of the lane's own spare counter
+    static_assert(kBucketsMax + 64 <= 1024, "bucket numbers, the spare ones included, take 10 bits of `where`");
     const int64_t row_blocks = (n + kWindowRows - 1) / kWindowRows;
     const int64_t rb_stride = (int64_t)gridDim.x * kScatterWaves;
     for (int b = threadIdx.x; b < kBucketsMax + 64; b += kScatterBlock) {
@@ -211,8 +214,9 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 #pragma unroll
             for (int q = 0; q < kPerLane; ++q) {
                 crp[q] = min(max(nrp[q], (int64_t)0), nnz);
-                aus[64 * q + lane] = r0 + 64 * q + lane < n ? nau[q] : 255;
+                aus[1 + 64 * q + lane] = r0 + 64 * q + lane < n ? nau[q] : 255;
             }
+            if (lane == 0) aus[0] = 255;
             const int64_t block_end = min(max(nrp_end, (int64_t)0), nnz);
             // (the old values are used up before the new loads are issued: loaded into other registers first, they
             // would have to be copied, and a copy waits for its load)
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 
     for (;;) {
         // ---- phase A ----
-        uint32_t rec[kTileSteps * 4], where[kTileSteps * 4];   // where = bucket | rank << 9; 0xffffffff: no entry
+        uint32_t rec[kTileSteps * 4], where[kTileSteps * 4];   // where = bucket | rank << 10; bucket >= kBucketsMax: no entry
         bool worked = false;
 #pragma unroll
         for (int st = 0; st < kTileSteps; ++st) {
@@ -242,7 +246,6 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
             for (int t = 0; t < 4; ++t) where[4 * st + t] = 0xffffffffu;
             if (have) {   // uniform over the wave
                 worked = true;
-                const int64_t p = p0 + 4 * lane;
                 const i32x4 c = ahead;
                 ahead = load4(p0 + 256);   // the next step of this block, in flight while this one is ranked
                 // The row of every entry without a search: rows that start inside the step leave their number + 1
@@ -267,25 +270,25 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                 uint32_t before = (uint32_t)__shfl_up((int)incl, 1, 64);   // the lanes before this one
                 before = max(lane == 0 ? 0u : before, carry);
                 carry = max(carry, (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
-                uint32_t lu[4];
-                int bucket[4];
-                bool ok[4];
+                // Which of the lane's places 4 lane + t hold entries of the block: lo <= place < hi, wave-uniform.
+                const int lo = (int)min(max(e_begin - p0, (int64_t)0), (int64_t)256);
+                const int hi = (int)min(max(e_end - p0, (int64_t)0), (int64_t)256);
+                const uint32_t span = (uint32_t)max(hi - lo, 0);
+                const int first_place = 4 * lane - lo;
+                uint32_t lu[4], vv[4];   // vv: the column, or the lane's stand-in past all vertices for an entry that counts for nothing
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const int row = (int)max(before, upto[t]) - 1;   // -1 only before the block's first entry
-                    lu[t] = (uint32_t)aus[min(max(row, 0), kWindowRows - 1)];
-                    const int64_t pe = p + t;
-                    const int32_t v = c[t];
-                    ok[t] = pe >= e_begin && pe < e_end && v >= 0 && v < n;
-                    bucket[t] = ok[t] ? (int)(v >> shift) : kBucketsMax + lane;
+                    lu[t] = (uint32_t)aus[max(before, upto[t])];   // row number + 1 <= kWindowRows; 0 only before the block's first entry
+                    const bool ok = (uint32_t)(first_place + t) < span && (uint32_t)c[t] < n_ids;
+                    vv[t] = ok ? (uint32_t)c[t] : scrap_v;
                 }
                 int rank[4];   // all four asked for at once (integer, LDS: the order inside a run is free)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) rank[t] = atomicAdd(&tile_cnt[bucket[t]], 1);
+                for (int t = 0; t < 4; ++t) rank[t] = atomicAdd(&tile_cnt[vv[t] >> shift], 1);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    rec[4 * st + t] = ((uint32_t)c[t] & ((1u << shift) - 1u)) | (lu[t] << shift);
-                    where[4 * st + t] = ok[t] ? ((uint32_t)bucket[t] | ((uint32_t)rank[t] << 9)) : 0xffffffffu;
+                    rec[4 * st + t] = (vv[t] & ((1u << shift) - 1u)) | (lu[t] << shift);
+                    where[4 * st + t] = (vv[t] >> shift) | ((uint32_t)rank[t] << 10);
                 }
                 p0 += 256;
             }
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         // ---- phase C ----
 #pragma unroll
         for (int i = 0; i < kTileSteps * 4; ++i)
-            if (where[i] != 0xffffffffu) sorted[run_start[where[i] & 511u] + (int)(where[i] >> 9)] = rec[i];
+            if ((where[i] & 1023u) < (uint32_t)kBucketsMax) sorted[run_start[where[i] & 1023u] + (int)(where[i] >> 10)] = rec[i];
         {   // (straight-line code: the one wait for the answer sits on every path, and the write-out below, whose
             // stores must stay in flight from turn to turn, is not made to wait for it again)
             const bool fits = (int64_t)pos + my_out <= my_limit;   // never write past a bucket
