@@ -126,7 +126,10 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     static_assert(kBucketsMax + 64 <= kScatterBlock, "one thread per bucket in the scan of a tile");
     __shared__ int32_t tile_cnt[kBucketsMax + 64];   // entries of the tile per bucket (+ one word per lane for entries
                                                      // that count for nothing: their rank is asked for all the same)
-    __shared__ int32_t run_start[kBucketsMax + 1];   // start of every bucket's run in `sorted`
+    __shared__ int32_t run_start[1024];              // start of every bucket's run in `sorted` (any 10-bit bucket number may
+                                                     // be looked up; only those below nb hold something)
+    __shared__ i32x4 run_meta[kBucketsMax];          // per bucket: run start, run length, records that leave with this
+                                                     // tile, records that waited
     __shared__ int64_t run_dest[kBucketsMax];        // its place in the record buffer (-1: no room)
     __shared__ __attribute__((aligned(16))) int32_t mark_lds[kScatterWaves][256];   // per step: row number + 1 at a row's first entry
     __shared__ int32_t au_lds[kScatterWaves][kWindowRows + 1];   // [0]: for places before the block's first entry
@@ -137,9 +140,8 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     // partial block costs the memory a read-modify-write).
     extern __shared__ __attribute__((aligned(16))) uint32_t scatter_lds[];
     uint32_t *sorted = scatter_lds;           // kTile records, sorted by bucket
-    uint32_t *resid = scatter_lds + kTile;    // nb * (kAlign - 1) records
+    uint32_t *resid = scatter_lds + kTile + 64;   // nb * (kAlign - 1) records (between the two: one spare word per lane)
     __shared__ int32_t resid_cnt[kBucketsMax];
-    __shared__ int32_t run_out[kBucketsMax];         // records of (waiting + run) that leave with this tile
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int32_t *mk = mark_lds[wave];
@@ -305,14 +307,10 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         int my_out = 0;
         {
             const int cnt = t < nb ? tile_cnt[t] : 0;
-            int incl = cnt;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off, 64);
-                if (lane >= off) incl += up;
-            }
+            const int incl = wave_inclusive_add(cnt);
             if (lane == 63) wave_total[wave] = incl;
-            my_out = t < nb ? ((resid_cnt[t] + cnt) & ~(kAlign - 1)) : 0;   // whole blocks of waiting + new records
+            const int waited = t < nb ? resid_cnt[t] : 0;
+            my_out = (waited + cnt) & ~(kAlign - 1);   // whole blocks of waiting + new records
             if (my_out > 0) pos = atomicAdd(&cursor[t * kCursorStride], (unsigned long long)my_out);
             __syncthreads();
             // every thread has read its counter and the flag: both start the next tile at zero (the barrier below
@@ -323,15 +321,22 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
             for (int w = 0; w < wave; ++w) before += wave_total[w];
             if (t < nb) {
                 run_start[t] = before + incl - cnt;
-                run_out[t] = my_out;
+                run_meta[t] = i32x4{before + incl - cnt, cnt, my_out, waited};
             }
-            if (t == kScatterBlock - 1) run_start[nb] = before + incl;   // nb <= kScatterBlock: the total
         }
         __syncthreads();
         // ---- phase C ----
+        {   // all look-ups of a thread's 16 records at once, then all writes; a record that counts for nothing goes to
+            // the lane's spare word
+            uint32_t at[kTileSteps * 4];
 #pragma unroll
-        for (int i = 0; i < kTileSteps * 4; ++i)
-            if ((where[i] & 1023u) < (uint32_t)kBucketsMax) sorted[run_start[where[i] & 1023u] + (int)(where[i] >> 10)] = rec[i];
+            for (int i = 0; i < kTileSteps * 4; ++i) at[i] = (uint32_t)run_start[where[i] & 1023u];
+#pragma unroll
+            for (int i = 0; i < kTileSteps * 4; ++i) {
+                const bool counts = (where[i] & 1023u) < (uint32_t)kBucketsMax;
+                sorted[counts ? at[i] + (where[i] >> 10) : (uint32_t)(kTile + lane)] = rec[i];
+            }
+        }
         {   // (straight-line code: the one wait for the answer sits on every path, and the write-out below, whose
             // stores must stay in flight from turn to turn, is not made to wait for it again)
             const bool fits = (int64_t)pos + my_out <= my_limit;   // never write past a bucket
@@ -344,23 +349,24 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         for (int b0 = 4 * wave; b0 < nb; b0 += 4 * kScatterWaves) {
             const int b = b0 + (lane >> 4), li = lane & 15;
             const bool valid = b < nb;
+            const int bc = min(b, nb - 1);
             // the bucket's stream = the records that waited, then this tile's run; `out` of them leave
-            const int first = valid ? run_start[b] : 0, cnt = valid ? run_start[b + 1] - first : 0;
-            const int waiting = valid ? resid_cnt[b] : 0, out = valid ? run_out[b] : 0;
-            const int64_t dest = valid ? run_dest[b] : -1;
-            uint32_t *wait_b = resid + (valid ? b : 0) * (kAlign - 1);
-            if (dest >= 0)
-                for (int i = li; i < out; i += 16) records[dest + i] = i < waiting ? wait_b[i] : sorted[first + i - waiting];
+            const i32x4 meta = run_meta[bc];
+            const int64_t dest = run_dest[bc];
+            const int first = meta[0], cnt = meta[1], out = meta[2], waiting = meta[3];
+            uint32_t *wait_b = resid + bc * (kAlign - 1);
+            const int leaving = valid && dest >= 0 ? out : 0;   // a multiple of kAlign
+            // (fewer than kAlign records wait, so only a lane's first record can be one of them)
+            if (li < leaving) records[dest + li] = li < waiting ? wait_b[li] : sorted[first + li - waiting];
+            for (int i = li + kAlign; i < leaving; i += kAlign) records[dest + i] = sorted[first + i - waiting];
+            // What stays: with nothing gone the run joins the waiting records, else (out >= kAlign > waiting) the
+            // tail of the run waits.
             const int keep = waiting + cnt - out;   // < kAlign
+            const int moved = out == 0 ? cnt : keep;
+            const int from = first + li + (out == 0 ? 0 : out - waiting), to = li + (out == 0 ? waiting : 0);
             wave_fence();
-            if (valid) {
-                if (out == 0) {                          // nothing left: the run joins the waiting records
-                    if (li < cnt) wait_b[waiting + li] = sorted[first + li];
-                } else if (li < keep) {                  // out >= kAlign > waiting: the tail of the run waits
-                    wait_b[li] = sorted[first + out - waiting + li];
-                }
-                if (li == 0) resid_cnt[b] = keep;
-            }
+            if (valid && li < moved) wait_b[to] = sorted[from];
+            if (valid && li == 0) resid_cnt[b] = keep;
         }
         // No barrier here: a wave that is done writing goes on to gather its part of the next tile.  What the next
         // tile shares with this write-out is touched only behind its first barrier (`sorted` and the run tables
@@ -505,9 +511,9 @@ int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void
     bucket_scan_kernel<<<1, 64, 0, s>>>(pl.nb, (int)sgrid, hist, w.bucket_base, cursor, w.bucket_items);
     EP_LAUNCH_CHECK();
     {
-        // the tile (64 KB) and the waiting records (<= 30 KB) in dynamic LDS
-        const int scatter_bytes = (kTile + pl.nb * (kAlign - 1)) * 4;
-        constexpr int kScatterLdsMax = (kTile + kBucketsMax * (kAlign - 1)) * 4;
+        // the tile (64 KB), a spare word per lane and the waiting records (<= 30 KB) in dynamic LDS
+        const int scatter_bytes = (kTile + 64 + pl.nb * (kAlign - 1)) * 4;
+        constexpr int kScatterLdsMax = (kTile + 64 + kBucketsMax * (kAlign - 1)) * 4;
         if (i64) {
             int rc = set_big_lds(reinterpret_cast<const void *>(bucket_scatter_kernel<int64_t>), g_scatter_lds64, kScatterLdsMax);
             if (rc != EP_OK) return rc;
