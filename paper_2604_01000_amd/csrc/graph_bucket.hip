@@ -113,6 +113,7 @@ constexpr int kScatterWaves = kScatterBlock / 64;
 constexpr int kWindowRows = 128;   // rows per window of a wave: two per lane (a new window costs two memory latencies)
 constexpr int kTileSteps = 4;
 constexpr int kTile = kScatterWaves * kTileSteps * 256;
+constexpr int kSpareWords = 320;   // > kScatterWaves * kTileSteps * 4: where records that count for nothing are put
 
 template <typename RowT>
 __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n, int64_t nnz, int shift, int nb,
@@ -123,6 +124,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
                                                                         unsigned long long *__restrict__ cursor,
                                                                         uint32_t *__restrict__ records,
                                                                         unsigned long long *__restrict__ dropped) {
+    static_assert(kScatterWaves == 16, "a wave's offset in the tile is summed over one row of 16 lanes");
     static_assert(kBucketsMax + 64 <= kScatterBlock, "one thread per bucket in the scan of a tile");
     __shared__ int32_t tile_cnt[kBucketsMax + 64];   // entries of the tile per bucket (+ one word per lane for entries
                                                      // that count for nothing: their rank is asked for all the same)
@@ -140,12 +142,13 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     // partial block costs the memory a read-modify-write).
     extern __shared__ __attribute__((aligned(16))) uint32_t scatter_lds[];
     uint32_t *sorted = scatter_lds;           // kTile records, sorted by bucket
-    uint32_t *resid = scatter_lds + kTile + 64;   // nb * (kAlign - 1) records (between the two: one spare word per lane)
+    uint32_t *resid = scatter_lds + kTile + kSpareWords;   // nb * (kAlign - 1) records (between the two: the spare words)
     __shared__ int32_t resid_cnt[kBucketsMax];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int32_t *mk = mark_lds[wave];
     int32_t *aus = au_lds[wave];
+    const int lane_before4 = ((lane + 63) & 63) << 2;   // byte address of lane - 1 for the lane exchange (lane 0: unused)
     const uint32_t n_ids = (uint32_t)min(n, (int64_t)1 << 31);          // a column c is a vertex iff (uint32_t)c < n_ids
     const uint32_t scrap_v = (uint32_t)(kBucketsMax + lane) << shift;   // "vertex" of the lane's own spare counter
     static_assert(kBucketsMax + 64 <= 1024, "bucket numbers, the spare ones included, take 10 bits of `where`");
@@ -154,6 +157,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
     for (int b = threadIdx.x; b < kBucketsMax + 64; b += kScatterBlock) {
         tile_cnt[b] = 0;
         if (b < kBucketsMax) resid_cnt[b] = 0;
+        else run_start[b] = kTile;   // the spare buckets: never written again (phase B writes below nb <= kBucketsMax)
     }
     if (threadIdx.x == 0) any_work = 0;
     __syncthreads();
@@ -238,14 +242,14 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 
     for (;;) {
         // ---- phase A ----
-        uint32_t rec[kTileSteps * 4], where[kTileSteps * 4];   // where = bucket | rank << 10; bucket >= kBucketsMax: no entry
+        uint32_t rec[kTileSteps * 4], where[kTileSteps * 4];   // where = 4 bucket | rank << 12; bucket >= kBucketsMax: no entry
         bool worked = false;
 #pragma unroll
         for (int st = 0; st < kTileSteps; ++st) {
             bool have = p0 < e_end;
             if (!have) have = next_block();
 #pragma unroll
-            for (int t = 0; t < 4; ++t) where[4 * st + t] = 0xffffffffu;
+            for (int t = 0; t < 4; ++t) where[4 * st + t] = (uint32_t)kBucketsMax << 2;   // a spare bucket, rank 0
             if (have) {   // uniform over the wave
                 worked = true;
                 const i32x4 c = ahead;
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 #pragma unroll
                 for (int t = 1; t < 4; ++t) upto[t] = max(upto[t - 1], (uint32_t)m[t]);
                 const uint32_t incl = wave_inclusive_max(upto[3]);
-                uint32_t before = (uint32_t)__shfl_up((int)incl, 1, 64);   // the lanes before this one
+                uint32_t before = (uint32_t)__builtin_amdgcn_ds_bpermute(lane_before4, (int)incl);   // the lanes before this one
                 before = max(lane == 0 ? 0u : before, carry);
                 carry = max(carry, (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
                 // Which of the lane's places 4 lane + t hold entries of the block: lo <= place < hi, wave-uniform.
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     rec[4 * st + t] = (vv[t] & ((1u << shift) - 1u)) | (lu[t] << shift);
-                    where[4 * st + t] = (vv[t] >> shift) | ((uint32_t)rank[t] << 10);
+                    where[4 * st + t] = ((vv[t] >> shift) << 2) | ((uint32_t)rank[t] << 12);
                 }
                 p0 += 256;
             }
@@ -317,8 +321,11 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
             // orders this before any wave's next phase A)
             if (t < kBucketsMax + 64) tile_cnt[t] = 0;
             if (t == 0) any_work = 0;
-            int before = 0;
-            for (int w = 0; w < wave; ++w) before += wave_total[w];
+            int before = (lane & 15) < wave ? wave_total[lane & 15] : 0;   // summed over the 16 lanes of a row
+            before += __builtin_amdgcn_update_dpp(0, before, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+            before += __builtin_amdgcn_update_dpp(0, before, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+            before += __builtin_amdgcn_update_dpp(0, before, 0x141, 0xF, 0xF, true);   // row_half_mirror
+            before += __builtin_amdgcn_update_dpp(0, before, 0x140, 0xF, 0xF, true);   // row_mirror
             if (t < nb) {
                 run_start[t] = before + incl - cnt;
                 run_meta[t] = i32x4{before + incl - cnt, cnt, my_out, waited};
@@ -326,16 +333,15 @@ __global__ __launch_bounds__(kScatterBlock) void bucket_scatter_kernel(int64_t n
         }
         __syncthreads();
         // ---- phase C ----
-        {   // all look-ups of a thread's 16 records at once, then all writes; a record that counts for nothing goes to
-            // the lane's spare word
+        {   // All look-ups of a thread's 16 records at once, then all writes.  A record that counts for nothing was
+            // ranked on a spare counter (at most kTileSteps * 4 per thread and tile, one counter per lane number): the
+            // spare buckets' runs all start at the spare words behind the tile, kScatterWaves * kTileSteps * 4 + 1 of them.
             uint32_t at[kTileSteps * 4];
 #pragma unroll
-            for (int i = 0; i < kTileSteps * 4; ++i) at[i] = (uint32_t)run_start[where[i] & 1023u];
+            for (int i = 0; i < kTileSteps * 4; ++i)
+                at[i] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(run_start) + (where[i] & 0xFFCu));
 #pragma unroll
-            for (int i = 0; i < kTileSteps * 4; ++i) {
-                const bool counts = (where[i] & 1023u) < (uint32_t)kBucketsMax;
-                sorted[counts ? at[i] + (where[i] >> 10) : (uint32_t)(kTile + lane)] = rec[i];
-            }
+            for (int i = 0; i < kTileSteps * 4; ++i) sorted[at[i] + (where[i] >> 12)] = rec[i];
         }
         {   // (straight-line code: the one wait for the answer sits on every path, and the write-out below, whose
             // stores must stay in flight from turn to turn, is not made to wait for it again)
@@ -511,9 +517,9 @@ int launch_cut_bucketed(int64_t n, int64_t nnz, const BucketPlan &pl, const void
     bucket_scan_kernel<<<1, 64, 0, s>>>(pl.nb, (int)sgrid, hist, w.bucket_base, cursor, w.bucket_items);
     EP_LAUNCH_CHECK();
     {
-        // the tile (64 KB), a spare word per lane and the waiting records (<= 30 KB) in dynamic LDS
-        const int scatter_bytes = (kTile + 64 + pl.nb * (kAlign - 1)) * 4;
-        constexpr int kScatterLdsMax = (kTile + 64 + kBucketsMax * (kAlign - 1)) * 4;
+        // the tile (64 KB), the spare words and the waiting records (<= 30 KB) in dynamic LDS
+        const int scatter_bytes = (kTile + kSpareWords + pl.nb * (kAlign - 1)) * 4;
+        constexpr int kScatterLdsMax = (kTile + kSpareWords + kBucketsMax * (kAlign - 1)) * 4;
         if (i64) {
             int rc = set_big_lds(reinterpret_cast<const void *>(bucket_scatter_kernel<int64_t>), g_scatter_lds64, kScatterLdsMax);
             if (rc != EP_OK) return rc;
