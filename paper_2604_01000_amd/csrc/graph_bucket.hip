@@ -39,6 +39,7 @@ constexpr int kSliceShift = 17;            // label piece held in LDS: 2^17 byte
 constexpr int kSweepBlock = 1024;
 constexpr int kSweepPerThread = 96;
 constexpr int kChunk = kSweepBlock * kSweepPerThread;   // records per work item of the last pass
+static_assert(kSweepPerThread % 4 == 0, "a thread takes its records four at a time");
 constexpr int kSweepGrid = 1024;
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -419,11 +420,26 @@ __global__ __launch_bounds__(kSweepBlock) void bucket_sweep_kernel(int64_t n, in
             if (b + step < nb && prefix_lds[b + step] <= w) b += step;
         const int64_t first = base[b] + (w - prefix_lds[b]) * kChunk;
         const int64_t end = min((int64_t)cursor[b * kCursorStride], base[b + 1]);   // what the scatter pass wrote
+        // The item's records, 16 bytes per lane and load, all loads of a thread in flight at once, through a buffer
+        // descriptor that ends at the bucket's last record: what lies past it reads as zero and is replaced below
+        // (only the last item of a bucket has such places) by a record that counts for nothing.
         uint32_t rec[kSweepPerThread];
+        const int have = (int)min(max(end - first, (int64_t)0), (int64_t)kChunk);
 #pragma unroll
-        for (int q = 0; q < kSweepPerThread; ++q) {
-            const int64_t at = first + (int64_t)q * kSweepBlock + threadIdx.x;
-            rec[q] = at < end ? records[at] : (255u << shift);   // pid(u) = 255: counts for nothing
+        for (int q = 0; q < kSweepPerThread / 4; ++q) {   // (a descriptor per load: scalar work, and one offset register for all)
+            const int here = min(max(have - q * 4 * kSweepBlock, 0), 4 * kSweepBlock);   // records of this load's 16 KB
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint32_t *>(records + (here ? first + (int64_t)q * 4 * kSweepBlock : 0)), 0, here * 4, 0x00020000);
+            const u32x4 four = __builtin_amdgcn_raw_buffer_load_b128(rsrc, 16 * (int)threadIdx.x, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rec[4 * q + j] = four[j];
+        }
+        if (have < kChunk) {   // uniform over the workgroup
+#pragma unroll
+            for (int q = 0; q < kSweepPerThread; ++q) {
+                const int at = 4 * ((int)threadIdx.x + (q / 4) * kSweepBlock) + (q % 4);
+                rec[q] = at < have ? rec[q] : (255u << shift);   // pid(u) = 255
+            }
         }
         const int64_t v0 = (int64_t)b << shift;
         for (int piece = 0; piece < pieces; ++piece) {
