@@ -10,10 +10,10 @@
 // entries are first bucketed by the vertex range of v, so that the labels a bucket needs are 256 KB (L2)
 // and, in two pieces, 128 KB (LDS):
 //   bucket_hist_kernel     entries per bucket (one streaming read of colidx)
-//   bucket_scan_kernel     bucket offsets (each bucket starts on a 128-byte line), work items of the last pass
-//   bucket_scatter_kernel  streams colidx with its rows' labels (128-row windows, otherwise as in the plain sweep) and
+//   bucket_scan_kernel     bucket offsets (each bucket starts on a 64-byte block), work items of the last pass
+//   bucket_scatter_kernel  streams colidx with its rows' labels (blocks of 128 rows per wave) and
 //                          writes one 32-bit record per entry, (v - bucket start) | pid(u) << shift, to
-//                          the entry's bucket: a workgroup sorts a tile of 8,192 entries by bucket in LDS and
+//                          the entry's bucket: a workgroup sorts a tile of 16,384 entries by bucket in LDS and
 //                          every bucket's run leaves as a contiguous stream of whole 64-byte blocks, its place
 //                          reserved with one integer atomic per bucket and tile
 //   bucket_sweep_kernel    a workgroup takes 96 K records of one bucket into registers, walks the bucket's
@@ -111,7 +111,7 @@ __global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long
 //   phase C  the records go to their sorted place in LDS, then every run leaves as one contiguous stream
 constexpr int kScatterBlock = 1024;
 constexpr int kScatterWaves = kScatterBlock / 64;
-constexpr int kWindowRows = 128;   // rows per window of a wave: two per lane (a new window costs two memory latencies)
+constexpr int kWindowRows = 128;   // rows per block of a wave: two per lane (a new block costs two memory latencies)
 constexpr int kTileSteps = 4;
 constexpr int kTile = kScatterWaves * kTileSteps * 256;
 constexpr int kSpareWords = 320;   // > kScatterWaves * kTileSteps * 4: where records that count for nothing are put
