@@ -82,22 +82,50 @@ __global__ __launch_bounds__(kBlock) void bucket_hist_kernel(int64_t n, int64_t 
 
 // base[b] = start of bucket b in the record buffer, cursor[b] = base[b], item_prefix[b] = number of
 // kChunk-record work items before bucket b.  A bucket has room for its entries rounded up to whole blocks plus
-// one block per workgroup of the scatter pass (the padded last flush of each).  One thread: nb <= kBucketsMax.
-__global__ void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long long *__restrict__ hist,
-                                   int64_t *__restrict__ base, unsigned long long *__restrict__ cursor,
-                                   int64_t *__restrict__ item_prefix) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int64_t at = 0, items = 0;
-    for (int b = 0; b < nb; ++b) {
-        base[b] = at;
-        cursor[b * kCursorStride] = (unsigned long long)at;
-        item_prefix[b] = items;
-        const int64_t room = ((int64_t)hist[b] + kAlign - 1) / kAlign * kAlign + (int64_t)kAlign * scatter_grid;
-        at += room;
-        items += (room + kChunk - 1) / kChunk;
+// one block per workgroup of the scatter pass (the padded last flush of each).  One wave: lane l takes buckets
+// kPerLaneBuckets l .. + kPerLaneBuckets - 1, the lanes' totals are scanned across the wave (one thread walking all
+// buckets took 66 us of dependent memory round trips).
+constexpr int kPerLaneBuckets = kBucketsMax / 64;
+static_assert(kPerLaneBuckets * 64 == kBucketsMax, "the buckets divide over the lanes of one wave");
+__global__ __launch_bounds__(64) void bucket_scan_kernel(int nb, int scatter_grid, const unsigned long long *__restrict__ hist,
+                                                         int64_t *__restrict__ base, unsigned long long *__restrict__ cursor,
+                                                         int64_t *__restrict__ item_prefix) {
+    if (blockIdx.x != 0) return;
+    const int lane = threadIdx.x, b0 = lane * kPerLaneBuckets;
+    int64_t room[kPerLaneBuckets], mine_room = 0, mine_items = 0;
+#pragma unroll
+    for (int i = 0; i < kPerLaneBuckets; ++i) {
+        const int b = b0 + i;
+        const int64_t entries = b < nb ? (int64_t)hist[b] : 0;
+        room[i] = b < nb ? (entries + kAlign - 1) / kAlign * kAlign + (int64_t)kAlign * scatter_grid : 0;
+        mine_room += room[i];
+        mine_items += (room[i] + kChunk - 1) / kChunk;
     }
-    base[nb] = at;
-    item_prefix[nb] = items;
+    int64_t at = mine_room, items = mine_items;   // inclusive over the lanes, then made exclusive
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t up_room = __shfl_up(at, off, 64), up_items = __shfl_up(items, off, 64);
+        if (lane >= off) {
+            at += up_room;
+            items += up_items;
+        }
+    }
+    at -= mine_room;
+    items -= mine_items;
+#pragma unroll
+    for (int i = 0; i < kPerLaneBuckets; ++i) {
+        const int b = b0 + i;
+        if (b <= nb) {   // b == nb: the totals
+            base[b] = at;
+            item_prefix[b] = items;
+        }
+        if (b < nb) cursor[b * kCursorStride] = (unsigned long long)at;
+        at += room[i];
+        items += (room[i] + kChunk - 1) / kChunk;
+    }
+    if (lane == 63 && nb == kBucketsMax) {   // the totals when every lane's buckets are real ones
+        base[nb] = at;
+        item_prefix[nb] = items;
+    }
 }
 
 // A workgroup gathers a tile of up to kTile entries, sorts it by bucket in LDS and writes every bucket's run
