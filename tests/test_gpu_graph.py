@@ -95,7 +95,7 @@ def test_out_of_range_labels_are_skipped_not_read_out_of_bounds():
 def test_cut_count_through_buckets_on_a_graph_beyond_the_caches(rowptr_i64):
     """6.4 M vertices: the cut count goes through buckets of column ranges (two buckets of 2^20 vertices and more,
     a ragged last one).  Hubs, empty rows, labels outside [0, k) and every k the byte labels allow, bit-exact
-    against the oracle; then a graph whose columns all fall into one bucket."""
+    against the oracle; then a graph whose columns all fall into one bucket, and one with column indices out of range."""
     from paper_2604_01000_amd import embedpart as ep
     n = 6_400_123
     w = synth.WORKLOADS["papers_like"].scaled(n)
@@ -138,3 +138,16 @@ def test_cut_count_through_buckets_on_a_graph_beyond_the_caches(rowptr_i64):
     gr2 = Graph(torch.from_numpy(gr.rp_np).to(torch.int64 if rowptr_i64 else torch.int32), torch.from_numpy(ci2))
     lab = _labels(n, 9, 8)
     assert gr2.quality(lab.to(DEV), 9)[0] == oracle.partition_quality(gr2.rp_np, ci2, lab.numpy(), 9)[0]
+    # column indices outside [0, n) are skipped by every pass of the bucketed path (the header's contract); the
+    # expected count is the definition over the remaining entries
+    ci3 = gr.ci_np.copy()
+    pick = rng.choice(len(ci3), size=4_000, replace=False)
+    ci3[pick[:1_500]] = -7
+    ci3[pick[1_500:3_000]] = n + 11
+    ci3[pick[3_000:]] = np.iinfo(np.int32).max
+    del gr2
+    gr3 = Graph(torch.from_numpy(gr.rp_np).to(torch.int64 if rowptr_i64 else torch.int32), torch.from_numpy(ci3))
+    lab = _labels(n, 64, 10)
+    inside = (ci3 >= 0) & (ci3 < n)
+    l = lab.numpy()
+    assert gr3.quality(lab.to(DEV), 64)[0] == int(np.count_nonzero(inside & (l[src] != l[np.where(inside, ci3, 0)])))
