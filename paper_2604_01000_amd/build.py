@@ -24,7 +24,7 @@ FLAGS = [
 # instruction issue; this scheduling strategy leaves fewer idle and wait instructions in them (the order the
 # kernel pins with scheduling barriers stays).
 FILE_FLAGS = {
-    "kmeans_small.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
+    "kmeans_small.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp", "-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 
